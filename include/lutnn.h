@@ -1,0 +1,163 @@
+/*
+ * liblutnn — LUT-NN table-lookup linear operator for AMD MI355X (gfx950).
+ *
+ * C ABI of the inference hot path of LUT-NN (arXiv 2302.03213): a linear operator
+ * Y = A x B (an FC layer or an im2col'd convolution, Sec. 4) evaluated by
+ *   1. encoding: every row of A is split into C sub-vectors of length V (Sec. 2.1) and
+ *      each sub-vector is replaced by the index of its nearest of K centroids (Eq. 2);
+ *   2. lookup + aggregation: Y[n][m] = sum_c T[c][idx[n][c]][m] (Eq. 4), where the table
+ *      T[c][k][m] = P[c][k] . B[cV:(c+1)V][m] is precomputed (Eq. 3) and optionally
+ *      quantised to INT8 with one symmetric scale (Sec. 3.3).
+ *
+ * Conventions common to every call
+ *   - Pointers are DEVICE pointers unless a parameter is marked "host".  The caller owns
+ *     every buffer; the library allocates nothing and keeps no reference after the
+ *     call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work on that stream; they never synchronise.
+ *   - Matrices are row-major with a row stride in ELEMENTS (ldx, ldy, ldw).
+ *   - Every call validates its arguments on the host before launching anything and
+ *     returns a lutnn_status; on failure nothing has been enqueued and
+ *     lutnn_last_error() describes the reason.  No exception crosses this boundary.
+ *   - N == 0 is valid and enqueues nothing.
+ *   - Inputs are assumed finite.  Non-finite activations never cause an out-of-range
+ *     index or an out-of-bounds access; the index chosen for them is unspecified.
+ *   - Outputs must not alias inputs.
+ */
+#ifndef LUTNN_H
+#define LUTNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LUTNN_API __attribute__((visibility("default")))
+
+typedef enum {
+    LUTNN_OK = 0,
+    LUTNN_E_NULL = 1,        /* a required pointer is NULL                                   */
+    LUTNN_E_SHAPE = 2,       /* a dimension is non-positive, K > 256, or a stride is too small */
+    LUTNN_E_UNSUPPORTED = 3, /* no kernel for this (dtype, variant, K) combination           */
+    LUTNN_E_ALIGN = 4,       /* a pointer is not aligned as documented                       */
+    LUTNN_E_HIP = 5          /* the HIP runtime reported an error on launch                  */
+} lutnn_status;
+
+typedef enum {
+    LUTNN_TABLE_F32 = 0, /* T[C][K][M] fp32                                   */
+    LUTNN_TABLE_I8 = 1   /* T[C][K][M] int8 + one fp32 scale (Sec. 3.3, n = 8) */
+} lutnn_table_dtype;
+
+typedef enum {
+    LUTNN_VARIANT_AUTO = 0,  /* the library picks                                                  */
+    LUTNN_VARIANT_LDS = 1,   /* table tiles staged in LDS, gathered by index, register accumulate   */
+    LUTNN_VARIANT_MFMA = 2,  /* Eq. 4 as a dense onehot[N x CK] x T[CK x M] int8 MFMA contraction   */
+    LUTNN_VARIANT_FUSED = 3  /* lutnn_linear only: one kernel, indices never leave the chip          */
+} lutnn_variant;
+
+/*
+ * One LUT layer.  Plain data filled by the caller (host struct holding device pointers);
+ * the library only reads it during the call.
+ */
+typedef struct {
+    int32_t C;               /* number of codebooks (sub-vectors per row), D = C * V           */
+    int32_t K;               /* centroids per codebook, 1..256                                  */
+    int32_t V;               /* sub-vector length                                              */
+    int32_t M;               /* output width                                                   */
+    int32_t table_dtype;     /* lutnn_table_dtype                                              */
+    int32_t reserved;        /* must be 0                                                      */
+    const float* centroids;  /* P[C][K][V] fp32 (needed by encode / linear)                    */
+    const void* table;       /* T[C][K][M], m fastest, int8 or fp32 (needed by the LDS variant) */
+    const void* table_packed;/* INT8 only: MFMA operand layout written by lutnn_build_table,
+                                lutnn_packed_bytes() bytes, 16-byte aligned; NULL if absent    */
+    const float* scale;      /* INT8 only: device pointer to the layer's single fp32 scale      */
+    const float* bias;       /* [M] fp32 or NULL                                               */
+} lutnn_layer;
+
+/* Size in bytes of T[C][K][M] for `dtype`.  Host; returns 0 on invalid arguments. */
+LUTNN_API size_t lutnn_table_bytes(int32_t C, int32_t K, int32_t M, int32_t dtype);
+
+/*
+ * Size in bytes of the MFMA operand copy of an INT8 table (padded; see lutnn_build_table).
+ * Host; returns 0 for fp32 tables or invalid arguments.
+ */
+LUTNN_API size_t lutnn_packed_bytes(int32_t C, int32_t K, int32_t M, int32_t dtype);
+
+/*
+ * Offline table construction (Eq. 3) and, for INT8, symmetric scalar quantisation
+ * (Sec. 3.3).  Not part of the timed path.
+ *
+ *   centroids  P[C][K][V] fp32
+ *   W          B[D][M] fp32 row-major (Table 1), row stride ldw >= M, D = C*V
+ *   table_out  T[C][K][M]: fp32 entries  T = sum_v P[c][k][v] * W[cV+v][m]  (fp32, v
+ *              ascending, fused multiply-add), or for INT8
+ *              q = clamp(round_half_even(T / s), -127, 127) with
+ *              s = max|T| / 127 over the whole layer (s = 1 when the table is all zero)
+ *   packed_out INT8 only, nullable: the same q re-laid out for the MFMA variant:
+ *              [C * ceil(K/16)][Mp][16] int8 with Mp = M rounded up to 256, k fastest,
+ *              zero padded.  Must be 16-byte aligned.
+ *   scale_out  INT8 only: receives s (one fp32).  Also used as scratch during the call.
+ *
+ * Errors: E_NULL, E_SHAPE, E_UNSUPPORTED (unknown dtype), E_ALIGN, E_HIP.
+ */
+LUTNN_API lutnn_status lutnn_build_table(const float* centroids, const float* W, int64_t ldw,
+                                         int32_t C, int32_t K, int32_t V, int32_t M,
+                                         int32_t dtype, void* table_out, void* packed_out,
+                                         float* scale_out, void* stream);
+
+/*
+ * Encoding (Eq. 2; "closest centroid search", Sec. 5.1):
+ *   idx[n][c] = argmin_k sum_v (X[n][cV+v] - P[c][k][v])^2
+ * evaluated in fp32 in exactly this form (v ascending, one fused multiply-add per term);
+ * the lowest k wins ties.
+ *
+ *   X    [N][D] fp32, row stride ldx >= D = C*V
+ *   idx  [N][C] uint8, dense
+ * Uses layer->centroids, C, K, V.  Errors: E_NULL, E_SHAPE, E_HIP.
+ */
+LUTNN_API lutnn_status lutnn_encode(const lutnn_layer* layer, const float* X, int64_t N,
+                                    int64_t ldx, uint8_t* idx, void* stream);
+
+/*
+ * Lookup + aggregation (Eq. 4; "table read and accumulation", Sec. 5.2):
+ *   INT8 table:  acc = sum_c (int32) q[c][idx[n][c]][m]  (exact),
+ *                Y[n][m] = fma((float)acc, s, bias[m])   (or (float)acc * s without bias)
+ *   fp32 table:  Y[n][m] = sum_c T[c][idx[n][c]][m] (+ bias[m]), fp32 accumulation
+ *
+ *   idx  [N][C] uint8, dense; every value must be < K (larger values never cause an
+ *        out-of-bounds access but give an unspecified result)
+ *   Y    [N][M] fp32, row stride ldy >= M
+ *   variant  AUTO, LDS (needs layer->table) or MFMA (INT8 only, needs layer->table_packed).
+ * Errors: E_NULL, E_SHAPE, E_UNSUPPORTED, E_ALIGN, E_HIP.
+ */
+LUTNN_API lutnn_status lutnn_lookup(const lutnn_layer* layer, const uint8_t* idx, int64_t N,
+                                    float* Y, int64_t ldy, int32_t variant, void* stream);
+
+/*
+ * The whole operator: encode then lookup, Y ~= X . B (+ bias).
+ *
+ *   variant FUSED  one kernel; the indices stay in LDS.  `idx_workspace` is ignored.
+ *   variant LDS / MFMA  lutnn_encode into idx_workspace, then lutnn_lookup with that variant.
+ *   variant AUTO   picks per shape; may need the workspace.
+ *   idx_workspace  [N][C] uint8 device scratch; may be NULL only for FUSED.
+ * Errors: as lutnn_encode and lutnn_lookup.
+ */
+LUTNN_API lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, int64_t N,
+                                    int64_t ldx, float* Y, int64_t ldy, int32_t variant,
+                                    uint8_t* idx_workspace, void* stream);
+
+/* Host: static name of a status code. */
+LUTNN_API const char* lutnn_status_string(int32_t status);
+
+/* Host: description of the calling thread's most recent failure ("" if none). */
+LUTNN_API const char* lutnn_last_error(void);
+
+/* Host: library version, "major.minor.patch". */
+LUTNN_API const char* lutnn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LUTNN_H */

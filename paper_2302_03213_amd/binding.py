@@ -1,0 +1,181 @@
+"""Thin ctypes binding of liblutnn.so (C ABI in include/lutnn.h).
+
+Argument marshalling only: every step of the operator runs in the HIP kernels.  PyTorch is used
+for device memory and streams.  There is no CPU fallback: if the shared library cannot be loaded
+the import of this module fails.
+
+Names and notation follow arXiv 2302.03213: N rows, D = C*V inputs, K centroids per codebook,
+M outputs; codebooks P[C][K][V], weights W[D][M] (Table 1), table T[C][K][M] (Eq. 3).
+"""
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+TABLE_F32 = 0
+TABLE_I8 = 1
+
+VARIANT_AUTO = 0
+VARIANT_LDS = 1
+VARIANT_MFMA = 2
+VARIANT_FUSED = 3
+
+VARIANTS = {"auto": VARIANT_AUTO, "lds": VARIANT_LDS, "mfma": VARIANT_MFMA, "fused": VARIANT_FUSED}
+
+EXPORTS = ["lutnn_table_bytes", "lutnn_packed_bytes", "lutnn_build_table", "lutnn_encode",
+           "lutnn_lookup", "lutnn_linear", "lutnn_status_string", "lutnn_last_error",
+           "lutnn_version"]
+
+
+class LutnnError(RuntimeError):
+    def __init__(self, status, name, detail):
+        super().__init__("%s: %s" % (name, detail))
+        self.status = status
+        self.name = name
+
+
+class _CLayer(ctypes.Structure):
+    _fields_ = [("C", ctypes.c_int32), ("K", ctypes.c_int32), ("V", ctypes.c_int32),
+                ("M", ctypes.c_int32), ("table_dtype", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("centroids", ctypes.c_void_p),
+                ("table", ctypes.c_void_p), ("table_packed", ctypes.c_void_p),
+                ("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p)]
+
+
+def _load():
+    path = _build.LIB
+    if not os.path.exists(path):
+        _build.build()  # raises if hipcc is missing or the compile fails
+    lib = ctypes.CDLL(path)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.lutnn_table_bytes.restype = ctypes.c_size_t
+    lib.lutnn_table_bytes.argtypes = [i32, i32, i32, i32]
+    lib.lutnn_packed_bytes.restype = ctypes.c_size_t
+    lib.lutnn_packed_bytes.argtypes = [i32, i32, i32, i32]
+    lib.lutnn_build_table.restype = i32
+    lib.lutnn_build_table.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, vp]
+    lib.lutnn_encode.restype = i32
+    lib.lutnn_encode.argtypes = [ctypes.POINTER(_CLayer), vp, i64, i64, vp, vp]
+    lib.lutnn_lookup.restype = i32
+    lib.lutnn_lookup.argtypes = [ctypes.POINTER(_CLayer), vp, i64, vp, i64, i32, vp]
+    lib.lutnn_linear.restype = i32
+    lib.lutnn_linear.argtypes = [ctypes.POINTER(_CLayer), vp, i64, i64, vp, i64, i32, vp, vp]
+    lib.lutnn_status_string.restype = ctypes.c_char_p
+    lib.lutnn_status_string.argtypes = [i32]
+    lib.lutnn_last_error.restype = ctypes.c_char_p
+    lib.lutnn_version.restype = ctypes.c_char_p
+    return lib
+
+
+LIB = _load()
+
+
+def _check(status):
+    if status != 0:
+        raise LutnnError(status, LIB.lutnn_status_string(status).decode(),
+                         LIB.lutnn_last_error().decode())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _variant(v):
+    return VARIANTS[v] if isinstance(v, str) else int(v)
+
+
+def version():
+    return LIB.lutnn_version().decode()
+
+
+def table_bytes(C, K, M, dtype):
+    return int(LIB.lutnn_table_bytes(C, K, M, dtype))
+
+
+def packed_bytes(C, K, M, dtype):
+    return int(LIB.lutnn_packed_bytes(C, K, M, dtype))
+
+
+class LutLayer:
+    """Device buffers of one LUT layer plus the C descriptor that points at them."""
+
+    def __init__(self, centroids, table, table_dtype, M, packed=None, scale=None, bias=None):
+        C, K, V = centroids.shape
+        self.C, self.K, self.V, self.M = int(C), int(K), int(V), int(M)
+        self.table_dtype = int(table_dtype)
+        self.centroids, self.table, self.packed, self.scale, self.bias = \
+            centroids, table, packed, scale, bias
+        self.c = _CLayer(self.C, self.K, self.V, self.M, self.table_dtype, 0, _ptr(centroids),
+                         _ptr(table), _ptr(packed), _ptr(scale), _ptr(bias))
+
+    @property
+    def D(self):
+        return self.C * self.V
+
+
+def build_table(centroids, W, table_dtype, bias=None, packed=True):
+    """lutnn_build_table: Eq. 3 (+ Sec. 3.3 for INT8).  centroids [C,K,V], W [D,M] on the GPU."""
+    assert centroids.is_cuda and W.is_cuda and centroids.dtype == torch.float32
+    assert centroids.is_contiguous() and W.dtype == torch.float32 and W.stride(1) == 1
+    C, K, V = centroids.shape
+    D, M = W.shape
+    if D != C * V:
+        raise ValueError("W has %d rows, expected C*V = %d" % (D, C * V))
+    dev = centroids.device
+    if table_dtype == TABLE_F32:
+        table = torch.empty((C, K, M), dtype=torch.float32, device=dev)
+        pk, scale = None, None
+    else:
+        table = torch.empty((C, K, M), dtype=torch.int8, device=dev)
+        scale = torch.empty(1, dtype=torch.float32, device=dev)
+        pk = None
+        if packed:
+            nbytes = packed_bytes(C, K, M, table_dtype)
+            pk = torch.empty(nbytes, dtype=torch.int8, device=dev)
+    _check(LIB.lutnn_build_table(_ptr(centroids), _ptr(W), W.stride(0), C, K, V, M, table_dtype,
+                                 _ptr(table), _ptr(pk), _ptr(scale), _stream()))
+    return LutLayer(centroids, table, table_dtype, M, pk, scale, bias)
+
+
+def encode(layer, X, out=None):
+    """lutnn_encode: Eq. 2.  X [N, D] fp32 (row stride free) -> idx [N, C] uint8."""
+    assert X.is_cuda and X.dtype == torch.float32 and X.stride(1) == 1
+    N = X.shape[0]
+    if out is None:
+        out = torch.empty((N, layer.C), dtype=torch.uint8, device=X.device)
+    assert out.is_contiguous() and out.shape == (N, layer.C) and out.dtype == torch.uint8
+    _check(LIB.lutnn_encode(ctypes.byref(layer.c), _ptr(X), N, X.stride(0), _ptr(out), _stream()))
+    return out
+
+
+def lookup(layer, idx, variant="auto", out=None):
+    """lutnn_lookup: Eq. 4.  idx [N, C] uint8 -> Y [N, M] fp32."""
+    assert idx.is_cuda and idx.dtype == torch.uint8 and idx.is_contiguous()
+    N = idx.shape[0]
+    if out is None:
+        out = torch.empty((N, layer.M), dtype=torch.float32, device=idx.device)
+    assert out.dtype == torch.float32 and out.stride(1) == 1 and out.shape == (N, layer.M)
+    _check(LIB.lutnn_lookup(ctypes.byref(layer.c), _ptr(idx), N, _ptr(out), out.stride(0),
+                            _variant(variant), _stream()))
+    return out
+
+
+def linear(layer, X, variant="auto", out=None, idx_workspace=None):
+    """lutnn_linear: the whole operator, Y ~= X @ W (+ bias)."""
+    assert X.is_cuda and X.dtype == torch.float32 and X.stride(1) == 1
+    N = X.shape[0]
+    if out is None:
+        out = torch.empty((N, layer.M), dtype=torch.float32, device=X.device)
+    assert out.dtype == torch.float32 and out.stride(1) == 1 and out.shape == (N, layer.M)
+    v = _variant(variant)
+    if idx_workspace is None and v != VARIANT_FUSED:
+        idx_workspace = torch.empty((N, layer.C), dtype=torch.uint8, device=X.device)
+    _check(LIB.lutnn_linear(ctypes.byref(layer.c), _ptr(X), N, X.stride(0), _ptr(out),
+                            out.stride(0), v, _ptr(idx_workspace), _stream()))
+    return out

@@ -1,0 +1,63 @@
+"""Cost model of a LUT-NN linear operator (arXiv 2302.03213, Sec. 4, Table 1) and the work /
+traffic figures the benchmark prices against the MI355X rooflines.  Pure host arithmetic."""
+
+# MI355X published peaks used as roofline denominators.
+PEAK_HBM_BYTES_PER_S = 8.0e12
+PEAK_MFMA_INT8_OPS_PER_S = 5.0e15
+PEAK_VALU_F32_LANE_OPS_PER_S = 256 * 64 * 2.4e9  # 256 CUs x 64 lanes x 2.4 GHz, one op per lane-clock
+
+
+def lut_flops(N, D, M, K, V):
+    """Table 1, "Ours": N*D*K (encoding) + N*M*D/V (lookup + aggregation); a multiply-add counts 1."""
+    return N * D * K + N * M * D // V
+
+
+def mm_flops(N, D, M):
+    """Table 1, "MM": N*D*M."""
+    return N * D * M
+
+
+def flops_reduction(M, K, V):
+    """Sec. 6.2: M / (K + M/V)."""
+    return M / (K + M / V)
+
+
+def lut_size_bytes(D, M, K, V):
+    """Table 1, "Ours": 4*D*K (fp32 codebooks) + D*M*K/V (INT8 table)."""
+    return 4 * D * K + D * M * K // V
+
+
+def mm_size_bytes(D, M):
+    """Table 1, "MM": 4*D*M."""
+    return 4 * D * M
+
+
+def equivalent_flops(N, D, M):
+    """FLOPs of the dense product the operator replaces, multiply and add counted separately."""
+    return 2 * N * D * M
+
+
+def encode_bytes(N, C, V):
+    """Algorithmic HBM bytes of the encoder: read X once (4*D per row), write idx (C per row)."""
+    return N * (4 * C * V + C)
+
+
+def encode_lane_ops(N, C, K, V):
+    """VALU lane-ops of the direct-form distance + arg-min: per (row, codebook, centroid)
+    V subtracts + V fused multiply-adds + one compare + one select."""
+    return N * C * K * (2 * V + 2)
+
+
+def lookup_entries(N, C, M):
+    """Table entries read and added by Eq. 4."""
+    return N * C * M
+
+
+def lookup_mfma_ops(N, C, M, kpad=16):
+    """Dense INT8 ops of the one-hot contraction: 2 * N * (C*kpad) * M (1/kpad of them useful)."""
+    return 2 * N * C * kpad * M
+
+
+def lookup_hbm_bytes(N, C, K, M, table_elem_bytes):
+    """Algorithmic HBM bytes of the lookup: idx in, Y out, the table once."""
+    return N * C + 4 * N * M + C * K * M * table_elem_bytes

@@ -1,0 +1,255 @@
+// Host side of liblutnn: argument validation and dispatch for the C ABI declared in
+// include/lutnn.h.  Nothing here allocates device memory or synchronises.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "lutnn.h"
+#include "lutnn_kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+lutnn_status fail(lutnn_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+lutnn_status hip_result(hipError_t e, const char* what) {
+    if (e == hipSuccess) return LUTNN_OK;
+    return fail(LUTNN_E_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Dimensions shared by every entry point.  CK*M and N*C style products are formed in int64 by the
+// kernels; the individual dimensions must fit comfortably in int32.
+lutnn_status check_dims(int32_t C, int32_t K, int32_t V, int32_t M) {
+    if (C <= 0 || K <= 0 || V <= 0 || M <= 0)
+        return fail(LUTNN_E_SHAPE, "C, K, V, M must be positive (got C=%d K=%d V=%d M=%d)", C, K, V, M);
+    if (K > 256) return fail(LUTNN_E_SHAPE, "K=%d exceeds 256 (indices are uint8)", K);
+    if ((int64_t)C * V > (1 << 24) || M > (1 << 24) || C > (1 << 22))
+        return fail(LUTNN_E_SHAPE, "dimension too large (C=%d V=%d M=%d)", C, V, M);
+    return LUTNN_OK;
+}
+
+lutnn_status check_layer(const lutnn_layer* L) {
+    if (!L) return fail(LUTNN_E_NULL, "layer is NULL");
+    if (L->reserved != 0) return fail(LUTNN_E_SHAPE, "layer->reserved must be 0");
+    if (L->table_dtype != LUTNN_TABLE_F32 && L->table_dtype != LUTNN_TABLE_I8)
+        return fail(LUTNN_E_UNSUPPORTED, "unknown table dtype %d", L->table_dtype);
+    return check_dims(L->C, L->K, L->V, L->M);
+}
+
+constexpr int64_t kMaxRows = (int64_t)1 << 31;
+
+// Which lookup kernel AUTO resolves to.
+int resolve_lookup_variant(const lutnn_layer* L, int variant) {
+    if (variant != LUTNN_VARIANT_AUTO) return variant;
+    if (L->table_dtype == LUTNN_TABLE_I8 && L->table_packed && L->K <= 16) return LUTNN_VARIANT_MFMA;
+    return LUTNN_VARIANT_LDS;
+}
+
+lutnn_status check_lookup(const lutnn_layer* L, int variant, const float* Y, int64_t N, int64_t ldy) {
+    if (!Y) return fail(LUTNN_E_NULL, "Y is NULL");
+    if (N < 0 || N >= kMaxRows) return fail(LUTNN_E_SHAPE, "N=%lld out of range", (long long)N);
+    if (ldy < L->M) return fail(LUTNN_E_SHAPE, "ldy=%lld is smaller than M=%d", (long long)ldy, L->M);
+    if (!aligned(Y, 4)) return fail(LUTNN_E_ALIGN, "Y must be 4-byte aligned");
+    if (L->bias && !aligned(L->bias, 4)) return fail(LUTNN_E_ALIGN, "bias must be 4-byte aligned");
+    if (L->table_dtype == LUTNN_TABLE_I8 && !L->scale)
+        return fail(LUTNN_E_NULL, "INT8 table needs layer->scale");
+    switch (variant) {
+        case LUTNN_VARIANT_LDS:
+            if (!L->table) return fail(LUTNN_E_NULL, "the LDS variant needs layer->table");
+            if (L->table_dtype == LUTNN_TABLE_F32 && !aligned(L->table, 4))
+                return fail(LUTNN_E_ALIGN, "fp32 table must be 4-byte aligned");
+            break;
+        case LUTNN_VARIANT_MFMA:
+            if (L->table_dtype != LUTNN_TABLE_I8)
+                return fail(LUTNN_E_UNSUPPORTED, "the MFMA variant needs an INT8 table");
+            if (L->K > 16)
+                return fail(LUTNN_E_UNSUPPORTED, "the MFMA variant supports K <= 16 (got %d)", L->K);
+            if (!L->table_packed) return fail(LUTNN_E_NULL, "the MFMA variant needs layer->table_packed");
+            if (!aligned(L->table_packed, 16))
+                return fail(LUTNN_E_ALIGN, "table_packed must be 16-byte aligned");
+            break;
+        default:
+            return fail(LUTNN_E_UNSUPPORTED, "variant %d is not a lookup variant", variant);
+    }
+    return LUTNN_OK;
+}
+
+lutnn_status do_lookup(const lutnn_layer* L, int variant, const uint8_t* idx, int64_t N, float* Y,
+                       int64_t ldy, hipStream_t s) {
+    hipError_t e;
+    if (variant == LUTNN_VARIANT_MFMA) {
+        e = lutnn::launch_lookup_mfma_i8(static_cast<const int8_t*>(L->table_packed), L->scale, L->bias,
+                                         L->C, L->K, L->M, idx, N, Y, ldy, s);
+    } else if (L->table_dtype == LUTNN_TABLE_I8) {
+        e = lutnn::launch_lookup_lds_i8(static_cast<const int8_t*>(L->table), L->scale, L->bias, L->C,
+                                        L->K, L->M, idx, N, Y, ldy, s);
+    } else {
+        e = lutnn::launch_lookup_lds_f32(static_cast<const float*>(L->table), L->bias, L->C, L->K, L->M,
+                                         idx, N, Y, ldy, s);
+    }
+    return hip_result(e, "lookup launch");
+}
+
+lutnn_status check_encode(const lutnn_layer* L, const float* X, int64_t N, int64_t ldx) {
+    if (!L->centroids) return fail(LUTNN_E_NULL, "layer->centroids is NULL");
+    if (!X) return fail(LUTNN_E_NULL, "X is NULL");
+    if (N < 0 || N >= kMaxRows) return fail(LUTNN_E_SHAPE, "N=%lld out of range", (long long)N);
+    if (ldx < (int64_t)L->C * L->V)
+        return fail(LUTNN_E_SHAPE, "ldx=%lld is smaller than D=C*V=%lld", (long long)ldx,
+                    (long long)L->C * L->V);
+    if (!aligned(X, 4) || !aligned(L->centroids, 4))
+        return fail(LUTNN_E_ALIGN, "X and centroids must be 4-byte aligned");
+    return LUTNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t lutnn_table_bytes(int32_t C, int32_t K, int32_t M, int32_t dtype) {
+    if (C <= 0 || K <= 0 || M <= 0) return 0;
+    const size_t n = (size_t)C * (size_t)K * (size_t)M;
+    if (dtype == LUTNN_TABLE_I8) return n;
+    if (dtype == LUTNN_TABLE_F32) return n * 4;
+    return 0;
+}
+
+size_t lutnn_packed_bytes(int32_t C, int32_t K, int32_t M, int32_t dtype) {
+    if (C <= 0 || K <= 0 || K > 256 || M <= 0 || dtype != LUTNN_TABLE_I8) return 0;
+    return (size_t)C * (size_t)lutnn::kblocks(K) * (size_t)lutnn::packed_cols(M) * 16;
+}
+
+lutnn_status lutnn_build_table(const float* centroids, const float* W, int64_t ldw, int32_t C,
+                               int32_t K, int32_t V, int32_t M, int32_t dtype, void* table_out,
+                               void* packed_out, float* scale_out, void* stream) {
+    if (!centroids || !W || !table_out) return fail(LUTNN_E_NULL, "centroids, W or table_out is NULL");
+    if (lutnn_status st = check_dims(C, K, V, M)) return st;
+    if (ldw < M) return fail(LUTNN_E_SHAPE, "ldw=%lld is smaller than M=%d", (long long)ldw, M);
+    if (!aligned(centroids, 4) || !aligned(W, 4))
+        return fail(LUTNN_E_ALIGN, "centroids and W must be 4-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dtype == LUTNN_TABLE_F32) {
+        if (!aligned(table_out, 4)) return fail(LUTNN_E_ALIGN, "table_out must be 4-byte aligned");
+        return hip_result(lutnn::launch_build_table_f32(centroids, W, ldw, C, K, V, M,
+                                                        static_cast<float*>(table_out), s),
+                          "build_table launch");
+    }
+    if (dtype == LUTNN_TABLE_I8) {
+        if (!scale_out) return fail(LUTNN_E_NULL, "INT8 table needs scale_out");
+        if (!aligned(scale_out, 4)) return fail(LUTNN_E_ALIGN, "scale_out must be 4-byte aligned");
+        if (packed_out && !aligned(packed_out, 16))
+            return fail(LUTNN_E_ALIGN, "packed_out must be 16-byte aligned");
+        return hip_result(lutnn::launch_build_table_i8(centroids, W, ldw, C, K, V, M,
+                                                       static_cast<int8_t*>(table_out),
+                                                       static_cast<int8_t*>(packed_out), scale_out, s),
+                          "build_table launch");
+    }
+    return fail(LUTNN_E_UNSUPPORTED, "unknown table dtype %d", dtype);
+}
+
+lutnn_status lutnn_encode(const lutnn_layer* layer, const float* X, int64_t N, int64_t ldx,
+                          uint8_t* idx, void* stream) {
+    if (lutnn_status st = check_layer(layer)) return st;
+    if (lutnn_status st = check_encode(layer, X, N, ldx)) return st;
+    if (!idx) return fail(LUTNN_E_NULL, "idx is NULL");
+    if (N == 0) return LUTNN_OK;
+    return hip_result(lutnn::launch_encode(layer->centroids, layer->C, layer->K, layer->V, X, N, ldx, idx,
+                                           static_cast<hipStream_t>(stream)),
+                      "encode launch");
+}
+
+lutnn_status lutnn_lookup(const lutnn_layer* layer, const uint8_t* idx, int64_t N, float* Y,
+                          int64_t ldy, int32_t variant, void* stream) {
+    if (lutnn_status st = check_layer(layer)) return st;
+    if (!idx) return fail(LUTNN_E_NULL, "idx is NULL");
+    if (variant == LUTNN_VARIANT_FUSED)
+        return fail(LUTNN_E_UNSUPPORTED, "FUSED is a lutnn_linear variant, not a lookup variant");
+    const int v = resolve_lookup_variant(layer, variant);
+    if (lutnn_status st = check_lookup(layer, v, Y, N, ldy)) return st;
+    if (N == 0) return LUTNN_OK;
+    return do_lookup(layer, v, idx, N, Y, ldy, static_cast<hipStream_t>(stream));
+}
+
+lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, int64_t N, int64_t ldx, float* Y,
+                          int64_t ldy, int32_t variant, uint8_t* idx_workspace, void* stream) {
+    if (lutnn_status st = check_layer(layer)) return st;
+    if (lutnn_status st = check_encode(layer, X, N, ldx)) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const lutnn_layer* L = layer;
+
+    int v = variant;
+    if (v == LUTNN_VARIANT_AUTO) {
+        // One launch beats two while the encode recomputation it implies stays small; otherwise
+        // encode once and use the fastest lookup.
+        const bool fused_ok = lutnn::fused_supported(L->C, L->K, L->V, L->M, L->table_dtype) &&
+                              (L->table_dtype == LUTNN_TABLE_F32 ? L->table != nullptr
+                                                                 : L->table_packed != nullptr);
+        if (fused_ok && (L->M <= 256 || !idx_workspace))
+            v = LUTNN_VARIANT_FUSED;
+        else
+            v = resolve_lookup_variant(L, LUTNN_VARIANT_AUTO);
+    }
+
+    if (v == LUTNN_VARIANT_FUSED) {
+        if (!Y) return fail(LUTNN_E_NULL, "Y is NULL");
+        if (ldy < L->M) return fail(LUTNN_E_SHAPE, "ldy=%lld is smaller than M=%d", (long long)ldy, L->M);
+        if (!aligned(Y, 4)) return fail(LUTNN_E_ALIGN, "Y must be 4-byte aligned");
+        if (!lutnn::fused_supported(L->C, L->K, L->V, L->M, L->table_dtype))
+            return fail(LUTNN_E_UNSUPPORTED, "no fused kernel for C=%d K=%d V=%d M=%d dtype=%d", L->C, L->K,
+                        L->V, L->M, L->table_dtype);
+        if (N == 0) return LUTNN_OK;
+        if (L->table_dtype == LUTNN_TABLE_I8) {
+            if (!L->scale) return fail(LUTNN_E_NULL, "INT8 table needs layer->scale");
+            if (!L->table_packed) return fail(LUTNN_E_NULL, "the fused INT8 kernel needs layer->table_packed");
+            if (!aligned(L->table_packed, 16))
+                return fail(LUTNN_E_ALIGN, "table_packed must be 16-byte aligned");
+            return hip_result(lutnn::launch_linear_fused_i8(
+                                  L->centroids, static_cast<const int8_t*>(L->table_packed), L->scale,
+                                  L->bias, L->C, L->K, L->V, L->M, X, N, ldx, Y, ldy, s),
+                              "fused linear launch");
+        }
+        if (!L->table) return fail(LUTNN_E_NULL, "the fused fp32 kernel needs layer->table");
+        return hip_result(lutnn::launch_linear_fused_f32(L->centroids, static_cast<const float*>(L->table),
+                                                         L->bias, L->C, L->K, L->V, L->M, X, N, ldx, Y,
+                                                         ldy, s),
+                          "fused linear launch");
+    }
+
+    if (lutnn_status st = check_lookup(L, v, Y, N, ldy)) return st;
+    if (!idx_workspace) return fail(LUTNN_E_NULL, "this variant needs idx_workspace");
+    if (N == 0) return LUTNN_OK;
+    if (lutnn_status st = hip_result(
+            lutnn::launch_encode(L->centroids, L->C, L->K, L->V, X, N, ldx, idx_workspace, s),
+            "encode launch"))
+        return st;
+    return do_lookup(L, v, idx_workspace, N, Y, ldy, s);
+}
+
+const char* lutnn_status_string(int32_t status) {
+    switch (status) {
+        case LUTNN_OK: return "LUTNN_OK";
+        case LUTNN_E_NULL: return "LUTNN_E_NULL";
+        case LUTNN_E_SHAPE: return "LUTNN_E_SHAPE";
+        case LUTNN_E_UNSUPPORTED: return "LUTNN_E_UNSUPPORTED";
+        case LUTNN_E_ALIGN: return "LUTNN_E_ALIGN";
+        case LUTNN_E_HIP: return "LUTNN_E_HIP";
+        default: return "LUTNN_E_UNKNOWN";
+    }
+}
+
+const char* lutnn_last_error(void) { return g_err; }
+
+const char* lutnn_version(void) { return "0.1.0"; }
+
+}  // extern "C"

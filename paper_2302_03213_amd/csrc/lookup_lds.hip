@@ -1,0 +1,328 @@
+// Table read and accumulation (arXiv 2302.03213, Eq. 4 and Sec. 5.2), LDS gather variant, gfx950.
+//
+//   Y[n][m] = epilogue( sum_c T[c][idx[n][c]][m] )
+//
+// A workgroup owns an (R rows x MT columns) output tile and walks the codebooks in stages: the
+// K x MT slab of each of CC codebooks is staged in LDS as [codebook][k][MT] (m fastest), then
+// every wavefront handles its own rows one at a time.  For one (row, codebook) the index is
+// wave-uniform: it is fetched with a scalar load, four codebooks per dword, and the 64 lanes read
+// 64 consecutive dwords of the selected table row - consecutive banks, conflict free by
+// construction.  The paper's byte-shuffle table read (16 lookups per 128-bit shuffle) has no
+// CDNA counterpart; a wave-wide LDS row read is the equivalent "one instruction, many lookups".
+//
+// INT8 accumulation follows the paper's mixed-precision idea (16-bit partial sums, then 32-bit):
+// table bytes are stored in LDS with a +128 bias so they are unsigned, one dword carries four
+// columns, and the even/odd bytes are added as two packed 16-bit lanes with plain 32-bit adds.
+// 256 biased bytes cannot overflow 16 bits (256*255 < 65536); the partial sums are widened to
+// int32 at least that often and the bias (128 per codebook) is removed in the epilogue, so the
+// result is the exact integer sum.
+#include "lutnn_kernels.h"
+
+namespace lutnn {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;
+
+// ------------------------------------------------------------------------------------------ INT8
+constexpr int kColsI8 = 256;  // MT: 64 lanes x 4 columns
+constexpr int kRowsPerWaveI8 = 16;
+
+template <bool IDX_DWORD>
+__global__ __launch_bounds__(kThreads) void lookup_lds_i8_kernel(
+    const int8_t* __restrict__ T, const float* __restrict__ scale, const float* __restrict__ bias,
+    int C, int K, int M, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y,
+    int64_t ldy, int CC, int col_tiles, int table_vec16) {
+    extern __shared__ uint32_t lds[];  // [CC][K][64] dwords = 4 biased bytes each
+    constexpr int RW = kRowsPerWaveI8;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t row_tile = blockIdx.x / col_tiles;
+    const int n0 = (int)(blockIdx.x % col_tiles) * kColsI8;
+    const int64_t row0 = row_tile * (RW * kWaves) + (int64_t)w * RW;
+
+    uint32_t lo[RW], hi[RW];
+    int32_t acc[RW][4];
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+        lo[r] = hi[r] = 0;
+        acc[r][0] = acc[r][1] = acc[r][2] = acc[r][3] = 0;
+    }
+    int pending = 0;  // codebooks accumulated in lo/hi since the last widening
+    int slots = 0;    // codebook slots accumulated in total (each carries a +128 bias)
+
+    for (int c0 = 0; c0 < C; c0 += CC) {
+        __syncthreads();  // previous stage fully consumed
+        // ---- stage [CC][K][256 B]; bytes outside the table become 0 (biased: 0x80)
+        const int chunks = CC * K * 16;  // 16-byte chunks
+        for (int i = tid; i < chunks; i += kThreads) {
+            const int rowid = i >> 4, ch = i & 15;
+            const int cl = rowid / K, k = rowid - cl * K;
+            const int c = c0 + cl;
+            const int m = n0 + ch * 16;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (c < C) {
+                const int8_t* src = T + ((size_t)c * K + k) * M + m;
+                if (table_vec16 && m + 16 <= M) {
+                    v = *reinterpret_cast<const uint4*>(src);
+                } else {
+                    uint32_t t[4] = {0u, 0u, 0u, 0u};
+                    for (int b = 0; b < 16; ++b)
+                        if (m + b < M) t[b >> 2] |= (uint32_t)(uint8_t)src[b] << (8 * (b & 3));
+                    v = make_uint4(t[0], t[1], t[2], t[3]);
+                }
+            }
+            v.x ^= 0x80808080u;
+            v.y ^= 0x80808080u;
+            v.z ^= 0x80808080u;
+            v.w ^= 0x80808080u;
+            *reinterpret_cast<uint4*>(lds + (size_t)rowid * 64 + ch * 4) = v;
+        }
+        __syncthreads();
+
+        if (pending + CC > 256) {  // widen before 16-bit lanes could overflow
+#pragma unroll
+            for (int r = 0; r < RW; ++r) {
+                acc[r][0] += lo[r] & 0xffff;
+                acc[r][2] += lo[r] >> 16;
+                acc[r][1] += hi[r] & 0xffff;
+                acc[r][3] += hi[r] >> 16;
+                lo[r] = hi[r] = 0;
+            }
+            pending = 0;
+        }
+#pragma unroll
+        for (int r = 0; r < RW; ++r) {
+            const int64_t row = row0 + r;
+            if (row < N) {
+                for (int cl4 = 0; cl4 < CC; cl4 += 4) {
+                    uint32_t word;
+                    if (IDX_DWORD) {  // C % 4 == 0, 4-byte aligned: in range whenever c0+cl4 < C
+                        word = (c0 + cl4 < C)
+                                   ? *reinterpret_cast<const uint32_t*>(idx + row * C + c0 + cl4)
+                                   : 0u;
+                    } else {
+                        word = 0;
+                        for (int b = 0; b < 4; ++b)
+                            if (c0 + cl4 + b < C)
+                                word |= (uint32_t)idx[row * C + c0 + cl4 + b] << (8 * b);
+                    }
+                    word = __builtin_amdgcn_readfirstlane(word);
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        int k = (word >> (8 * b)) & 0xff;
+                        k = k < K ? k : K - 1;  // out-of-range indices must not read out of bounds
+                        const uint32_t x = lds[((cl4 + b) * K + k) * 64 + lane];
+                        lo[r] += x & 0x00ff00ffu;
+                        hi[r] += (x >> 8) & 0x00ff00ffu;
+                    }
+                }
+            }
+        }
+        pending += CC;
+        slots += CC;
+    }
+
+    // ---- epilogue: widen, remove the bias, dequantise (r = s*q, Sec. 3.3), add the layer bias
+    const float s = *scale;
+    const int col = n0 + lane * 4;
+    float bv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (bias)
+        for (int j = 0; j < 4; ++j)
+            if (col + j < M) bv[j] = bias[col + j];
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+        const int64_t row = row0 + r;
+        if (row >= N) continue;
+        int32_t a[4];
+        a[0] = acc[r][0] + (int32_t)(lo[r] & 0xffff) - 128 * slots;
+        a[2] = acc[r][2] + (int32_t)(lo[r] >> 16) - 128 * slots;
+        a[1] = acc[r][1] + (int32_t)(hi[r] & 0xffff) - 128 * slots;
+        a[3] = acc[r][3] + (int32_t)(hi[r] >> 16) - 128 * slots;
+        float* y = Y + row * ldy + col;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (col + j < M)
+                y[j] = bias ? __fmaf_rn((float)a[j], s, bv[j]) : __fmul_rn((float)a[j], s);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ FP32
+constexpr int kColsF32 = 128;  // MT: 64 lanes x 2 columns
+constexpr int kRowsPerWaveF32 = 8;
+
+template <bool IDX_DWORD>
+__global__ __launch_bounds__(kThreads) void lookup_lds_f32_kernel(
+    const float* __restrict__ T, const float* __restrict__ bias, int C, int K, int M,
+    const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y, int64_t ldy, int CC,
+    int col_tiles) {
+    extern __shared__ uint32_t lds[];
+    float2* tab = reinterpret_cast<float2*>(lds);  // [CC][K][64] float2
+    constexpr int RW = kRowsPerWaveF32;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t row_tile = blockIdx.x / col_tiles;
+    const int n0 = (int)(blockIdx.x % col_tiles) * kColsF32;
+    const int64_t row0 = row_tile * (RW * kWaves) + (int64_t)w * RW;
+
+    float2 acc[RW];
+#pragma unroll
+    for (int r = 0; r < RW; ++r) acc[r] = make_float2(0.f, 0.f);
+
+    for (int c0 = 0; c0 < C; c0 += CC) {
+        __syncthreads();
+        const int elems = CC * K * 64;  // float2 elements
+        for (int i = tid; i < elems; i += kThreads) {
+            const int rowid = i >> 6, j = i & 63;
+            const int cl = rowid / K, k = rowid - cl * K;
+            const int c = c0 + cl;
+            const int m = n0 + 2 * j;
+            float2 v = make_float2(0.f, 0.f);
+            if (c < C) {
+                const float* src = T + ((size_t)c * K + k) * M + m;
+                if (m < M) v.x = src[0];
+                if (m + 1 < M) v.y = src[1];
+            }
+            tab[i] = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < RW; ++r) {
+            const int64_t row = row0 + r;
+            if (row < N) {
+                for (int cl4 = 0; cl4 < CC; cl4 += 4) {
+                    uint32_t word;
+                    if (IDX_DWORD) {
+                        word = (c0 + cl4 < C)
+                                   ? *reinterpret_cast<const uint32_t*>(idx + row * C + c0 + cl4)
+                                   : 0u;
+                    } else {
+                        word = 0;
+                        for (int b = 0; b < 4; ++b)
+                            if (c0 + cl4 + b < C)
+                                word |= (uint32_t)idx[row * C + c0 + cl4 + b] << (8 * b);
+                    }
+                    word = __builtin_amdgcn_readfirstlane(word);
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        int k = (word >> (8 * b)) & 0xff;
+                        k = k < K ? k : K - 1;
+                        const float2 x = tab[((cl4 + b) * K + k) * 64 + lane];
+                        acc[r].x += x.x;  // codebooks past C were staged as zeros
+                        acc[r].y += x.y;
+                    }
+                }
+            }
+        }
+    }
+
+    const int col = n0 + lane * 2;
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+        const int64_t row = row0 + r;
+        if (row >= N) continue;
+        float* y = Y + row * ldy + col;
+        if (col < M) y[0] = bias ? acc[r].x + bias[col] : acc[r].x;
+        if (col + 1 < M) y[1] = bias ? acc[r].y + bias[col + 1] : acc[r].y;
+    }
+}
+
+// ------------------------------------------------------------------------------- any K: no LDS
+// One thread per (row, column); the table is read straight from global memory (L2).  Used when a
+// codebook's K x MT slab does not fit the LDS staging buffer.
+template <typename TT>
+__global__ __launch_bounds__(kThreads) void lookup_global_kernel(
+    const TT* __restrict__ T, const float* __restrict__ scale, const float* __restrict__ bias, int C,
+    int K, int M, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y, int64_t ldy) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= N * (int64_t)M) return;
+    const int64_t n = i / M;
+    const int m = (int)(i % M);
+    if constexpr (sizeof(TT) == 1) {
+        int32_t acc = 0;
+        for (int c = 0; c < C; ++c) {
+            int k = idx[n * C + c];
+            k = k < K ? k : K - 1;
+            acc += (int32_t)T[((size_t)c * K + k) * M + m];
+        }
+        const float s = *scale;
+        Y[n * ldy + m] = bias ? __fmaf_rn((float)acc, s, bias[m]) : __fmul_rn((float)acc, s);
+    } else {
+        float acc = 0.f;
+        for (int c = 0; c < C; ++c) {
+            int k = idx[n * C + c];
+            k = k < K ? k : K - 1;
+            acc += T[((size_t)c * K + k) * M + m];
+        }
+        Y[n * ldy + m] = bias ? acc + bias[m] : acc;
+    }
+}
+
+constexpr int kLdsBudget = 64 * 1024;
+
+inline bool idx_dword_ok(const uint8_t* idx, int C) {
+    return (C % 4 == 0) && ((reinterpret_cast<uintptr_t>(idx) & 3) == 0);
+}
+
+}  // namespace
+
+hipError_t launch_lookup_lds_i8(const int8_t* T, const float* scale, const float* bias, int C, int K,
+                                int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,
+                                hipStream_t s) {
+    const int per_codebook = K * kColsI8;  // LDS bytes per staged codebook
+    if (4 * per_codebook > kLdsBudget) {
+        const int64_t blocks = (N * (int64_t)M + kThreads - 1) / kThreads;
+        if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((lookup_global_kernel<int8_t>), dim3((unsigned)blocks), dim3(kThreads), 0, s,
+                           T, scale, bias, C, K, M, idx, N, Y, ldy);
+        return hipGetLastError();
+    }
+    int CC = (kLdsBudget / 2 / per_codebook) & ~3;  // aim for 32 KiB so two workgroups share a CU
+    if (CC < 4) CC = 4;
+    if (CC > 16) CC = 16;
+    const int col_tiles = (M + kColsI8 - 1) / kColsI8;
+    const int64_t row_tiles = (N + kRowsPerWaveI8 * kWaves - 1) / (kRowsPerWaveI8 * kWaves);
+    const int64_t blocks = row_tiles * col_tiles;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int vec16 = (M % 16 == 0) && ((reinterpret_cast<uintptr_t>(T) & 15) == 0);
+    const size_t shmem = (size_t)CC * per_codebook;
+    if (idx_dword_ok(idx, C))
+        hipLaunchKernelGGL((lookup_lds_i8_kernel<true>), dim3((unsigned)blocks), dim3(kThreads), shmem,
+                           s, T, scale, bias, C, K, M, idx, N, Y, ldy, CC, col_tiles, vec16);
+    else
+        hipLaunchKernelGGL((lookup_lds_i8_kernel<false>), dim3((unsigned)blocks), dim3(kThreads), shmem,
+                           s, T, scale, bias, C, K, M, idx, N, Y, ldy, CC, col_tiles, vec16);
+    return hipGetLastError();
+}
+
+hipError_t launch_lookup_lds_f32(const float* T, const float* bias, int C, int K, int M,
+                                 const uint8_t* idx, int64_t N, float* Y, int64_t ldy, hipStream_t s) {
+    const int per_codebook = K * kColsF32 * 4;
+    if (4 * per_codebook > kLdsBudget) {
+        const int64_t blocks = (N * (int64_t)M + kThreads - 1) / kThreads;
+        if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((lookup_global_kernel<float>), dim3((unsigned)blocks), dim3(kThreads), 0, s, T,
+                           (const float*)nullptr, bias, C, K, M, idx, N, Y, ldy);
+        return hipGetLastError();
+    }
+    int CC = (kLdsBudget / 2 / per_codebook) & ~3;
+    if (CC < 4) CC = 4;
+    if (CC > 16) CC = 16;
+    const int col_tiles = (M + kColsF32 - 1) / kColsF32;
+    const int64_t row_tiles = (N + kRowsPerWaveF32 * kWaves - 1) / (kRowsPerWaveF32 * kWaves);
+    const int64_t blocks = row_tiles * col_tiles;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const size_t shmem = (size_t)CC * per_codebook;
+    if (idx_dword_ok(idx, C))
+        hipLaunchKernelGGL((lookup_lds_f32_kernel<true>), dim3((unsigned)blocks), dim3(kThreads), shmem,
+                           s, T, bias, C, K, M, idx, N, Y, ldy, CC, col_tiles);
+    else
+        hipLaunchKernelGGL((lookup_lds_f32_kernel<false>), dim3((unsigned)blocks), dim3(kThreads), shmem,
+                           s, T, bias, C, K, M, idx, N, Y, ldy, CC, col_tiles);
+    return hipGetLastError();
+}
+
+}  // namespace lutnn

@@ -1,0 +1,47 @@
+// Internal launcher declarations shared by the host dispatch (api.hip) and the kernel files.
+// Every launcher assumes its arguments were validated by the caller in api.hip and returns the
+// hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lutnn {
+
+// Column padding of the MFMA operand copy of an INT8 table: [C*Kb][Mp][16], Mp = roundup(M, this).
+constexpr int kPackedColPad = 256;
+
+inline int64_t packed_cols(int64_t M) { return (M + kPackedColPad - 1) / kPackedColPad * kPackedColPad; }
+inline int kblocks(int K) { return (K + 15) / 16; }
+
+// Eq. 2.
+hipError_t launch_encode(const float* P, int C, int K, int V, const float* X, int64_t N, int64_t ldx,
+                         uint8_t* idx, hipStream_t s);
+
+// Eq. 3 + Sec. 3.3.
+hipError_t launch_build_table_f32(const float* P, const float* W, int64_t ldw, int C, int K, int V,
+                                  int M, float* T, hipStream_t s);
+hipError_t launch_build_table_i8(const float* P, const float* W, int64_t ldw, int C, int K, int V,
+                                 int M, int8_t* T, int8_t* packed, float* scale, hipStream_t s);
+
+// Eq. 4, gather variant.
+hipError_t launch_lookup_lds_i8(const int8_t* T, const float* scale, const float* bias, int C, int K,
+                                int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,
+                                hipStream_t s);
+hipError_t launch_lookup_lds_f32(const float* T, const float* bias, int C, int K, int M,
+                                 const uint8_t* idx, int64_t N, float* Y, int64_t ldy, hipStream_t s);
+
+// Eq. 4, one-hot MFMA variant (INT8).
+hipError_t launch_lookup_mfma_i8(const int8_t* packed, const float* scale, const float* bias, int C,
+                                 int K, int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,
+                                 hipStream_t s);
+
+// Eq. 2 + Eq. 4 in one kernel.
+bool fused_supported(int C, int K, int V, int M, int dtype);
+hipError_t launch_linear_fused_i8(const float* P, const int8_t* packed, const float* scale,
+                                  const float* bias, int C, int K, int V, int M, const float* X,
+                                  int64_t N, int64_t ldx, float* Y, int64_t ldy, hipStream_t s);
+hipError_t launch_linear_fused_f32(const float* P, const float* T, const float* bias, int C, int K,
+                                   int V, int M, const float* X, int64_t N, int64_t ldx, float* Y,
+                                   int64_t ldy, hipStream_t s);
+
+}  // namespace lutnn

@@ -1,0 +1,147 @@
+// One-hot INT8 MFMA contraction of Eq. 4 (arXiv 2302.03213) for one workgroup tile, shared by the
+// stand-alone lookup kernel and the fused encode+lookup kernel.
+//
+// Eq. 4 writes the lookup as  g^c(a^c) . h^c(b^c)  with g a one-hot vector of length K: stacked
+// over the codebooks this is  OneHot[N x C*K] x T[C*K x M].  With K <= 16 the one-hot slice of one
+// (row, codebook) is 16 bytes - exactly one lane's A operand of v_mfma_i32_32x32x32_i8 (a lane
+// holds 16 consecutive k of one row).  So the A operand is never read from memory: each lane
+// builds its 16 bytes from one index byte in registers.  The B operand is the table in the packed
+// layout [codebook][m][16 k], where a lane's 16 bytes are again contiguous, so B tiles are copied
+// global -> LDS -> registers without any transposition.
+//
+// Workgroup = 4 wavefronts arranged 2 x 2 over a (2*TM*32 rows) x 256 columns tile; each wave owns
+// TM x 4 MFMA tiles of 32 x 32.  The codebook loop runs in stages of 8 codebooks (32 KiB of B),
+// double buffered in LDS with register prefetch.  Within a stage, MFMA step j pairs codebook
+// 4h + j for lane half h (lanes 0-31 / 32-63); a lane therefore needs the index bytes of four
+// consecutive codebooks per stage, i.e. one dword.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lutnn {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kMfmaThreads = 256;
+constexpr int kMfmaBN = 256;  // columns per workgroup tile
+constexpr int kMfmaSC = 8;    // codebooks per stage
+constexpr int kMfmaStageVecs = kMfmaSC * kMfmaBN;  // uint4 per stage buffer (32 KiB)
+
+// 16-byte one-hot: byte k is 1, the rest 0 (k in 0..15).
+__device__ __forceinline__ v4i onehot16(uint32_t k) {
+    const uint32_t bit = 1u << ((k & 3u) * 8u);
+    const uint32_t d = (k >> 2) & 3u;
+    v4i a;
+    a.x = d == 0 ? bit : 0u;
+    a.y = d == 1 ? bit : 0u;
+    a.z = d == 2 ? bit : 0u;
+    a.w = d == 3 ? bit : 0u;
+    return a;
+}
+
+// Accumulates the whole codebook range into acc for this wave's TM x 4 MFMA tiles.
+//   packed    table in MFMA layout, [C][Mp] uint4
+//   n0        first column of the workgroup tile (multiple of 256, < Mp)
+//   lds       2 * kMfmaStageVecs uint4 of LDS, free for use on entry (all threads must have
+//             passed a barrier since its last use); on return every thread has passed a final barrier
+//   idx_word  idx_word(i, cbase) -> the index bytes of codebooks cbase..cbase+3 (cbase % 4 == 0)
+//             for the row this lane feeds in row block i; 0 for codebooks >= C or rows >= N
+template <int TM, class IdxWord>
+__device__ __forceinline__ void mfma_lookup_tile(const uint4* __restrict__ packed, int C, int Mp, int n0,
+                                                 uint4* __restrict__ lds, IdxWord idx_word,
+                                                 v16i (&acc)[TM][4]) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wn = (tid >> 6) & 1;
+    const int l32 = lane & 31, h = lane >> 5;
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    const int stages = (C + kMfmaSC - 1) / kMfmaSC;
+    uint4 pre[kMfmaSC];  // next stage's B bytes in flight: thread tid copies column tid of each codebook
+
+    auto fetch = [&](int st) {
+#pragma unroll
+        for (int i = 0; i < kMfmaSC; ++i) {
+            const int c = st * kMfmaSC + i;
+            pre[i] = (c < C) ? packed[((size_t)c * Mp + n0) + tid] : make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < kMfmaSC; ++i) lds[buf * kMfmaStageVecs + i * kMfmaBN + tid] = pre[i];
+    };
+
+    fetch(0);
+    stash(0);
+    __syncthreads();
+
+    for (int st = 0; st < stages; ++st) {
+        const int buf = st & 1;
+        if (st + 1 < stages) fetch(st + 1);
+
+        uint32_t word[TM];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) word[i] = idx_word(i, st * kMfmaSC + 4 * h);
+
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            v4i a[TM];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = onehot16((word[i] >> (8 * j)) & 15u);
+            v4i b[4];
+#pragma unroll
+            for (int tn = 0; tn < 4; ++tn) {
+                const uint4 v =
+                    lds[buf * kMfmaStageVecs + (4 * h + j) * kMfmaBN + wn * 128 + tn * 32 + l32];
+                b[tn] = v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w};
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int tn = 0; tn < 4; ++tn)
+                    acc[i][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[tn], acc[i][tn], 0, 0, 0);
+        }
+
+        if (st + 1 < stages) stash(buf ^ 1);
+        __syncthreads();
+    }
+}
+
+// Dequantise (r = s*q, Sec. 3.3), add the bias and store this wave's tiles.
+// 32x32 accumulator layout: lane -> column l32, register r -> row 8*(r/4) + 4*h + (r%4).
+//   row_base  first row of this wave's row block 0 (row block i starts at row_base + 32*i)
+template <int TM>
+__device__ __forceinline__ void mfma_store_tile(const v16i (&acc)[TM][4], float s,
+                                                const float* __restrict__ bias, int M, int64_t N,
+                                                int64_t row_base, int n0, float* __restrict__ Y,
+                                                int64_t ldy) {
+    const int lane = threadIdx.x & 63;
+    const int wn = (threadIdx.x >> 6) & 1;
+    const int l32 = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int tn = 0; tn < 4; ++tn) {
+        const int col = n0 + wn * 128 + tn * 32 + l32;
+        if (col >= M) continue;
+        const float bv = bias ? bias[col] : 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = row_base + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (row < N) {
+                    const float a = (float)acc[i][tn][r];
+                    Y[row * ldy + col] = bias ? __fmaf_rn(a, s, bv) : __fmul_rn(a, s);
+                }
+            }
+        }
+    }
+}
+
+}  // namespace lutnn

@@ -1,0 +1,155 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol include/lutnn.h declares,
+and rejects bad arguments on the host before anything could be launched.  No GPU needed."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lut():
+    import paper_2302_03213_amd as lut_mod
+    return lut_mod
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "lutnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"LUTNN_API[^;(]*?\b(lutnn_\w+)\s*\(", text)))
+
+
+def test_header_declares_the_documented_entry_points():
+    names = declared_symbols()
+    for must in ("lutnn_build_table", "lutnn_encode", "lutnn_lookup", "lutnn_linear"):
+        assert must in names
+    assert len(names) >= 9
+
+
+def test_library_exports_every_declared_symbol(lut):
+    for name in declared_symbols():
+        assert hasattr(lut.LIB, name), "liblutnn.so does not export %s" % name
+    assert sorted(lut.binding.EXPORTS) == declared_symbols()
+
+
+def test_no_other_symbols_leak(lut):
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", lut.binding._build.LIB],
+                         capture_output=True, text=True, check=True).stdout
+    syms = [l.split()[-1] for l in out.splitlines() if " T " in l]
+    assert sorted(s for s in syms if s.startswith("lutnn_")) == declared_symbols()
+
+
+def test_size_queries(lut):
+    assert lut.table_bytes(1024, 16, 4096, lut.TABLE_I8) == 64 * 2 ** 20  # 64 MiB table
+    assert lut.table_bytes(128, 16, 512, lut.TABLE_F32) == 128 * 16 * 512 * 4
+    assert lut.table_bytes(0, 16, 512, lut.TABLE_I8) == 0
+    assert lut.table_bytes(4, 16, 8, 7) == 0
+    assert lut.packed_bytes(64, 16, 64, lut.TABLE_I8) == 64 * 256 * 16  # M padded to 256
+    assert lut.packed_bytes(3, 33, 257, lut.TABLE_I8) == 3 * 3 * 512 * 16  # ceil(33/16) k blocks
+    assert lut.packed_bytes(64, 16, 64, lut.TABLE_F32) == 0
+
+
+def test_status_strings_and_version(lut):
+    names = [lut.LIB.lutnn_status_string(i).decode() for i in range(7)]
+    assert names == ["LUTNN_OK", "LUTNN_E_NULL", "LUTNN_E_SHAPE", "LUTNN_E_UNSUPPORTED",
+                     "LUTNN_E_ALIGN", "LUTNN_E_HIP", "LUTNN_E_UNKNOWN"]
+    assert re.fullmatch(r"\d+\.\d+\.\d+", lut.version())
+
+
+def _layer(lut, **kw):
+    from paper_2302_03213_amd.binding import _CLayer
+    f = dict(C=4, K=16, V=4, M=8, table_dtype=lut.TABLE_I8, reserved=0, centroids=0x1000,
+             table=0x2000, table_packed=0x3000, scale=0x4000, bias=None)
+    f.update(kw)
+    return _CLayer(**f)
+
+
+def _status(lut, code):
+    return lut.LIB.lutnn_status_string(code).decode(), lut.LIB.lutnn_last_error().decode()
+
+
+def test_host_validation_rejects_bad_arguments_before_any_launch(lut):
+    """Every call below fails validation on the host; the fake non-NULL addresses are never
+    dereferenced and nothing is enqueued."""
+    L, vp = lut.LIB, ctypes.c_void_p
+    X, Y, IDX = vp(0x10000), vp(0x20000), vp(0x30000)
+    ok = _layer(lut)
+    cases = [
+        (L.lutnn_encode(None, X, 4, 16, IDX, None), "LUTNN_E_NULL"),
+        (L.lutnn_encode(ctypes.byref(ok), None, 4, 16, IDX, None), "LUTNN_E_NULL"),
+        (L.lutnn_encode(ctypes.byref(ok), X, 4, 16, None, None), "LUTNN_E_NULL"),
+        (L.lutnn_encode(ctypes.byref(ok), X, -1, 16, IDX, None), "LUTNN_E_SHAPE"),
+        (L.lutnn_encode(ctypes.byref(ok), X, 4, 15, IDX, None), "LUTNN_E_SHAPE"),  # ldx < C*V
+        (L.lutnn_encode(ctypes.byref(ok), vp(0x10002), 4, 16, IDX, None), "LUTNN_E_ALIGN"),
+        (L.lutnn_encode(ctypes.byref(_layer(lut, K=257)), X, 4, 16, IDX, None), "LUTNN_E_SHAPE"),
+        (L.lutnn_encode(ctypes.byref(_layer(lut, C=0)), X, 4, 16, IDX, None), "LUTNN_E_SHAPE"),
+        (L.lutnn_encode(ctypes.byref(_layer(lut, table_dtype=9)), X, 4, 16, IDX, None),
+         "LUTNN_E_UNSUPPORTED"),
+        (L.lutnn_encode(ctypes.byref(_layer(lut, reserved=1)), X, 4, 16, IDX, None),
+         "LUTNN_E_SHAPE"),
+        (L.lutnn_encode(ctypes.byref(_layer(lut, centroids=None)), X, 4, 16, IDX, None),
+         "LUTNN_E_NULL"),
+        (L.lutnn_lookup(ctypes.byref(ok), None, 4, Y, 8, lut.VARIANT_LDS, None), "LUTNN_E_NULL"),
+        (L.lutnn_lookup(ctypes.byref(ok), IDX, 4, None, 8, lut.VARIANT_LDS, None), "LUTNN_E_NULL"),
+        (L.lutnn_lookup(ctypes.byref(ok), IDX, 4, Y, 7, lut.VARIANT_LDS, None), "LUTNN_E_SHAPE"),
+        (L.lutnn_lookup(ctypes.byref(ok), IDX, 4, Y, 8, lut.VARIANT_FUSED, None),
+         "LUTNN_E_UNSUPPORTED"),
+        (L.lutnn_lookup(ctypes.byref(ok), IDX, 4, Y, 8, 17, None), "LUTNN_E_UNSUPPORTED"),
+        (L.lutnn_lookup(ctypes.byref(_layer(lut, table_packed=None)), IDX, 4, Y, 8,
+                        lut.VARIANT_MFMA, None), "LUTNN_E_NULL"),
+        (L.lutnn_lookup(ctypes.byref(_layer(lut, table_packed=0x3008)), IDX, 4, Y, 8,
+                        lut.VARIANT_MFMA, None), "LUTNN_E_ALIGN"),
+        (L.lutnn_lookup(ctypes.byref(_layer(lut, K=32)), IDX, 4, Y, 8, lut.VARIANT_MFMA, None),
+         "LUTNN_E_UNSUPPORTED"),
+        (L.lutnn_lookup(ctypes.byref(_layer(lut, table_dtype=lut.TABLE_F32)), IDX, 4, Y, 8,
+                        lut.VARIANT_MFMA, None), "LUTNN_E_UNSUPPORTED"),
+        (L.lutnn_lookup(ctypes.byref(_layer(lut, scale=None)), IDX, 4, Y, 8, lut.VARIANT_LDS, None),
+         "LUTNN_E_NULL"),
+        (L.lutnn_lookup(ctypes.byref(_layer(lut, table=None)), IDX, 4, Y, 8, lut.VARIANT_LDS, None),
+         "LUTNN_E_NULL"),
+        (L.lutnn_linear(ctypes.byref(ok), X, 4, 16, Y, 8, lut.VARIANT_MFMA, None, None),
+         "LUTNN_E_NULL"),  # split variants need the index workspace
+        (L.lutnn_linear(ctypes.byref(_layer(lut, V=5)), X, 4, 20, Y, 8, lut.VARIANT_FUSED, None,
+                        None), "LUTNN_E_UNSUPPORTED"),
+        (L.lutnn_linear(ctypes.byref(ok), X, 4, 16, None, 8, lut.VARIANT_FUSED, None, None),
+         "LUTNN_E_NULL"),
+        (L.lutnn_build_table(None, X, 8, 4, 16, 4, 8, lut.TABLE_I8, Y, None, IDX, None),
+         "LUTNN_E_NULL"),
+        (L.lutnn_build_table(X, X, 7, 4, 16, 4, 8, lut.TABLE_I8, Y, None, IDX, None),
+         "LUTNN_E_SHAPE"),  # ldw < M
+        (L.lutnn_build_table(X, X, 8, 4, 16, 4, 8, lut.TABLE_I8, Y, None, None, None),
+         "LUTNN_E_NULL"),  # INT8 needs scale_out
+        (L.lutnn_build_table(X, X, 8, 4, 16, 4, 8, 5, Y, None, IDX, None), "LUTNN_E_UNSUPPORTED"),
+        (L.lutnn_build_table(X, X, 8, 4, 16, 4, 8, lut.TABLE_I8, Y, vp(0x3004), IDX, None),
+         "LUTNN_E_ALIGN"),
+    ]
+    for i, (code, want) in enumerate(cases):
+        name, detail = _status(lut, code)
+        assert name == want, "case %d: got %s (%s), wanted %s" % (i, name, detail, want)
+        assert detail
+
+
+def test_empty_batch_is_ok_without_a_gpu(lut):
+    L, vp = lut.LIB, ctypes.c_void_p
+    ok = _layer(lut)
+    assert L.lutnn_encode(ctypes.byref(ok), vp(0x10000), 0, 16, vp(0x30000), None) == 0
+    assert L.lutnn_lookup(ctypes.byref(ok), vp(0x30000), 0, vp(0x20000), 8, lut.VARIANT_MFMA, None) == 0
+    assert L.lutnn_linear(ctypes.byref(ok), vp(0x10000), 0, 16, vp(0x20000), 8, lut.VARIANT_FUSED,
+                          None, None) == 0
+
+
+def test_cost_model_formulas(lut):
+    c = lut.cost
+    # Table 1 with the paper's own example: FLOPs reduction M / (K + M/V) (Sec. 6.2)
+    N, D, M, K, V = 3136, 576, 64, 16, 9
+    assert c.lut_flops(N, D, M, K, V) == N * D * K + N * M * (D // V)
+    assert abs(c.mm_flops(N, D, M) / c.lut_flops(N, D, M, K, V) - c.flops_reduction(M, K, V)) < 1e-9
+    # "M = 128, 256 or 512 ... FLOPs can be reduced by 4x when K = 8" (Sec. 4): K-dominated limit
+    assert 3.0 < c.flops_reduction(512, 8, 9) / (512 / (8 + 512 / 9)) * c.flops_reduction(128, 8, 9) < 6.0
+    assert c.lut_size_bytes(D, M, K, V) == 4 * D * K + D * M * K // V
+    assert c.mm_size_bytes(D, M) == 4 * D * M
+    assert c.equivalent_flops(16384, 4096, 4096) == 2 * 16384 * 4096 * 4096
+    assert c.lookup_mfma_ops(16384, 1024, 4096) == 2 * 16384 * 16384 * 4096

@@ -1,0 +1,329 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element, on
+identical seeded inputs.  Bars (arXiv 2302.03213 leaves precision open; these are this project's):
+indices bit-exact except counted near-ties (fp64 distance gap < 1e-6 relative); INT8-table
+outputs bit-exact; fp32-table outputs within 1e-5 relative / 1e-4 absolute."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import lutnn_workloads as wl
+import oracle
+from gpu_util import (OracleLayer, dev, device_layer_from_oracle, host, near_tie_report,
+                      packed_from_q)
+
+pytestmark = pytest.mark.gpu
+
+F32_RTOL, F32_ATOL = 1e-5, 1e-4
+
+
+@pytest.fixture(scope="module")
+def lut():
+    import paper_2302_03213_amd as lut_mod
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return lut_mod
+
+
+@pytest.fixture(autouse=True)
+def announce(request):
+    print("\n[case] %s" % request.node.nodeid, file=sys.stderr, flush=True)
+    yield
+
+
+def assert_f32_close(got, ref):
+    np.testing.assert_allclose(got, ref, rtol=F32_RTOL, atol=F32_ATOL)
+
+
+# ------------------------------------------------------------------ lutnn_build_table (Eq. 3, Sec. 3.3)
+@pytest.mark.parametrize("C,K,V,M", [(5, 16, 4, 37), (3, 16, 9, 64), (8, 7, 2, 300), (2, 33, 3, 5),
+                                     (64, 16, 9, 64), (1, 1, 1, 1)])
+def test_build_table_matches_oracle(lut, C, K, V, M):
+    w = wl.make_layer("t", 1, C, K, V, M, "i8", seed=C * 1000 + M)
+    ol = OracleLayer(w)
+    P, W = dev(w.P), dev(w.W)
+    lf = lut.build_table(P, W, lut.TABLE_F32)
+    np.testing.assert_array_equal(host(lf.table), ol.Tf)  # same fma chain -> bit-exact
+    l8 = lut.build_table(P, W, lut.TABLE_I8)
+    assert host(l8.scale)[0] == ol.s
+    np.testing.assert_array_equal(host(l8.table), ol.q)
+    Kb, Mp = (K + 15) // 16, (M + 255) // 256 * 256
+    assert l8.packed.numel() == C * Kb * Mp * 16 == lut.packed_bytes(C, K, M, lut.TABLE_I8)
+    np.testing.assert_array_equal(host(l8.packed).reshape(C * Kb, Mp, 16), packed_from_q(ol.q))
+
+
+def test_build_table_strided_weights_and_zero_table(lut):
+    w = wl.make_layer("t", 1, 4, 16, 4, 20, "i8", seed=5)
+    Wbig = np.zeros((16, 31), np.float32)
+    Wbig[:, :20] = w.W
+    layer = lut.build_table(dev(w.P), dev(Wbig)[:, :20], lut.TABLE_I8)
+    ol = OracleLayer(w)
+    np.testing.assert_array_equal(host(layer.table), ol.q)
+    zero = lut.build_table(dev(w.P), dev(np.zeros_like(w.W)), lut.TABLE_I8)
+    assert host(zero.scale)[0] == np.float32(1.0) and not host(zero.table).any()
+
+
+# ------------------------------------------------------------------ lutnn_encode (Eq. 2)
+ENC_SHAPES = [
+    # N, C, K, V
+    (1, 1, 16, 4), (63, 5, 16, 4), (64, 32, 16, 4), (65, 33, 16, 4), (200, 128, 16, 4),
+    (130, 64, 16, 9), (77, 17, 16, 9), (300, 384, 16, 2), (129, 70, 16, 2), (100, 9, 16, 1),
+    (100, 35, 16, 3), (100, 20, 16, 8), (90, 7, 16, 5), (50, 3, 16, 16), (40, 2, 16, 32),
+    (150, 12, 8, 4), (150, 12, 5, 9), (60, 6, 1, 4), (60, 6, 256, 2), (33, 4, 100, 7),
+]
+
+
+@pytest.mark.parametrize("N,C,K,V", ENC_SHAPES)
+def test_encode_matches_oracle(lut, N, C, K, V):
+    w = wl.make_layer("t", N, C, K, V, 8, "f32", seed=N + 7 * C + K + V)
+    ref = oracle.encode(w.P, w.X)
+    layer = lut.LutLayer(dev(w.P), None, lut.TABLE_F32, w.M)
+    got = host(lut.encode(layer, dev(w.X)))
+    assert got.max() < K
+    ties = near_tie_report(w, got, ref)
+    assert ties <= max(1, N * C // 10000), "%d near-ties" % ties
+
+
+def test_encode_ties_and_centroid_inputs(lut):
+    # exact ties (duplicated centroids, equidistant grid points) must resolve to the lowest index
+    rng = np.random.default_rng(3)
+    C, K, V, N = 6, 16, 4, 500
+    P = (rng.integers(-4, 5, (C, K, V)) / 2.0).astype(np.float32)
+    P[:, 9] = P[:, 2]
+    X = (rng.integers(-8, 9, (N, C * V)) / 4.0).astype(np.float32)
+    layer = lut.LutLayer(dev(P), None, lut.TABLE_F32, 8)
+    np.testing.assert_array_equal(host(lut.encode(layer, dev(X))), oracle.encode(P, X))
+    w = wl.make_layer("t", 1, 40, 16, 9, 8, "f32", seed=4)
+    Xc, choice = wl.rows_from_centroids(w.P, 333, seed=5)
+    layer = lut.LutLayer(dev(w.P), None, lut.TABLE_F32, 8)
+    np.testing.assert_array_equal(host(lut.encode(layer, dev(Xc))), choice)
+
+
+def test_encode_row_stride_and_misaligned_rows(lut):
+    w = wl.make_layer("t", 150, 32, 16, 4, 8, "f32", seed=6)
+    ref = oracle.encode(w.P, w.X)
+    layer = lut.LutLayer(dev(w.P), None, lut.TABLE_F32, 8)
+    big = torch.zeros((150, 128 + 13), dtype=torch.float32, device="cuda")
+    big[:, 1:129] = dev(w.X)  # row stride 141 floats, first element 4-byte aligned only
+    got = host(lut.encode(layer, big[:, 1:129]))
+    np.testing.assert_array_equal(got, ref)
+
+
+def test_encode_nonfinite_inputs_stay_in_range(lut):
+    w = wl.make_layer("t", 64, 8, 16, 4, 8, "f32", seed=7)
+    X = w.X.copy()
+    X[3, 5] = np.nan
+    X[10, 0] = np.inf
+    layer = lut.LutLayer(dev(w.P), None, lut.TABLE_F32, 8)
+    got = host(lut.encode(layer, dev(X)))
+    assert got.max() < 16
+    ref = oracle.encode(w.P, w.X)
+    clean = np.ones(64, bool)
+    clean[[3, 10]] = False
+    np.testing.assert_array_equal(got[clean], ref[clean])
+
+
+# ------------------------------------------------------------------ lutnn_lookup (Eq. 4)
+LOOKUP_SHAPES = [
+    # N, C, K, M
+    (1, 1, 16, 1), (130, 8, 16, 64), (257, 37, 16, 250), (64, 5, 16, 300), (200, 64, 16, 64),
+    (129, 384, 16, 513), (70, 300, 16, 100), (90, 12, 7, 40), (50, 9, 1, 33), (128, 128, 16, 512),
+]
+
+
+@pytest.mark.parametrize("variant", ["lds", "mfma"])
+@pytest.mark.parametrize("N,C,K,M", LOOKUP_SHAPES)
+def test_lookup_i8_bit_exact(lut, variant, N, C, K, M):
+    w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=11 + N + C + M)
+    ol = OracleLayer(w)
+    ol.q = wl.random_table_i8(C, K, M, seed=12 + C)  # full-range table, arbitrary scale
+    ol.s = np.float32(0.0371)
+    idx = wl.random_indices(N, C, K, seed=13 + N)
+    for with_bias in (True, False):
+        layer = device_layer_from_oracle(lut, ol, with_bias)
+        got = host(lut.lookup(layer, dev(idx), variant))
+        ref = oracle.lookup_i8(ol.q, ol.s, idx, w.bias if with_bias else None)
+        np.testing.assert_array_equal(got, ref)
+
+
+@pytest.mark.parametrize("variant", ["lds", "mfma"])
+def test_lookup_i8_extreme_sums_do_not_wrap(lut, variant):
+    # all entries +-127 over C = 1536 codebooks (the deepest layer of the BERT workload):
+    # 16-bit partial sums would overflow many times over.
+    C, K, M, N = 1536, 16, 96, 70
+    q = np.full((C, K, M), 127, np.int8)
+    q[:, 1::2] = -127
+    w = wl.make_layer("t", 1, C, K, 1, M, "i8", seed=1)
+    ol = OracleLayer.__new__(OracleLayer)
+    ol.w, ol.q, ol.s, ol.Tf = w, q, np.float32(1.0), None
+    idx = np.zeros((N, C), np.uint8)
+    idx[1::2] = 1
+    idx[2] = wl.random_indices(1, C, K, seed=2)[0]
+    layer = device_layer_from_oracle(lut, ol, False)
+    got = host(lut.lookup(layer, dev(idx), variant))
+    ref = oracle.lookup_i8(q, 1.0, idx, None)
+    np.testing.assert_array_equal(got, ref)
+    assert got[0, 0] == 127.0 * C and got[1, 0] == -127.0 * C
+
+
+@pytest.mark.parametrize("N,C,K,M", LOOKUP_SHAPES + [(40, 6, 40, 70)])
+def test_lookup_f32_within_tolerance(lut, N, C, K, M):
+    w = wl.make_layer("t", 1, C, K, 4, M, "f32", seed=21 + N + C + M)
+    ol = OracleLayer(w)
+    idx = wl.random_indices(N, C, K, seed=23 + N)
+    for with_bias in (True, False):
+        layer = device_layer_from_oracle(lut, ol, with_bias)
+        got = host(lut.lookup(layer, dev(idx), "lds"))
+        assert_f32_close(got, oracle.lookup_f32(ol.Tf, idx, w.bias if with_bias else None))
+
+
+def test_lookup_large_k_uses_global_gather(lut):
+    N, C, K, M = 50, 5, 200, 130
+    q = wl.random_table_i8(C, K, M, seed=31)
+    idx = wl.random_indices(N, C, K, seed=32)
+    w = wl.make_layer("t", 1, C, K, 1, M, "i8", seed=33)
+    ol = OracleLayer.__new__(OracleLayer)
+    ol.w, ol.q, ol.s, ol.Tf = w, q, np.float32(0.5), None
+    layer = device_layer_from_oracle(lut, ol, True)
+    np.testing.assert_array_equal(host(lut.lookup(layer, dev(idx), "lds")),
+                                  oracle.lookup_i8(q, 0.5, idx, w.bias))
+    with pytest.raises(lut.LutnnError) as e:
+        lut.lookup(layer, dev(idx), "mfma")
+    assert e.value.name == "LUTNN_E_UNSUPPORTED"
+
+
+def test_lookup_output_stride_and_guard_band(lut):
+    N, C, K, M = 100, 16, 16, 70
+    w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=41)
+    ol = OracleLayer(w)
+    idx = wl.random_indices(N, C, K, seed=42)
+    layer = device_layer_from_oracle(lut, ol, True)
+    ref = ol.lookup(idx)
+    for variant in ("lds", "mfma"):
+        buf = torch.full((N + 8, M + 9), -777.0, dtype=torch.float32, device="cuda")
+        lut.lookup(layer, dev(idx), variant, out=buf[4:4 + N, 3:3 + M])
+        got = host(buf)
+        np.testing.assert_array_equal(got[4:4 + N, 3:3 + M], ref)
+        mask = np.ones_like(got, bool)
+        mask[4:4 + N, 3:3 + M] = False
+        assert (got[mask] == -777.0).all(), "%s wrote outside its output" % variant
+
+
+def test_lookup_out_of_range_indices_are_harmless(lut):
+    # idx >= K is the caller's bug: result unspecified, but in-bounds rows must be right and
+    # nothing may be read or written out of bounds.
+    N, C, K, M = 64, 8, 5, 64
+    w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=51)
+    ol = OracleLayer(w)
+    idx = wl.random_indices(N, C, K, seed=52)
+    bad = idx.copy()
+    bad[7, 3] = 250
+    layer = device_layer_from_oracle(lut, ol, True)
+    ref = ol.lookup(idx)
+    for variant in ("lds", "mfma"):
+        got = host(lut.lookup(layer, dev(bad), variant))
+        keep = np.arange(N) != 7
+        np.testing.assert_array_equal(got[keep], ref[keep])
+        assert np.isfinite(got).all()
+
+
+# ------------------------------------------------------------------ lutnn_linear (whole operator)
+def check_linear(lut, w, variants, X=None):
+    ol = OracleLayer(w)
+    X = w.X if X is None else X
+    idx_ref = ol.encode(X)
+    ref = ol.lookup(idx_ref)
+    P, W, Xd = dev(w.P), dev(w.W), dev(X)
+    dt = lut.TABLE_I8 if w.table_dtype == "i8" else lut.TABLE_F32
+    layer = lut.build_table(P, W, dt, bias=dev(w.bias))
+    idx_gpu = host(lut.encode(layer, Xd))
+    flips = near_tie_report(w, idx_gpu, idx_ref, X)
+    clean = (idx_gpu == idx_ref).all(axis=1)
+    assert flips <= max(1, idx_ref.size // 10000)
+    for v in variants:
+        got = host(lut.linear(layer, Xd, v))
+        if w.table_dtype == "i8":
+            np.testing.assert_array_equal(got[clean], ref[clean], err_msg="variant %s" % v)
+            # rows holding a flipped near-tie: one table entry swapped per flip
+            assert np.abs(got[~clean] - ref[~clean]).max(initial=0.0) <= 2 * 127 * float(ol.s) * 4
+        else:
+            assert_f32_close(got[clean], ref[clean])
+    return flips
+
+
+LINEAR_SHAPES = [
+    # N, C, K, V, M, dtype
+    (1, 1, 16, 4, 1, "i8"), (70, 5, 16, 4, 37, "i8"), (129, 33, 16, 9, 64, "i8"),
+    (257, 100, 16, 2, 300, "i8"), (100, 20, 7, 3, 40, "i8"), (64, 16, 16, 8, 512, "i8"),
+    (70, 5, 16, 4, 37, "f32"), (129, 33, 16, 9, 130, "f32"), (200, 70, 16, 2, 64, "f32"),
+    (50, 9, 5, 1, 20, "f32"),
+]
+
+
+@pytest.mark.parametrize("N,C,K,V,M,dtype", LINEAR_SHAPES)
+def test_linear_small_shapes(lut, N, C, K, V, M, dtype):
+    w = wl.make_layer("t", N, C, K, V, M, dtype, seed=N + C + M)
+    variants = ["auto", "lds", "fused"] + (["mfma"] if dtype == "i8" else [])
+    check_linear(lut, w, variants)
+
+
+def test_linear_generic_subvector_length(lut):
+    # V = 5 has no tiled encoder: split path works, fused is refused with a clear status.
+    w = wl.make_layer("t", 90, 7, 16, 5, 40, "i8", seed=8)
+    check_linear(lut, w, ["auto", "lds", "mfma"])
+    layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8)
+    with pytest.raises(lut.LutnnError) as e:
+        lut.linear(layer, dev(w.X), "fused")
+    assert e.value.name == "LUTNN_E_UNSUPPORTED"
+
+
+def test_config1_fc_small_fp32(lut):
+    flips = check_linear(lut, wl.fc_small(0), ["auto", "lds", "fused"])
+    print("config 1 near-ties: %d" % flips)
+
+
+def test_config2_conv_int8(lut):
+    flips = check_linear(lut, wl.conv_resnet18(0), ["auto", "lds", "mfma", "fused"])
+    print("config 2 near-ties: %d" % flips)
+
+
+def test_config3_bert_ffn_up_int8(lut):
+    flips = check_linear(lut, wl.bert_ffn_up(0), ["auto", "lds", "mfma", "fused"])
+    print("config 3 near-ties: %d" % flips)
+
+
+def test_identity_on_centroid_inputs(lut):
+    # end-to-end property independent of the oracle: rows made of centroids reproduce X @ W + b
+    w = wl.make_layer("t", 1, 24, 16, 4, 80, "f32", seed=9)
+    X, _ = wl.rows_from_centroids(w.P, 200, seed=10)
+    layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_F32, bias=dev(w.bias))
+    ref = X.astype(np.float64) @ w.W.astype(np.float64) + w.bias.astype(np.float64)
+    for v in ("lds", "fused"):
+        np.testing.assert_allclose(host(lut.linear(layer, dev(X), v)), ref, rtol=1e-5, atol=1e-5)
+
+
+def test_empty_batch_and_determinism(lut):
+    w = wl.make_layer("t", 300, 64, 16, 4, 256, "i8", seed=12)
+    layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8, bias=dev(w.bias))
+    X = dev(w.X)
+    for v in ("lds", "mfma", "fused"):
+        assert lut.linear(layer, X[:0], v).shape == (0, 256)
+        a = host(lut.linear(layer, X, v))
+        b = host(lut.linear(layer, X, v))
+        np.testing.assert_array_equal(a, b)
+    assert lut.encode(layer, X[:0]).shape == (0, 64)
+
+
+def test_error_statuses(lut):
+    w = wl.make_layer("t", 10, 4, 16, 4, 8, "i8", seed=13)
+    layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8)
+    X = dev(w.X)
+    with pytest.raises(lut.LutnnError) as e:
+        lut.lookup(layer, dev(wl.random_indices(10, 4, 16)), "fused")
+    assert e.value.name == "LUTNN_E_UNSUPPORTED"
+    no_packed = lut.LutLayer(layer.centroids, layer.table, lut.TABLE_I8, 8, None, layer.scale)
+    with pytest.raises(lut.LutnnError) as e:
+        lut.linear(no_packed, X, "mfma")
+    assert e.value.name == "LUTNN_E_NULL"
+    np.testing.assert_array_equal(host(lut.linear(no_packed, X, "auto")),
+                                  host(lut.linear(layer, X, "lds")))
