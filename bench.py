@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the LUT-NN linear operator (arXiv 2302.03213, Eq. 2 + Eq. 4) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--variant V]
+
+A step is one pass of the whole hot path - lutnn_linear: encode, then lookup-accumulate - over one
+batch of seeded synthetic input that is already resident in HBM.  Prints ONE JSON line:
+throughput in rows/s (value), equivalent TFLOP/s (2*N*D*M/t), the roofline fraction of the
+dominant kernel measured with HIP events, and the CPU oracle timed on a bounded row sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE runs, scaled by the same counters on a copy kernel of known size); the summaries
+# are under profiles/.  Keyed by (workload, kernel).  None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def workload_by_name(name):
+    import lutnn_workloads as wl
+    table = {
+        "fc_large": wl.fc_large, "fc_small": wl.fc_small, "conv_resnet18": wl.conv_resnet18,
+        "bert_ffn_up": wl.bert_ffn_up,
+    }
+    if name == "bert_layer":
+        return wl.bert_layer(0)
+    return [table[name](0)]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="fc_large",
+                    choices=["fc_large", "fc_small", "conv_resnet18", "bert_ffn_up", "bert_layer"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "lds", "mfma", "fused"])
+    ap.add_argument("--cpu-sample-rows", type=int, default=2048)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the operator shards by rows with no "
+              "communication; multi-GPU runs are not part of it). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2302_03213_amd as lut
+    from paper_2302_03213_amd import cost
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    layers = workload_by_name(args.workload)
+
+    # ---- device-side set-up (untimed): tables, two rotating activation / output buffer sets
+    dev_layers = []
+    for w in layers:
+        dt = lut.TABLE_I8 if w.table_dtype == "i8" else lut.TABLE_F32
+        P, W = torch.from_numpy(w.P).cuda(), torch.from_numpy(w.W).cuda()
+        bias = torch.from_numpy(w.bias).cuda() if w.bias is not None else None
+        layer = lut.build_table(P, W, dt, bias=bias)
+        X0 = torch.from_numpy(w.X).cuda()
+        Xs = [X0, X0.flip(0).contiguous()]
+        Ys = [torch.empty((w.N, w.M), dtype=torch.float32, device="cuda") for _ in range(2)]
+        ws = torch.empty((w.N, w.C), dtype=torch.uint8, device="cuda")
+        dev_layers.append((w, layer, Xs, Ys, ws))
+        del W
+    torch.cuda.synchronize()
+
+    def step(i):
+        for (w, layer, Xs, Ys, ws) in dev_layers:
+            lut.linear(layer, Xs[i & 1], args.variant, out=Ys[i & 1], idx_workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec_per_step = (t1 - t0) / args.steps
+
+    rows = sum(w.N for (w, *_r) in dev_layers)
+    eq_flops = sum(cost.equivalent_flops(w.N, w.D, w.M) for (w, *_r) in dev_layers)
+
+    # ---- per-kernel durations with HIP events on the launch stream (same kernels, same inputs):
+    # encode and lookup of the FIRST (for bert_layer: every) layer, split as lutnn_linear splits them
+    enc_ms, look_ms, fused_ms = [], [], []
+    variant_used = {}
+    for (w, layer, Xs, Ys, ws) in dev_layers:
+        fused = args.variant == "fused" or (args.variant == "auto" and w.M <= 256)
+        variant_used[w.name] = "fused" if fused else (
+            "mfma" if (args.variant in ("auto", "mfma") and w.table_dtype == "i8") else "lds")
+        e_acc = l_acc = f_acc = 0.0
+        for i in range(args.steps):
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            if fused:
+                ev[0].record()
+                lut.linear(layer, Xs[i & 1], "fused", out=Ys[i & 1])
+                ev[1].record()
+                ev[1].synchronize()
+                f_acc += ev[0].elapsed_time(ev[1])
+            else:
+                ev[0].record()
+                lut.encode(layer, Xs[i & 1], out=ws)
+                ev[1].record()
+                lut.lookup(layer, ws, variant_used[w.name], out=Ys[i & 1])
+                ev[2].record()
+                ev[2].synchronize()
+                e_acc += ev[0].elapsed_time(ev[1])
+                l_acc += ev[1].elapsed_time(ev[2])
+        enc_ms.append(e_acc / args.steps)
+        look_ms.append(l_acc / args.steps)
+        fused_ms.append(f_acc / args.steps)
+
+    # ---- roofline of the dominant kernel (of the first layer for multi-layer workloads)
+    w0 = dev_layers[0][0]
+    v0 = variant_used[w0.name]
+    if v0 == "mfma":
+        ops = cost.lookup_mfma_ops(w0.N, w0.C, w0.M)
+        achieved = ops / (look_ms[0] * 1e-3) / 1e12
+        roofline = {"kernel": "lookup_mfma_i8", "bound": "mfma", "achieved": round(achieved, 2),
+                    "peak": cost.PEAK_MFMA_INT8_OPS_PER_S / 1e12, "unit": "TOP/s",
+                    "frac": round(achieved * 1e12 / cost.PEAK_MFMA_INT8_OPS_PER_S, 4),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "lookup_mfma_i8")),
+                    "kernel_ms": round(look_ms[0], 4),
+                    "ops_per_launch": ops,
+                    "note": "dense int8 ops of the one-hot contraction 2*N*C*16*M; 1/16 of them "
+                            "carry a table entry (N*C*M entries per launch)"}
+    elif v0 == "lds":
+        entries = cost.lookup_entries(w0.N, w0.C, w0.M)
+        achieved = entries / (look_ms[0] * 1e-3) / 1e12
+        peak = cost.PEAK_VALU_F32_LANE_OPS_PER_S / 1e12
+        roofline = {"kernel": "lookup_lds", "bound": "alu", "achieved": round(achieved, 3),
+                    "peak": round(peak, 2), "unit": "T entry-adds/s (1 VALU lane-op each)",
+                    "frac": round(achieved / peak, 4),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "lookup_lds")),
+                    "kernel_ms": round(look_ms[0], 4)}
+    else:
+        byts = 4 * w0.N * w0.D + 4 * w0.N * w0.M + w0.C * w0.K * w0.M * (
+            1 if w0.table_dtype == "i8" else 4)
+        achieved = byts / (fused_ms[0] * 1e-3) / 1e9
+        roofline = {"kernel": "linear_fused", "bound": "hbm", "achieved": round(achieved, 1),
+                    "peak": cost.PEAK_HBM_BYTES_PER_S / 1e9, "unit": "GB/s",
+                    "frac": round(achieved * 1e9 / cost.PEAK_HBM_BYTES_PER_S, 4),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "linear_fused")),
+                    "kernel_ms": round(fused_ms[0], 4)}
+    kernels = {}
+    for (w, *_r), e, l, f in zip(dev_layers, enc_ms, look_ms, fused_ms):
+        if variant_used[w.name] == "fused":
+            kernels[w.name] = {"fused_ms": round(f, 4)}
+        else:
+            eb = cost.encode_bytes(w.N, w.C, w.V)
+            kernels[w.name] = {"encode_ms": round(e, 4), "lookup_ms": round(l, 4),
+                               "encode_hbm_GBps": round(eb / (e * 1e-3) / 1e9, 1),
+                               "encode_hbm_frac": round(eb / (e * 1e-3) / cost.PEAK_HBM_BYTES_PER_S, 4)}
+
+    # ---- CPU baseline: the oracle, as it stands, on a bounded row sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        t_cpu, n_cpu = 0.0, 0
+        for (w, *_r) in dev_layers:
+            n = min(w.N, args.cpu_sample_rows)
+            Tf = oracle.build_table_f32(w.P, w.W)  # offline, untimed like on the GPU
+            Xs = np.ascontiguousarray(w.X[:n])
+            if w.table_dtype == "i8":
+                q, s = oracle.quantize_i8(Tf)
+                c0 = time.perf_counter()
+                y = oracle.linear_i8(w.P, q, s, Xs, w.bias)
+            else:
+                c0 = time.perf_counter()
+                y = oracle.linear_f32(w.P, Tf, Xs, w.bias)
+            t_cpu += time.perf_counter() - c0
+            n_cpu += n
+            # cheap sanity link between the two sides on the sampled rows (not a parity test)
+            got = dev_layers[[d[0].name for d in dev_layers].index(w.name)][3][0][:64].cpu().numpy()
+            exp = y[:64]
+            close = np.isclose(got, exp, rtol=1e-5, atol=1e-4).mean()
+            assert close > 0.99, "GPU output disagrees with the oracle on %s" % w.name
+        cpu = {"value": round(n_cpu / t_cpu, 1), "unit": "rows/s", "cores": oracle.threads(),
+               "kind": "oracle",
+               "sample": "first %d rows of each layer of %s, encode+lookup, tables prebuilt; "
+                         "%.2f s wall" % (args.cpu_sample_rows, args.workload, t_cpu)}
+
+    w_desc = "; ".join("%s N=%d D=%d M=%d V=%d C=%d K=%d %s table" %
+                       (w.name, w.N, w.D, w.M, w.V, w.C, w.K, w.table_dtype)
+                       for (w, *_r) in dev_layers)
+    out = {
+        "metric": "lut_linear_rows_per_s", "value": round(rows / sec_per_step, 1), "unit": "rows/s",
+        "equiv_tflops": round(eq_flops / sec_per_step / 1e12, 2),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec_per_step * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "i8" if w0.table_dtype == "i8" else "f32",
+        "data": "synthetic",
+        "config": {"workload": w_desc, "variant": args.variant, "variant_used": variant_used,
+                   "step": "lutnn_linear per layer (encode fp32 + lookup), inputs resident in HBM, "
+                           "two rotating X/Y buffer sets"},
+        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -19,7 +19,8 @@
  *   - Every call validates its arguments on the host before launching anything and
  *     returns a lutnn_status; on failure nothing has been enqueued and
  *     lutnn_last_error() describes the reason.  No exception crosses this boundary.
- *   - N == 0 is valid and enqueues nothing.
+ *   - N == 0 is valid: once the layer descriptor has been validated the call returns LUTNN_OK
+ *     without looking at the data pointers (an empty batch may have none) or enqueuing anything.
  *   - Inputs are assumed finite.  Non-finite activations never cause an out-of-range
  *     index or an out-of-bounds access; the index chosen for them is unspecified.
  *   - Outputs must not alias inputs.

@@ -161,9 +161,9 @@ lutnn_status lutnn_build_table(const float* centroids, const float* W, int64_t l
 lutnn_status lutnn_encode(const lutnn_layer* layer, const float* X, int64_t N, int64_t ldx,
                           uint8_t* idx, void* stream) {
     if (lutnn_status st = check_layer(layer)) return st;
+    if (N == 0) return LUTNN_OK;  // an empty batch may come with NULL data pointers
     if (lutnn_status st = check_encode(layer, X, N, ldx)) return st;
     if (!idx) return fail(LUTNN_E_NULL, "idx is NULL");
-    if (N == 0) return LUTNN_OK;
     return hip_result(lutnn::launch_encode(layer->centroids, layer->C, layer->K, layer->V, X, N, ldx, idx,
                                            static_cast<hipStream_t>(stream)),
                       "encode launch");
@@ -172,18 +172,19 @@ lutnn_status lutnn_encode(const lutnn_layer* layer, const float* X, int64_t N, i
 lutnn_status lutnn_lookup(const lutnn_layer* layer, const uint8_t* idx, int64_t N, float* Y,
                           int64_t ldy, int32_t variant, void* stream) {
     if (lutnn_status st = check_layer(layer)) return st;
+    if (N == 0) return LUTNN_OK;  // an empty batch may come with NULL data pointers
     if (!idx) return fail(LUTNN_E_NULL, "idx is NULL");
     if (variant == LUTNN_VARIANT_FUSED)
         return fail(LUTNN_E_UNSUPPORTED, "FUSED is a lutnn_linear variant, not a lookup variant");
     const int v = resolve_lookup_variant(layer, variant);
     if (lutnn_status st = check_lookup(layer, v, Y, N, ldy)) return st;
-    if (N == 0) return LUTNN_OK;
     return do_lookup(layer, v, idx, N, Y, ldy, static_cast<hipStream_t>(stream));
 }
 
 lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, int64_t N, int64_t ldx, float* Y,
                           int64_t ldy, int32_t variant, uint8_t* idx_workspace, void* stream) {
     if (lutnn_status st = check_layer(layer)) return st;
+    if (N == 0) return LUTNN_OK;  // an empty batch may come with NULL data pointers
     if (lutnn_status st = check_encode(layer, X, N, ldx)) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const lutnn_layer* L = layer;
@@ -208,7 +209,6 @@ lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, int64_t N, i
         if (!lutnn::fused_supported(L->C, L->K, L->V, L->M, L->table_dtype))
             return fail(LUTNN_E_UNSUPPORTED, "no fused kernel for C=%d K=%d V=%d M=%d dtype=%d", L->C, L->K,
                         L->V, L->M, L->table_dtype);
-        if (N == 0) return LUTNN_OK;
         if (L->table_dtype == LUTNN_TABLE_I8) {
             if (!L->scale) return fail(LUTNN_E_NULL, "INT8 table needs layer->scale");
             if (!L->table_packed) return fail(LUTNN_E_NULL, "the fused INT8 kernel needs layer->table_packed");
@@ -228,7 +228,6 @@ lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, int64_t N, i
 
     if (lutnn_status st = check_lookup(L, v, Y, N, ldy)) return st;
     if (!idx_workspace) return fail(LUTNN_E_NULL, "this variant needs idx_workspace");
-    if (N == 0) return LUTNN_OK;
     if (lutnn_status st = hip_result(
             lutnn::launch_encode(L->centroids, L->C, L->K, L->V, X, N, ldx, idx_workspace, s),
             "encode launch"))
