@@ -51,13 +51,15 @@ __global__ __launch_bounds__(kMfmaThreads) void linear_fused_i8_kernel(
     extern __shared__ uint4 smem[];
     // [0, 64 KiB): B stage buffers of phase 2, reused as the X staging tile in phase 1
     float* xs = reinterpret_cast<float*>(smem);
-    uint32_t* is = reinterpret_cast<uint32_t*>(smem + 2 * kMfmaStageVecs);
+    uint4* lut = smem + 2 * kMfmaStageVecs;
+    uint32_t* is = reinterpret_cast<uint32_t*>(lut + kOnehotLutVecs);
     const int IS = Cpad / 4 + 1;
     const int K = K_T ? K_T : K_rt;
 
     const int64_t row0 = (int64_t)(blockIdx.x / col_groups) * kEncRows;
     const int g = (int)(blockIdx.x % col_groups);
 
+    init_onehot_lut(lut);
     fused_encode_phase<V, K_T>(X, ldx, P, C, K, N, row0, xs, is, IS, vec4);
 
     const int lane = threadIdx.x & 63;
@@ -70,7 +72,7 @@ __global__ __launch_bounds__(kMfmaThreads) void linear_fused_i8_kernel(
     const int col_tiles = Mp / kMfmaBN;
     for (int ct = g; ct < col_tiles; ct += col_groups) {
         v16i acc[1][4];
-        mfma_lookup_tile<1>(packed, C, Mp, ct * kMfmaBN, smem, idx_word, acc);
+        mfma_lookup_tile<1>(packed, C, Mp, ct * kMfmaBN, smem, lut, idx_word, acc);
         mfma_store_tile<1>(acc, s, bias, M, N, row0 + wm * 32, ct * kMfmaBN, Y, ldy);
     }
 }
@@ -178,7 +180,8 @@ hipError_t launch_i8(const float* P, const uint4* packed, const float* scale, co
     const int col_groups = pick_col_groups(row_tiles, Mp / kMfmaBN);
     const int64_t blocks = row_tiles * col_groups;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    const size_t shmem = (size_t)2 * kMfmaStageVecs * 16 + (size_t)kEncRows * idx_stride_dwords(Cpad) * 4;
+    const size_t shmem = (size_t)2 * kMfmaStageVecs * 16 + kOnehotLutVecs * 16 +
+                         (size_t)kEncRows * idx_stride_dwords(Cpad) * 4;
     const int vec4 = enc_vec4_ok(X, ldx, C, V);
     hipError_t e;
     if (K == 16) {
@@ -234,7 +237,7 @@ bool fused_supported(int C, int K, int V, int M, int dtype) {
     if (!CT || K > 16) return false;
     const int Cpad = (C + CT - 1) / CT * CT;
     const size_t idx_bytes = (size_t)kEncRows * idx_stride_dwords(Cpad) * 4;
-    const size_t region_a = 64 * 1024;  // both dtypes stay within 64 KiB for staging
+    const size_t region_a = 64 * 1024 + kOnehotLutVecs * 16;  // both dtypes stay within this for staging
     (void)dtype;
     return region_a + idx_bytes <= (size_t)kLdsMax;
 }

@@ -28,16 +28,18 @@ constexpr int kMfmaBN = 256;  // columns per workgroup tile
 constexpr int kMfmaSC = 8;    // codebooks per stage
 constexpr int kMfmaStageVecs = kMfmaSC * kMfmaBN;  // uint4 per stage buffer (32 KiB)
 
-// 16-byte one-hot: byte k is 1, the rest 0 (k in 0..15).
-__device__ __forceinline__ v4i onehot16(uint32_t k) {
-    const uint32_t bit = 1u << ((k & 3u) * 8u);
-    const uint32_t d = (k >> 2) & 3u;
-    v4i a;
-    a.x = d == 0 ? bit : 0u;
-    a.y = d == 1 ? bit : 0u;
-    a.z = d == 2 ? bit : 0u;
-    a.w = d == 3 ? bit : 0u;
-    return a;
+// One-hot look-up table in LDS: entry k (16 bytes) has byte k = 1 and the rest 0.  Building a
+// lane's A operand is then one shift/mask and one 16-byte LDS read instead of a dozen VALU ops;
+// the 16 entries sit in 64 different banks, so lanes with different k never conflict and lanes
+// with equal k are served by broadcast.  Must be followed by a barrier before first use.
+constexpr int kOnehotLutVecs = 16;
+__device__ __forceinline__ void init_onehot_lut(uint4* lut) {
+    const int t = threadIdx.x;
+    if (t < 16) {
+        const uint32_t bit = 1u << ((t & 3) * 8);
+        const int d = t >> 2;
+        lut[t] = make_uint4(d == 0 ? bit : 0u, d == 1 ? bit : 0u, d == 2 ? bit : 0u, d == 3 ? bit : 0u);
+    }
 }
 
 // Accumulates the whole codebook range into acc for this wave's TM x 4 MFMA tiles.
@@ -45,12 +47,14 @@ __device__ __forceinline__ v4i onehot16(uint32_t k) {
 //   n0        first column of the workgroup tile (multiple of 256, < Mp)
 //   lds       2 * kMfmaStageVecs uint4 of LDS, free for use on entry (all threads must have
 //             passed a barrier since its last use); on return every thread has passed a final barrier
+//   lut       one-hot table written by init_onehot_lut (a barrier has passed since)
 //   idx_word  idx_word(i, cbase) -> the index bytes of codebooks cbase..cbase+3 (cbase % 4 == 0)
-//             for the row this lane feeds in row block i; 0 for codebooks >= C or rows >= N
+//             for the row this lane feeds in row block i.  For codebooks >= C any value will do
+//             (their table slab is staged as zeros); likewise for rows >= N (never stored).
 template <int TM, class IdxWord>
 __device__ __forceinline__ void mfma_lookup_tile(const uint4* __restrict__ packed, int C, int Mp, int n0,
-                                                 uint4* __restrict__ lds, IdxWord idx_word,
-                                                 v16i (&acc)[TM][4]) {
+                                                 uint4* __restrict__ lds, const uint4* __restrict__ lut,
+                                                 IdxWord idx_word, v16i (&acc)[TM][4]) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wn = (tid >> 6) & 1;
@@ -64,42 +68,64 @@ __device__ __forceinline__ void mfma_lookup_tile(const uint4* __restrict__ packe
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
     const int stages = (C + kMfmaSC - 1) / kMfmaSC;
+    const uint4* __restrict__ src = packed + n0 + tid;  // column tid of the tile, codebook 0
     uint4 pre[kMfmaSC];  // next stage's B bytes in flight: thread tid copies column tid of each codebook
 
     auto fetch = [&](int st) {
+        const uint4* __restrict__ p = src + (size_t)st * kMfmaSC * Mp;
+        if ((st + 1) * kMfmaSC <= C) {
 #pragma unroll
-        for (int i = 0; i < kMfmaSC; ++i) {
-            const int c = st * kMfmaSC + i;
-            pre[i] = (c < C) ? packed[((size_t)c * Mp + n0) + tid] : make_uint4(0u, 0u, 0u, 0u);
+            for (int i = 0; i < kMfmaSC; ++i) pre[i] = p[(size_t)i * Mp];
+        } else {
+#pragma unroll
+            for (int i = 0; i < kMfmaSC; ++i)
+                pre[i] = (st * kMfmaSC + i < C) ? p[(size_t)i * Mp] : make_uint4(0u, 0u, 0u, 0u);
         }
     };
     auto stash = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < kMfmaSC; ++i) lds[buf * kMfmaStageVecs + i * kMfmaBN + tid] = pre[i];
     };
+    // this lane's B operand for codebook slot 4h + j, column tile tn: bvec[j * kMfmaBN + tn * 32]
+    const uint4* __restrict__ bbase = lds + (4 * h) * kMfmaBN + wn * 128 + l32;
 
+    // Index words are fetched one stage ahead and BEFORE the B prefetch of the same stage, so that
+    // waiting for them never waits for the (younger) B loads: vector memory loads return in order.
+    uint32_t next_word[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) next_word[i] = idx_word(i, 4 * h);
     fetch(0);
     stash(0);
     __syncthreads();
 
     for (int st = 0; st < stages; ++st) {
         const int buf = st & 1;
-        if (st + 1 < stages) fetch(st + 1);
-
-        uint32_t word[TM];
+        // byte j of w16 = 16 * (index of codebook st*8 + 4h + j) = byte offset into the one-hot table
+        uint32_t w16[TM];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) word[i] = idx_word(i, st * kMfmaSC + 4 * h);
+        for (int i = 0; i < TM; ++i) w16[i] = (next_word[i] & 0x0f0f0f0fu) << 4;
+        if (st + 1 < stages) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) next_word[i] = idx_word(i, (st + 1) * kMfmaSC + 4 * h);
+#ifndef LUTNN_EXP_NO_BFETCH
+            fetch(st + 1);
+#endif
+        }
 
+        const uint4* __restrict__ bvec = bbase + buf * kMfmaStageVecs;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             v4i a[TM];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = onehot16((word[i] >> (8 * j)) & 15u);
+            for (int i = 0; i < TM; ++i) {
+                const uint32_t off = (w16[i] >> (8 * j)) & 0xffu;
+                const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(lut) + off);
+                a[i] = v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w};
+            }
             v4i b[4];
 #pragma unroll
             for (int tn = 0; tn < 4; ++tn) {
-                const uint4 v =
-                    lds[buf * kMfmaStageVecs + (4 * h + j) * kMfmaBN + wn * 128 + tn * 32 + l32];
+                const uint4 v = bvec[j * kMfmaBN + tn * 32];
                 b[tn] = v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w};
             }
 #pragma unroll
