@@ -43,7 +43,7 @@ def main():
     ap.add_argument("--workload", default="fc_large",
                     choices=["fc_large", "fc_small", "conv_resnet18", "bert_ffn_up", "bert_layer"])
     ap.add_argument("--variant", default="auto", choices=["auto", "lds", "mfma", "fused"])
-    ap.add_argument("--cpu-sample-rows", type=int, default=2048)
+    ap.add_argument("--cpu-sample-rows", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:

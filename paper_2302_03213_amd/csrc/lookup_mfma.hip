@@ -143,19 +143,21 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_mfma_i8_pipelined_kern
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // operand registers, double buffered over MFMA steps; read r < 4 is A block r, else B tile r-4
+    // operand registers, double buffered over MFMA steps.  Read r < 4 is B tile r, else A block
+    // r-4: the first MFMAs of a step need all four B tiles but only A block 0, so this order gives
+    // every operand at least four MFMA groups between its read and its first use.
     v4i a[2][TM], b[2][4];
     const uint4* __restrict__ bbase = ring + (4 * h) * kMfmaBN + wn * 128 + l32;
     // w16 = byte offsets into the one-hot table for the 4 steps of one stage
     auto load_operand = [&](int set, int sbuf, int j, const uint32_t (&w16)[TM], int r) {
         uint4 v;
-        if (r < TM) {
-            const uint32_t off = (w16[r] >> (8 * j)) & 0xffu;
+        if (r >= 4) {
+            const uint32_t off = (w16[r - 4] >> (8 * j)) & 0xffu;
             v = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(lut) + off);
-            a[set][r] = v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w};
+            a[set][r - 4] = v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w};
         } else {
-            v = bbase[sbuf * STAGE_VECS + j * kMfmaBN + (r - TM) * 32];
-            b[set][r - TM] = v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w};
+            v = bbase[sbuf * STAGE_VECS + j * kMfmaBN + r * 32];
+            b[set][r] = v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w};
         }
     };
     // index words of a super-stage: wq[i][s'] = one-hot table offsets of row block i, stage s'

@@ -1,13 +1,14 @@
-// One-hot INT8 MFMA contraction of Eq. 4 (arXiv 2302.03213) for one workgroup tile, shared by the
-// stand-alone lookup kernel and the fused encode+lookup kernel.
+// One-hot INT8 MFMA contraction of Eq. 4 (arXiv 2302.03213) for one workgroup tile: the simple
+// loop shared by the fallback lookup kernel and the fused encode+lookup kernel (the main lookup
+// kernel in lookup_mfma.hip has its own hand-pipelined version of the same contraction).
 //
 // Eq. 4 writes the lookup as  g^c(a^c) . h^c(b^c)  with g a one-hot vector of length K: stacked
 // over the codebooks this is  OneHot[N x C*K] x T[C*K x M].  With K <= 16 the one-hot slice of one
 // (row, codebook) is 16 bytes - exactly one lane's A operand of v_mfma_i32_32x32x32_i8 (a lane
-// holds 16 consecutive k of one row).  So the A operand is never read from memory: each lane
-// builds its 16 bytes from one index byte in registers.  The B operand is the table in the packed
-// layout [codebook][m][16 k], where a lane's 16 bytes are again contiguous, so B tiles are copied
-// global -> LDS -> registers without any transposition.
+// holds 16 consecutive k of one row).  So the A operand is never read from global memory: each
+// lane turns one index byte into its 16 bytes with one read of a 256-byte one-hot table in LDS.
+// The B operand is the table in the packed layout [codebook][m][16 k], where a lane's 16 bytes
+// are again contiguous, so B tiles are copied global -> LDS -> registers without transposition.
 //
 // Workgroup = 4 wavefronts arranged 2 x 2 over a (2*TM*32 rows) x 256 columns tile; each wave owns
 // TM x 4 MFMA tiles of 32 x 32.  The codebook loop runs in stages of 8 codebooks (32 KiB of B),
@@ -107,9 +108,7 @@ __device__ __forceinline__ void mfma_lookup_tile(const uint4* __restrict__ packe
         if (st + 1 < stages) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) next_word[i] = idx_word(i, (st + 1) * kMfmaSC + 4 * h);
-#ifndef LUTNN_EXP_NO_BFETCH
             fetch(st + 1);
-#endif
         }
 
         const uint4* __restrict__ bvec = bbase + buf * kMfmaStageVecs;

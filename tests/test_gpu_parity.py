@@ -292,6 +292,41 @@ def test_config3_bert_ffn_up_int8(lut):
     print("config 3 near-ties: %d" % flips)
 
 
+def check_sampled_rows(lut, w, variants, n_sample=384, seed=0):
+    """Full-size parity: the GPU computes every row; the oracle's lookup (the slow part) is run on a
+    seeded sample of rows, its encoder on all of them."""
+    ol = OracleLayer(w)
+    idx_ref = ol.encode()
+    rng = np.random.default_rng(seed)
+    rows = np.sort(rng.choice(w.N, size=min(n_sample, w.N), replace=False))
+    rows[-1] = w.N - 1  # always include the last row
+    ref = ol.lookup(idx_ref[rows])
+    layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8, bias=dev(w.bias))
+    np.testing.assert_array_equal(host(layer.table), ol.q)
+    Xd = dev(w.X)
+    idx_gpu = host(lut.encode(layer, Xd))
+    flips = near_tie_report(w, idx_gpu, idx_ref)
+    assert flips <= max(1, idx_ref.size // 10000)
+    clean = (idx_gpu[rows] == idx_ref[rows]).all(axis=1)
+    for v in variants:
+        got = host(lut.linear(layer, Xd, v))[rows]
+        np.testing.assert_array_equal(got[clean], ref[clean], err_msg="variant %s" % v)
+    return flips
+
+
+def test_config4_bert_layer_linears_int8(lut):
+    for w in wl.bert_layer(0):
+        flips = check_sampled_rows(lut, w, ["auto", "mfma"], n_sample=256)
+        print("config 4 %s near-ties: %d" % (w.name, flips))
+
+
+def test_config5_fc_large_int8(lut):
+    # the benchmark workload, in the launch configuration bench.py times (variant auto)
+    w = wl.fc_large(0)
+    flips = check_sampled_rows(lut, w, ["auto", "mfma", "lds", "fused"], n_sample=384)
+    print("config 5 near-ties: %d" % flips)
+
+
 def test_identity_on_centroid_inputs(lut):
     # end-to-end property independent of the oracle: rows made of centroids reproduce X @ W + b
     w = wl.make_layer("t", 1, 24, 16, 4, 80, "f32", seed=9)
