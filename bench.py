@@ -21,7 +21,10 @@ if ROOT not in sys.path:
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by the same counters on a copy kernel of known size); the summaries
 # are under profiles/.  Keyed by (workload, kernel).  None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/lutnn_linear_fc_large.md: fetch 403,578,922 (197,084 KiB raw x 2.0) + write 268,435,456
+    ("fc_large", "lookup_mfma_i8"): 672014378,
+}
 
 
 def workload_by_name(name):
@@ -45,6 +48,9 @@ def main():
     ap.add_argument("--variant", default="auto", choices=["auto", "lds", "mfma", "fused"])
     ap.add_argument("--cpu-sample-rows", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (untimed): the known-size kernel "
+                         "against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the operator shards by rows with no "
@@ -75,6 +81,12 @@ def main():
         dev_layers.append((w, layer, Xs, Ys, ws))
         del W
     torch.cuda.synchronize()
+    if args.copy_calibration:
+        src = torch.empty(256 * 2 ** 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     def step(i):
         for (w, layer, Xs, Ys, ws) in dev_layers:
