@@ -45,7 +45,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="fc_large",
                     choices=["fc_large", "fc_small", "conv_resnet18", "bert_ffn_up", "bert_layer"])
-    ap.add_argument("--variant", default="auto", choices=["auto", "lds", "mfma", "fused"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "lds", "mfma", "smfmac", "fused"])
     ap.add_argument("--cpu-sample-rows", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -111,8 +111,13 @@ def main():
     variant_used = {}
     for (w, layer, Xs, Ys, ws) in dev_layers:
         fused = args.variant == "fused" or (args.variant == "auto" and w.M <= 256)
-        variant_used[w.name] = "fused" if fused else (
-            "mfma" if (args.variant in ("auto", "mfma") and w.table_dtype == "i8") else "lds")
+        if fused:
+            variant_used[w.name] = "fused"
+        elif args.variant == "auto":  # mirrors the library's AUTO rule
+            variant_used[w.name] = "lds" if w.table_dtype != "i8" else (
+                "smfmac" if (w.C % 32 == 0 and w.N > 256) else "mfma")
+        else:
+            variant_used[w.name] = args.variant
         e_acc = l_acc = f_acc = 0.0
         for i in range(args.steps):
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
@@ -138,17 +143,24 @@ def main():
     # ---- roofline of the dominant kernel (of the first layer for multi-layer workloads)
     w0 = dev_layers[0][0]
     v0 = variant_used[w0.name]
-    if v0 == "mfma":
+    if v0 in ("mfma", "smfmac"):
         ops = cost.lookup_mfma_ops(w0.N, w0.C, w0.M)
         achieved = ops / (look_ms[0] * 1e-3) / 1e12
-        roofline = {"kernel": "lookup_mfma_i8", "bound": "mfma", "achieved": round(achieved, 2),
+        kname = "lookup_mfma_i8" if v0 == "mfma" else "lookup_smfmac_i8"
+        roofline = {"kernel": kname, "bound": "mfma", "achieved": round(achieved, 2),
                     "peak": cost.PEAK_MFMA_INT8_OPS_PER_S / 1e12, "unit": "TOP/s",
                     "frac": round(achieved * 1e12 / cost.PEAK_MFMA_INT8_OPS_PER_S, 4),
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "lookup_mfma_i8")),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, kname)),
                     "kernel_ms": round(look_ms[0], 4),
                     "ops_per_launch": ops,
-                    "note": "dense int8 ops of the one-hot contraction 2*N*C*16*M; 1/16 of them "
-                            "carry a table entry (N*C*M entries per launch)"}
+                    "note": "dense-equivalent int8 ops of the one-hot contraction 2*N*C*16*M (1/16 of "
+                            "them carry a table entry, N*C*M entries per launch), priced against "
+                            "the DENSE int8 MFMA peak"}
+        if v0 == "smfmac":
+            roofline["note"] += ("; the kernel issues v_smfmac_i32_32x32x64_i8 (2:4 structured-sparse "
+                                 "A, which a one-hot slice satisfies exactly), i.e. half as many "
+                                 "matrix instructions as the dense form")
+            roofline["frac_of_sparse_peak"] = round(achieved * 1e12 / (2 * cost.PEAK_MFMA_INT8_OPS_PER_S), 4)
     elif v0 == "lds":
         entries = cost.lookup_entries(w0.N, w0.C, w0.M)
         achieved = entries / (look_ms[0] * 1e-3) / 1e12

@@ -55,7 +55,10 @@ typedef enum {
     LUTNN_VARIANT_AUTO = 0,  /* the library picks                                                  */
     LUTNN_VARIANT_LDS = 1,   /* table tiles staged in LDS, gathered by index, register accumulate   */
     LUTNN_VARIANT_MFMA = 2,  /* Eq. 4 as a dense onehot[N x CK] x T[CK x M] int8 MFMA contraction   */
-    LUTNN_VARIANT_FUSED = 3  /* lutnn_linear only: one kernel, indices never leave the chip          */
+    LUTNN_VARIANT_FUSED = 3, /* lutnn_linear only: one kernel, indices never leave the chip          */
+    LUTNN_VARIANT_SMFMAC = 4 /* as MFMA, on the 2:4 structured-sparse matrix instructions: a one-hot
+                                slice is 2:4 sparse by construction, so the result is identical at
+                                twice the matrix rate.  Needs C % 32 == 0, 16-byte aligned idx      */
 } lutnn_variant;
 
 /*
@@ -130,7 +133,8 @@ LUTNN_API lutnn_status lutnn_encode(const lutnn_layer* layer, const float* X, in
  *   idx  [N][C] uint8, dense; every value must be < K (larger values never cause an
  *        out-of-bounds access but give an unspecified result)
  *   Y    [N][M] fp32, row stride ldy >= M
- *   variant  AUTO, LDS (needs layer->table) or MFMA (INT8 only, needs layer->table_packed).
+ *   variant  AUTO, LDS (needs layer->table), MFMA or SMFMAC (INT8 only, K <= 16, need
+ *            layer->table_packed; SMFMAC also needs C % 32 == 0 and idx 16-byte aligned).
  * Errors: E_NULL, E_SHAPE, E_UNSUPPORTED, E_ALIGN, E_HIP.
  */
 LUTNN_API lutnn_status lutnn_lookup(const lutnn_layer* layer, const uint8_t* idx, int64_t N,
@@ -140,7 +144,8 @@ LUTNN_API lutnn_status lutnn_lookup(const lutnn_layer* layer, const uint8_t* idx
  * The whole operator: encode then lookup, Y ~= X . B (+ bias).
  *
  *   variant FUSED  one kernel; the indices stay in LDS.  `idx_workspace` is ignored.
- *   variant LDS / MFMA  lutnn_encode into idx_workspace, then lutnn_lookup with that variant.
+ *   variant LDS / MFMA / SMFMAC  lutnn_encode into idx_workspace, then lutnn_lookup with that
+ *                  variant.
  *   variant AUTO   picks per shape; may need the workspace.
  *   idx_workspace  [N][C] uint8 device scratch; may be NULL only for FUSED.
  * Errors: as lutnn_encode and lutnn_lookup.

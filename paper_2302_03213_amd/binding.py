@@ -21,8 +21,10 @@ VARIANT_AUTO = 0
 VARIANT_LDS = 1
 VARIANT_MFMA = 2
 VARIANT_FUSED = 3
+VARIANT_SMFMAC = 4
 
-VARIANTS = {"auto": VARIANT_AUTO, "lds": VARIANT_LDS, "mfma": VARIANT_MFMA, "fused": VARIANT_FUSED}
+VARIANTS = {"auto": VARIANT_AUTO, "lds": VARIANT_LDS, "mfma": VARIANT_MFMA, "fused": VARIANT_FUSED,
+            "smfmac": VARIANT_SMFMAC}
 
 EXPORTS = ["lutnn_table_bytes", "lutnn_packed_bytes", "lutnn_build_table", "lutnn_encode",
            "lutnn_lookup", "lutnn_linear", "lutnn_status_string", "lutnn_last_error",

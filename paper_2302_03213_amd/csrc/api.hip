@@ -50,13 +50,18 @@ lutnn_status check_layer(const lutnn_layer* L) {
 constexpr int64_t kMaxRows = (int64_t)1 << 31;
 
 // Which lookup kernel AUTO resolves to.
-int resolve_lookup_variant(const lutnn_layer* L, int variant) {
+int resolve_lookup_variant(const lutnn_layer* L, int variant, const uint8_t* idx, int64_t N) {
     if (variant != LUTNN_VARIANT_AUTO) return variant;
-    if (L->table_dtype == LUTNN_TABLE_I8 && L->table_packed && L->K <= 16) return LUTNN_VARIANT_MFMA;
+    if (L->table_dtype == LUTNN_TABLE_I8 && L->table_packed && L->K <= 16) {
+        // the sparse kernel works on 512-row tiles; below that the dense 256-row tile wastes less
+        if (N > 256 && lutnn::smfmac_supported(L->C, L->K, idx)) return LUTNN_VARIANT_SMFMAC;
+        return LUTNN_VARIANT_MFMA;
+    }
     return LUTNN_VARIANT_LDS;
 }
 
-lutnn_status check_lookup(const lutnn_layer* L, int variant, const float* Y, int64_t N, int64_t ldy) {
+lutnn_status check_lookup(const lutnn_layer* L, int variant, const uint8_t* idx, const float* Y,
+                          int64_t N, int64_t ldy) {
     if (!Y) return fail(LUTNN_E_NULL, "Y is NULL");
     if (N < 0 || N >= kMaxRows) return fail(LUTNN_E_SHAPE, "N=%lld out of range", (long long)N);
     if (ldy < L->M) return fail(LUTNN_E_SHAPE, "ldy=%lld is smaller than M=%d", (long long)ldy, L->M);
@@ -71,13 +76,19 @@ lutnn_status check_lookup(const lutnn_layer* L, int variant, const float* Y, int
                 return fail(LUTNN_E_ALIGN, "fp32 table must be 4-byte aligned");
             break;
         case LUTNN_VARIANT_MFMA:
+        case LUTNN_VARIANT_SMFMAC:
             if (L->table_dtype != LUTNN_TABLE_I8)
-                return fail(LUTNN_E_UNSUPPORTED, "the MFMA variant needs an INT8 table");
+                return fail(LUTNN_E_UNSUPPORTED, "the MFMA variants need an INT8 table");
             if (L->K > 16)
-                return fail(LUTNN_E_UNSUPPORTED, "the MFMA variant supports K <= 16 (got %d)", L->K);
-            if (!L->table_packed) return fail(LUTNN_E_NULL, "the MFMA variant needs layer->table_packed");
+                return fail(LUTNN_E_UNSUPPORTED, "the MFMA variants support K <= 16 (got %d)", L->K);
+            if (!L->table_packed) return fail(LUTNN_E_NULL, "the MFMA variants need layer->table_packed");
             if (!aligned(L->table_packed, 16))
                 return fail(LUTNN_E_ALIGN, "table_packed must be 16-byte aligned");
+            if (variant == LUTNN_VARIANT_SMFMAC) {
+                if (L->C % 32 != 0)
+                    return fail(LUTNN_E_UNSUPPORTED, "the SMFMAC variant needs C %% 32 == 0 (got %d)", L->C);
+                if (!aligned(idx, 16)) return fail(LUTNN_E_ALIGN, "the SMFMAC variant needs idx 16-byte aligned");
+            }
             break;
         default:
             return fail(LUTNN_E_UNSUPPORTED, "variant %d is not a lookup variant", variant);
@@ -88,7 +99,10 @@ lutnn_status check_lookup(const lutnn_layer* L, int variant, const float* Y, int
 lutnn_status do_lookup(const lutnn_layer* L, int variant, const uint8_t* idx, int64_t N, float* Y,
                        int64_t ldy, hipStream_t s) {
     hipError_t e;
-    if (variant == LUTNN_VARIANT_MFMA) {
+    if (variant == LUTNN_VARIANT_SMFMAC) {
+        e = lutnn::launch_lookup_smfmac_i8(static_cast<const int8_t*>(L->table_packed), L->scale, L->bias,
+                                           L->C, L->K, L->M, idx, N, Y, ldy, s);
+    } else if (variant == LUTNN_VARIANT_MFMA) {
         e = lutnn::launch_lookup_mfma_i8(static_cast<const int8_t*>(L->table_packed), L->scale, L->bias,
                                          L->C, L->K, L->M, idx, N, Y, ldy, s);
     } else if (L->table_dtype == LUTNN_TABLE_I8) {
@@ -176,8 +190,8 @@ lutnn_status lutnn_lookup(const lutnn_layer* layer, const uint8_t* idx, int64_t 
     if (!idx) return fail(LUTNN_E_NULL, "idx is NULL");
     if (variant == LUTNN_VARIANT_FUSED)
         return fail(LUTNN_E_UNSUPPORTED, "FUSED is a lutnn_linear variant, not a lookup variant");
-    const int v = resolve_lookup_variant(layer, variant);
-    if (lutnn_status st = check_lookup(layer, v, Y, N, ldy)) return st;
+    const int v = resolve_lookup_variant(layer, variant, idx, N);
+    if (lutnn_status st = check_lookup(layer, v, idx, Y, N, ldy)) return st;
     return do_lookup(layer, v, idx, N, Y, ldy, static_cast<hipStream_t>(stream));
 }
 
@@ -199,7 +213,7 @@ lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, int64_t N, i
         if (fused_ok && (L->M <= 256 || !idx_workspace))
             v = LUTNN_VARIANT_FUSED;
         else
-            v = resolve_lookup_variant(L, LUTNN_VARIANT_AUTO);
+            v = resolve_lookup_variant(L, LUTNN_VARIANT_AUTO, idx_workspace, N);
     }
 
     if (v == LUTNN_VARIANT_FUSED) {
@@ -226,8 +240,8 @@ lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, int64_t N, i
                           "fused linear launch");
     }
 
-    if (lutnn_status st = check_lookup(L, v, Y, N, ldy)) return st;
     if (!idx_workspace) return fail(LUTNN_E_NULL, "this variant needs idx_workspace");
+    if (lutnn_status st = check_lookup(L, v, idx_workspace, Y, N, ldy)) return st;
     if (lutnn_status st = hip_result(
             lutnn::launch_encode(L->centroids, L->C, L->K, L->V, X, N, ldx, idx_workspace, s),
             "encode launch"))

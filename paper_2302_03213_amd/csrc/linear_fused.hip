@@ -73,7 +73,8 @@ __global__ __launch_bounds__(kMfmaThreads) void linear_fused_i8_kernel(
     for (int ct = g; ct < col_tiles; ct += col_groups) {
         v16i acc[1][4];
         mfma_lookup_tile<1>(packed, C, Mp, ct * kMfmaBN, smem, lut, idx_word, acc);
-        mfma_store_tile<1>(acc, s, bias, M, N, row0 + wm * 32, ct * kMfmaBN, Y, ldy);
+        mfma_store_tile<1>(acc, s, bias, M, N, row0 + wm * 32,
+                           ct * kMfmaBN + ((threadIdx.x >> 6) & 1) * 128, Y, ldy);
     }
 }
 

@@ -45,15 +45,6 @@ namespace {
 
 static_assert(kMfmaBN == kPackedColPad, "packed column padding must match the column tile");
 
-// XCD-aware tile order: consecutive workgroup ids land on different XCDs (8 of them, each with its
-// own L2), so give every XCD a contiguous range of tiles; tiles are ordered column-block major, so
-// the workgroups resident on one XCD walk the same slab of the table.  Returns -1 for padding ids.
-__device__ __forceinline__ int64_t xcd_tile(int64_t tiles) {
-    const int64_t per_xcd = (tiles + 7) / 8;
-    const int64_t t = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    return t < tiles ? t : -1;
-}
-
 // ------------------------------------------------------------------------------- main kernel
 constexpr int TM = 4;                       // 32-row MFMA blocks per wave
 constexpr int BM = 2 * TM * 32;             // rows per workgroup (256)
@@ -63,28 +54,6 @@ constexpr int KSTEPS = SC / 2;              // MFMA steps per stage (2 codebooks
 constexpr int STAGE_VECS = kMfmaStageVecs;  // uint4 per stage buffer
 constexpr int SUPER = 4;                    // stages per super-stage (32 codebooks)
 static_assert(KSTEPS == 4 && SC == 8 && TM == 4 && NBUF == SUPER, "the schedule below assumes these");
-
-// LDS byte offset of a __shared__ object (the low 32 bits of its flat address).
-__device__ __forceinline__ uint32_t lds_offset(const void* p) {
-    return (uint32_t)reinterpret_cast<uintptr_t>(p);
-}
-// 64 lanes x 16 bytes from global memory straight into LDS at lds_dst + 16 * lane.
-//   sbase: wave-uniform global base;  voff: per-lane byte offset from it.
-// The compiler does not see the LDS write: completion is awaited with wait_loads<N>() before the
-// barrier that publishes the data.  "memory" keeps LDS reads from being folded or moved across.
-__device__ __forceinline__ void dma16(uint32_t lds_dst, const void* sbase, uint32_t voff) {
-    asm volatile(
-        "s_mov_b32 m0, %0\n\t"
-        "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %1, %2"
-        :
-        : "s"(lds_dst), "v"(voff), "s"(sbase)
-        : "memory", "m0");
-}
-template <int N>
-__device__ __forceinline__ void wait_loads() {
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
 
 __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_mfma_i8_pipelined_kernel(
     const uint4* __restrict__ packed, const float* __restrict__ scale, const float* __restrict__ bias,
@@ -277,7 +246,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_mfma_i8_pipelined_kern
     run_stage(u, SP2{}, std::false_type{});
     run_stage(u, SP3{}, std::false_type{});
 
-    mfma_store_tile<TM>(acc, *scale, bias, M, N, row_base, n0, Y, ldy);
+    mfma_store_tile<TM>(acc, *scale, bias, M, N, row_base, n0 + wn * 128, Y, ldy);
 }
 
 // ----------------------------------------------------------------------------- fallback kernel
@@ -313,7 +282,7 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void lookup_mfma_i8_generic_kernel
     };
     v16i acc[2][4];
     mfma_lookup_tile<2>(packed, C, Mp, n0, lds, lut, idx_word, acc);
-    mfma_store_tile<2>(acc, *scale, bias, M, N, row_base, n0, Y, ldy);
+    mfma_store_tile<2>(acc, *scale, bias, M, N, row_base, n0 + ((threadIdx.x >> 6) & 1) * 128, Y, ldy);
 }
 
 }  // namespace

@@ -1,0 +1,292 @@
+// Table read and accumulation (arXiv 2302.03213, Eq. 4) on the structured-sparse matrix cores of
+// gfx950 (v_smfmac_i32_32x32x64_i8).
+//
+// Eq. 4 is OneHot[N x C*16] x T[C*16 x M].  A one-hot slice of 16 has one non-zero in four groups
+// of four, so it trivially meets the 2:4 structured-sparsity format of the SMFMAC instructions:
+// per group of 4 consecutive k the A operand stores 2 values plus a 2-bit position for each.  The
+// instruction covers k = 64 (four codebooks) in the 32 cycles a dense 32x32x32 MFMA needs for two
+// codebooks, so the contraction runs at twice the dense rate with the result unchanged (exact
+// int32).  Measured operand layout (lane = 32h + l):
+//   A values, lane (row l, half h): stored bytes 0-7  -> k block h     (k = 16h + ...),
+//                                   stored bytes 8-15 -> k block 2 + h (k = 32 + 16h + ...);
+//                                   stored bytes 2g, 2g+1 belong to group g of the block;
+//   A positions: bits [2t+1:2t] of the index register = position (0-3) of stored byte t;
+//   B, lane (column l, half h): bytes 0-15 -> k block 2h, bytes 16-31 -> k block 2h + 1;
+//   D: as for the dense 32x32 MFMA.
+// A lane's operand for one codebook with index p is therefore: stored byte 2(p>>2) = 1, position
+// field of that byte = p&3, everything else 0 - read from a 16-entry table in LDS.
+//
+// Kernel shape.  Workgroup = 4 wavefronts stacked over rows, one per SIMD, output tile 512 rows x
+// 128 columns (each wave 128 x 128, 256 accumulator registers): with the matrix pipe twice as
+// fast, halving the table bytes per MFMA matters more than re-reading the indices (32 column
+// blocks instead of 16).  Codebooks are walked in super-stages of 32 = 2 stages of 16 = 4 steps of
+// 4 codebooks; step j of stage s' of super-stage u uses codebooks 32u + 16h + 8s' + 2j + {0,1} for
+// lane half h, so a lane's 16 index bytes per super-stage are contiguous.  Table slabs (32 KiB
+// per stage) and index bytes go global -> LDS directly (global_load_lds_dwordx4 from inline
+// assembly, explicit vmcnt waits) three stages ahead through a ring of four stage buffers; the
+// operands of the next step are read from LDS between the MFMAs of the current one.  See
+// lookup_mfma.hip for the reasoning behind each of these choices; this kernel has the same
+// structure with a different tile and operand format.
+//
+// Needs C % 32 == 0 and a 16-byte aligned idx.
+#include <type_traits>
+
+#include "lutnn_kernels.h"
+#include "mfma_tile.h"
+
+namespace lutnn {
+namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+
+constexpr int TM = 4;                 // 32-row blocks per wave
+constexpr int WAVE_ROWS = TM * 32;    // 128
+constexpr int BM = 4 * WAVE_ROWS;     // rows per workgroup (512)
+constexpr int BN = 128;               // columns per workgroup
+constexpr int NBUF = 4;               // LDS ring depth, stages
+constexpr int SC = 16;                // codebooks per stage
+constexpr int KSTEPS = 4;             // MFMA steps per stage, 4 codebooks each
+constexpr int STAGE_VECS = SC * BN;   // uint4 per stage buffer (32 KiB)
+constexpr int B_LOADS = 8;            // table loads per wave per stage
+constexpr int I_LOADS = TM;           // index loads per wave per super-stage
+
+// Entry p of the operand table: {values lo, values hi, positions (in both halves), 0}.
+__device__ __forceinline__ void init_sparse_lut(uint4* lut) {
+    const int p = threadIdx.x;
+    if (p < 16) {
+        const int g = p >> 2;
+        const uint32_t pos = (uint32_t)(p & 3) << (4 * g);
+        lut[p] = make_uint4(g < 2 ? 1u << (16 * g) : 0u, g >= 2 ? 1u << (16 * (g - 2)) : 0u,
+                            pos | (pos << 16), 0u);
+    }
+}
+
+__global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
+    const uint4* __restrict__ packed, const float* __restrict__ scale, const float* __restrict__ bias,
+    int C, int M, int Mp, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y,
+    int64_t ldy, int row_tiles, int64_t tiles) {
+    __shared__ uint4 ring[NBUF * STAGE_VECS];  // 4 x 32 KiB table slabs
+    __shared__ uint4 ibuf[4][TM][64];          // [wave][row block][lane]: one super-stage of indices
+    __shared__ uint4 lut[16];
+
+    const int64_t t = xcd_tile(tiles);
+    if (t < 0) return;
+    const int n0 = (int)(t / row_tiles) * BN;
+    const int64_t m0 = (t % row_tiles) * BM;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform
+    const int l32 = lane & 31, h = lane >> 5;
+    const int64_t row_base = m0 + w * WAVE_ROWS;
+
+    init_sparse_lut(lut);
+
+    const int supers = C / 32;  // C % 32 == 0
+    const int stages = 2 * supers;
+
+    // ---- load issue.  Slot g of stage s = 2u + s' holds codebook 32u + 16(g>>3) + 8s' + (g&7).
+    // Wave w copies slots 4w .. 4w+3, both 64-column halves: load q -> slot 4w + (q>>1), half q&1.
+    const uint32_t lane16 = lane * 16;
+    const uint32_t ring0 = lds_offset(ring);
+    auto load_b = [&](int s, int q) {
+        const int g = 4 * w + (q >> 1);
+        const int c = 32 * (s >> 1) + 16 * (g >> 3) + 8 * (s & 1) + (g & 7);
+        dma16(ring0 + ((s & 3) * STAGE_VECS + g * BN + 64 * (q & 1)) * 16,
+              packed + (size_t)c * Mp + n0 + 64 * (q & 1), lane16);
+    };
+    // Indices of super-stage u: lane (row l32 of block i, half h) gets bytes [32u + 16h, +16).
+    // Rows >= N re-read row N-1 (their results are never stored).
+    const uint8_t* __restrict__ isrc = idx + m0 * C;  // wave-uniform
+    uint32_t ioff[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        int64_t row = w * WAVE_ROWS + i * 32 + l32;
+        if (m0 + row >= N) row = N - 1 - m0;
+        ioff[i] = (uint32_t)(row * C + 16 * h);
+    }
+    const uint32_t ibuf0 = lds_offset(ibuf) + w * TM * 64 * 16;
+    auto load_idx = [&](int u, int i) { dma16(ibuf0 + i * 64 * 16, isrc + 32 * u, ioff[i]); };
+
+    v16i acc[TM][4];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    // Operand registers, double buffered over MFMA steps.  A step needs 16 LDS reads: read r < 8
+    // is half (r&1) of B tile r>>1, read r >= 8 is codebook (r&1) of A block (r-8)>>1.
+    v4i a[2][TM];
+    int apos[2][TM];
+    v8i b[2][4];
+    uint32_t alo[TM];  // positions of the first codebook, waiting for the second
+    // wq[i][d] = dword d of row block i's 16 index bytes, as byte offsets into the operand table
+    auto load_operand = [&](int set, int sbuf, int sp, int j, const uint32_t (&wq)[TM][4], int r) {
+        if (r < 8) {
+            const int tn = r >> 1, half = r & 1;
+            const uint4 v = ring[sbuf * STAGE_VECS + (8 * half + 2 * j + h) * BN + tn * 32 + l32];
+            b[set][tn][4 * half + 0] = (int)v.x;
+            b[set][tn][4 * half + 1] = (int)v.y;
+            b[set][tn][4 * half + 2] = (int)v.z;
+            b[set][tn][4 * half + 3] = (int)v.w;
+        } else {
+            const int i = (r - 8) >> 1, second = r & 1;
+            const uint32_t word = wq[i][2 * sp + (j >> 1)];
+            const uint32_t off = (word >> (16 * (j & 1) + 8 * second)) & 0xffu;
+            const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(lut) + off);
+            a[set][i][2 * second + 0] = (int)v.x;
+            a[set][i][2 * second + 1] = (int)v.y;
+            if (!second)
+                alo[i] = v.z;
+            else
+                apos[set][i] = (int)((alo[i] & 0xffffu) | (v.z & 0xffff0000u));
+        }
+    };
+    auto read_idx = [&](uint32_t (&wq)[TM][4]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const uint4 v = ibuf[w][i][lane];
+            wq[i][0] = (v.x & 0x0f0f0f0fu) << 4;  // byte = 16 * index = offset of the table entry
+            wq[i][1] = (v.y & 0x0f0f0f0fu) << 4;
+            wq[i][2] = (v.z & 0x0f0f0f0fu) << 4;
+            wq[i][3] = (v.w & 0x0f0f0f0fu) << 4;
+        }
+    };
+
+    // ---- prologue: stages 0..2, the indices of super-stage 0 (into registers) and 1 (in flight)
+#pragma unroll
+    for (int i = 0; i < TM; ++i) load_idx(0, i);
+#pragma unroll
+    for (int s = 0; s < 3; ++s)
+        if (s < stages)
+#pragma unroll
+            for (int q = 0; q < B_LOADS; ++q) load_b(s, q);
+    wait_loads<0>();
+    __syncthreads();
+    uint32_t wcur[TM][4], wnext[TM][4];
+    read_idx(wcur);
+    __syncthreads();  // every lane has its words before the buffer is refilled
+    if (supers > 1) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) load_idx(1, i);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) load_operand(0, 0, 0, 0, wcur, r);
+
+    // One stage s.  SB = s % 4 (ring buffer), SP = s % 2 (stage within the super-stage).
+    // FULL = steady state: stage s+3 exists, and in the second stage of a super-stage the
+    // super-stage after next exists, so nothing in the body is conditional.
+    auto run_stage = [&](int s, auto sb_c, auto full) {
+        constexpr int SB = decltype(sb_c)::value;
+        constexpr int SP = SB & 1;
+        constexpr bool FULL = decltype(full)::value;
+        const int u = s >> 1;
+        const bool do_fetch = FULL || s + 3 < stages;
+        const bool do_idx = SP == 1 && (FULL || u + 2 < supers);
+#pragma unroll
+        for (int j = 0; j < KSTEPS; ++j) {
+            // second stage of a super-stage: pick up the next super-stage's index words (their
+            // loads were issued a super-stage ago and awaited at the end of the previous stage;
+            // past the last super-stage this reads stale, unused data)
+            if (SP == 1 && j == 2) read_idx(wnext);
+            // 8 groups of two MFMAs; behind each group two LDS reads for the next step (after the
+            // last step: the first step of the next stage) and at most one load.
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = 2 * g; q < 2 * g + 2; ++q)
+                    acc[q >> 2][q & 3] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(
+                        a[j & 1][q >> 2], b[j & 1][q & 3], acc[q >> 2][q & 3], apos[j & 1][q >> 2], 0,
+                        0);
+                if (j + 1 < KSTEPS) {
+                    load_operand((j + 1) & 1, SB, SP, j + 1, wcur, 2 * g);
+                    load_operand((j + 1) & 1, SB, SP, j + 1, wcur, 2 * g + 1);
+                } else if (g < 4) {
+                    // first half of the last step only, so that the reads have returned when the
+                    // barrier waits for the LDS counter
+#pragma unroll
+                    for (int r = 4 * g; r < 4 * g + 4; ++r) {
+                        if (SP == 0)
+                            load_operand(0, (SB + 1) % NBUF, 1, 0, wcur, r);
+                        else
+                            load_operand(0, (SB + 1) % NBUF, 0, 0, wnext, r);
+                    }
+                }
+                if (do_fetch && (g == 1 || g == 5)) load_b(s + 3, 2 * j + (g == 5));
+                // the index buffer is free once read_idx above has returned (step 2); refill it in
+                // step 3 with the super-stage after next
+                if (do_idx && j == 3 && g < I_LOADS && g != 1) load_idx(u + 2, g);
+                if (do_idx && j == 3 && g == 6) load_idx(u + 2, 1);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // Before the barrier everything issued before this stage must have landed (stage s+2 is
+        // read from the end of stage s+1 on); this stage's own loads stay in flight.
+        if (FULL) {
+            if (SP == 1)
+                wait_loads<B_LOADS + I_LOADS>();
+            else
+                wait_loads<B_LOADS>();
+        } else {
+            wait_loads<0>();
+        }
+        __syncthreads();
+        if (SP == 1) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int d = 0; d < 4; ++d) wcur[i][d] = wnext[i][d];
+        }
+    };
+    using B0 = std::integral_constant<int, 0>;
+    using B1 = std::integral_constant<int, 1>;
+    using B2 = std::integral_constant<int, 2>;
+    using B3 = std::integral_constant<int, 3>;
+
+    // steady state while the last stage of the group of four still has stage s+3 and super-stage
+    // u+2 ahead of it: (s+3) + 3 < stages and (s+3)/2 + 2 < supers
+    int s = 0;
+    for (; s + 6 < stages && (s + 3) / 2 + 2 < supers; s += 4) {
+        run_stage(s + 0, B0{}, std::true_type{});
+        run_stage(s + 1, B1{}, std::true_type{});
+        run_stage(s + 2, B2{}, std::true_type{});
+        run_stage(s + 3, B3{}, std::true_type{});
+    }
+    for (; s < stages; s += 4) {
+        run_stage(s + 0, B0{}, std::false_type{});
+        run_stage(s + 1, B1{}, std::false_type{});  // stages come in pairs
+        if (s + 2 < stages) {
+            run_stage(s + 2, B2{}, std::false_type{});
+            run_stage(s + 3, B3{}, std::false_type{});
+        }
+    }
+
+    mfma_store_tile<TM>(acc, *scale, bias, M, N, row_base, n0, Y, ldy);
+}
+
+}  // namespace
+
+bool smfmac_supported(int C, int K, const uint8_t* idx) {
+    return K <= 16 && C % 32 == 0 && (reinterpret_cast<uintptr_t>(idx) & 15) == 0;
+}
+
+hipError_t launch_lookup_smfmac_i8(const int8_t* packed, const float* scale, const float* bias, int C,
+                                   int K, int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,
+                                   hipStream_t s) {
+    if (!smfmac_supported(C, K, idx)) return hipErrorInvalidValue;
+    const int Mp = (int)packed_cols(M);
+    const int64_t col_tiles = (M + BN - 1) / BN;  // the packed table is padded to 256 columns
+    const int64_t row_tiles = (N + BM - 1) / BM;
+    const int64_t tiles = row_tiles * col_tiles;
+    const int64_t blocks = (tiles + 7) / 8 * 8;
+    if (blocks > 0x7fffffffLL || row_tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(lookup_smfmac_i8_kernel, dim3((unsigned)blocks), dim3(kMfmaThreads), 0, s,
+                       reinterpret_cast<const uint4*>(packed), scale, bias, C, M, Mp, idx, N, Y, ldy,
+                       (int)row_tiles, tiles);
+    return hipGetLastError();
+}
+
+}  // namespace lutnn

@@ -35,6 +35,12 @@ hipError_t launch_lookup_mfma_i8(const int8_t* packed, const float* scale, const
                                  int K, int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,
                                  hipStream_t s);
 
+// Eq. 4, one-hot contraction on the 2:4 structured-sparse matrix instructions (INT8).
+bool smfmac_supported(int C, int K, const uint8_t* idx);
+hipError_t launch_lookup_smfmac_i8(const int8_t* packed, const float* scale, const float* bias, int C,
+                                   int K, int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,
+                                   hipStream_t s);
+
 // Eq. 2 + Eq. 4 in one kernel.
 bool fused_supported(int C, int K, int V, int M, int dtype);
 hipError_t launch_linear_fused_i8(const float* P, const int8_t* packed, const float* scale,

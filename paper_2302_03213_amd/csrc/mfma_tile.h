@@ -29,6 +29,37 @@ constexpr int kMfmaBN = 256;  // columns per workgroup tile
 constexpr int kMfmaSC = 8;    // codebooks per stage
 constexpr int kMfmaStageVecs = kMfmaSC * kMfmaBN;  // uint4 per stage buffer (32 KiB)
 
+// XCD-aware tile order: consecutive workgroup ids land on different XCDs (8 of them, each with its
+// own L2), so give every XCD a contiguous range of tiles; tiles are ordered column-block major, so
+// the workgroups resident on one XCD walk the same slab of the table.  Returns -1 for padding ids.
+__device__ __forceinline__ int64_t xcd_tile(int64_t tiles) {
+    const int64_t per_xcd = (tiles + 7) / 8;
+    const int64_t t = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    return t < tiles ? t : -1;
+}
+
+// LDS byte offset of a __shared__ object (the low 32 bits of its flat address).
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+    return (uint32_t)reinterpret_cast<uintptr_t>(p);
+}
+// 64 lanes x 16 bytes from global memory straight into LDS at lds_dst + 16 * lane.
+//   sbase: wave-uniform global base;  voff: per-lane byte offset from it.
+// The compiler does not see the LDS write: completion is awaited with wait_loads<N>() before the
+// barrier that publishes the data.  "memory" keeps LDS reads from being folded or moved across.
+__device__ __forceinline__ void dma16(uint32_t lds_dst, const void* sbase, uint32_t voff) {
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %2"
+        :
+        : "s"(lds_dst), "v"(voff), "s"(sbase)
+        : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads() {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
 // One-hot look-up table in LDS: entry k (16 bytes) has byte k = 1 and the rest 0.  Building a
 // lane's A operand is then one shift/mask and one 16-byte LDS read instead of a dozen VALU ops;
 // the 16 entries sit in 64 different banks, so lanes with different k never conflict and lanes
@@ -142,17 +173,17 @@ __device__ __forceinline__ void mfma_lookup_tile(const uint4* __restrict__ packe
 // Dequantise (r = s*q, Sec. 3.3), add the bias and store this wave's tiles.
 // 32x32 accumulator layout: lane -> column l32, register r -> row 8*(r/4) + 4*h + (r%4).
 //   row_base  first row of this wave's row block 0 (row block i starts at row_base + 32*i)
+//   col_base  first column of this wave's column tile 0
 template <int TM>
 __device__ __forceinline__ void mfma_store_tile(const v16i (&acc)[TM][4], float s,
                                                 const float* __restrict__ bias, int M, int64_t N,
-                                                int64_t row_base, int n0, float* __restrict__ Y,
+                                                int64_t row_base, int col_base, float* __restrict__ Y,
                                                 int64_t ldy) {
     const int lane = threadIdx.x & 63;
-    const int wn = (threadIdx.x >> 6) & 1;
     const int l32 = lane & 31, h = lane >> 5;
 #pragma unroll
     for (int tn = 0; tn < 4; ++tn) {
-        const int col = n0 + wn * 128 + tn * 32 + l32;
+        const int col = col_base + tn * 32 + l32;
         if (col >= M) continue;
         const float bv = bias ? bias[col] : 0.f;
 #pragma unroll

@@ -104,6 +104,10 @@ def test_host_validation_rejects_bad_arguments_before_any_launch(lut):
                         lut.VARIANT_MFMA, None), "LUTNN_E_ALIGN"),
         (L.lutnn_lookup(ctypes.byref(_layer(lut, K=32)), IDX, 4, Y, 8, lut.VARIANT_MFMA, None),
          "LUTNN_E_UNSUPPORTED"),
+        (L.lutnn_lookup(ctypes.byref(ok), IDX, 4, Y, 8, lut.VARIANT_SMFMAC, None),
+         "LUTNN_E_UNSUPPORTED"),  # C = 4 is not a multiple of 32
+        (L.lutnn_lookup(ctypes.byref(_layer(lut, C=64)), vp(0x30004), 4, Y, 8, lut.VARIANT_SMFMAC, None),
+         "LUTNN_E_ALIGN"),
         (L.lutnn_lookup(ctypes.byref(_layer(lut, table_dtype=lut.TABLE_F32)), IDX, 4, Y, 8,
                         lut.VARIANT_MFMA, None), "LUTNN_E_UNSUPPORTED"),
         (L.lutnn_lookup(ctypes.byref(_layer(lut, scale=None)), IDX, 4, Y, 8, lut.VARIANT_LDS, None),
@@ -148,7 +152,7 @@ def test_cost_model_formulas(lut):
     assert c.lut_flops(N, D, M, K, V) == N * D * K + N * M * (D // V)
     assert abs(c.mm_flops(N, D, M) / c.lut_flops(N, D, M, K, V) - c.flops_reduction(M, K, V)) < 1e-9
     # "M = 128, 256 or 512 ... FLOPs can be reduced by 4x when K = 8" (Sec. 4): K-dominated limit
-    assert 3.0 < c.flops_reduction(512, 8, 9) / (512 / (8 + 512 / 9)) * c.flops_reduction(128, 8, 9) < 6.0
+    assert abs(c.flops_reduction(768, 16, 32) - 768 / (16 + 24)) < 1e-12
     assert c.lut_size_bytes(D, M, K, V) == 4 * D * K + D * M * K // V
     assert c.mm_size_bytes(D, M) == 4 * D * M
     assert c.equivalent_flops(16384, 4096, 4096) == 2 * 16384 * 4096 * 4096

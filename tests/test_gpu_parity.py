@@ -146,7 +146,36 @@ def test_lookup_i8_bit_exact(lut, variant, N, C, K, M):
         np.testing.assert_array_equal(got, ref)
 
 
-@pytest.mark.parametrize("variant", ["lds", "mfma"])
+SMFMAC_SHAPES = [
+    # N, C, K, M   (C % 32 == 0)
+    (1, 32, 16, 1), (130, 64, 16, 64), (513, 96, 16, 250), (1025, 384, 16, 513), (700, 32, 7, 100),
+    (512, 160, 16, 128), (300, 128, 1, 40), (2000, 224, 16, 130),
+]
+
+
+@pytest.mark.parametrize("N,C,K,M", SMFMAC_SHAPES)
+def test_lookup_smfmac_bit_exact(lut, N, C, K, M):
+    w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=71 + N + C + M)
+    ol = OracleLayer(w)
+    ol.q = wl.random_table_i8(C, K, M, seed=72 + C)
+    ol.s = np.float32(0.0123)
+    idx = wl.random_indices(N, C, K, seed=73 + N)
+    for with_bias in (True, False):
+        layer = device_layer_from_oracle(lut, ol, with_bias)
+        got = host(lut.lookup(layer, dev(idx), "smfmac"))
+        ref = oracle.lookup_i8(ol.q, ol.s, idx, w.bias if with_bias else None)
+        np.testing.assert_array_equal(got, ref)
+
+
+def test_smfmac_needs_whole_super_stages(lut):
+    w = wl.make_layer("t", 1, 40, 16, 2, 64, "i8", seed=74)
+    layer = device_layer_from_oracle(lut, OracleLayer(w), True)
+    with pytest.raises(lut.LutnnError) as e:
+        lut.lookup(layer, dev(wl.random_indices(10, 40, 16)), "smfmac")
+    assert e.value.name == "LUTNN_E_UNSUPPORTED"
+
+
+@pytest.mark.parametrize("variant", ["lds", "mfma", "smfmac"])
 def test_lookup_i8_extreme_sums_do_not_wrap(lut, variant):
     # all entries +-127 over C = 1536 codebooks (the deepest layer of the BERT workload):
     # 16-bit partial sums would overflow many times over.
@@ -193,13 +222,13 @@ def test_lookup_large_k_uses_global_gather(lut):
 
 
 def test_lookup_output_stride_and_guard_band(lut):
-    N, C, K, M = 100, 16, 16, 70
+    N, C, K, M = 100, 32, 16, 70
     w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=41)
     ol = OracleLayer(w)
     idx = wl.random_indices(N, C, K, seed=42)
     layer = device_layer_from_oracle(lut, ol, True)
     ref = ol.lookup(idx)
-    for variant in ("lds", "mfma"):
+    for variant in ("lds", "mfma", "smfmac"):
         buf = torch.full((N + 8, M + 9), -777.0, dtype=torch.float32, device="cuda")
         lut.lookup(layer, dev(idx), variant, out=buf[4:4 + N, 3:3 + M])
         got = host(buf)
@@ -283,12 +312,12 @@ def test_config1_fc_small_fp32(lut):
 
 
 def test_config2_conv_int8(lut):
-    flips = check_linear(lut, wl.conv_resnet18(0), ["auto", "lds", "mfma", "fused"])
+    flips = check_linear(lut, wl.conv_resnet18(0), ["auto", "lds", "mfma", "smfmac", "fused"])
     print("config 2 near-ties: %d" % flips)
 
 
 def test_config3_bert_ffn_up_int8(lut):
-    flips = check_linear(lut, wl.bert_ffn_up(0), ["auto", "lds", "mfma", "fused"])
+    flips = check_linear(lut, wl.bert_ffn_up(0), ["auto", "lds", "mfma", "smfmac", "fused"])
     print("config 3 near-ties: %d" % flips)
 
 
@@ -316,14 +345,14 @@ def check_sampled_rows(lut, w, variants, n_sample=384, seed=0):
 
 def test_config4_bert_layer_linears_int8(lut):
     for w in wl.bert_layer(0):
-        flips = check_sampled_rows(lut, w, ["auto", "mfma"], n_sample=256)
+        flips = check_sampled_rows(lut, w, ["auto", "mfma", "smfmac"], n_sample=256)
         print("config 4 %s near-ties: %d" % (w.name, flips))
 
 
 def test_config5_fc_large_int8(lut):
     # the benchmark workload, in the launch configuration bench.py times (variant auto)
     w = wl.fc_large(0)
-    flips = check_sampled_rows(lut, w, ["auto", "mfma", "lds", "fused"], n_sample=384)
+    flips = check_sampled_rows(lut, w, ["auto", "smfmac", "mfma", "lds", "fused"], n_sample=384)
     print("config 5 near-ties: %d" % flips)
 
 
@@ -341,7 +370,7 @@ def test_empty_batch_and_determinism(lut):
     w = wl.make_layer("t", 300, 64, 16, 4, 256, "i8", seed=12)
     layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8, bias=dev(w.bias))
     X = dev(w.X)
-    for v in ("lds", "mfma", "fused"):
+    for v in ("lds", "mfma", "smfmac", "fused"):
         assert lut.linear(layer, X[:0], v).shape == (0, 256)
         a = host(lut.linear(layer, X, v))
         b = host(lut.linear(layer, X, v))
