@@ -13,8 +13,11 @@
 //   A positions: bits [2t+1:2t] of the index register = position (0-3) of stored byte t;
 //   B, lane (column l, half h): bytes 0-15 -> k block 2h, bytes 16-31 -> k block 2h + 1;
 //   D: as for the dense 32x32 MFMA.
-// A lane's operand for one codebook with index p is therefore: stored byte 2(p>>2) = 1, position
-// field of that byte = p&3, everything else 0 - read from a 16-entry table in LDS.
+// A lane's operand for one codebook with index p is therefore: stored byte 2(p>>2) = 1 (a 64-bit
+// 1 << 16(p>>2)), position field of that byte = p&3, everything else 0.  The values are built in
+// registers with one 64-bit shift per codebook; the position words of a whole super-stage are
+// looked up (1 KiB table in LDS, indexed by a pair of index bytes) when its index bytes are picked
+// up, off the critical path.
 //
 // Kernel shape.  Workgroup = 4 wavefronts stacked over rows, one per SIMD, output tile 512 rows x
 // 128 columns (each wave 128 x 128, 256 accumulator registers): with the matrix pipe twice as
@@ -50,24 +53,13 @@ constexpr int STAGE_VECS = SC * BN;   // uint4 per stage buffer (32 KiB)
 constexpr int B_LOADS = 8;            // table loads per wave per stage
 constexpr int I_LOADS = TM;           // index loads per wave per super-stage
 
-// Entry p of the operand table: {values lo, values hi, positions (in both halves), 0}.
-__device__ __forceinline__ void init_sparse_lut(uint4* lut) {
-    const int p = threadIdx.x;
-    if (p < 16) {
-        const int g = p >> 2;
-        const uint32_t pos = (uint32_t)(p & 3) << (4 * g);
-        lut[p] = make_uint4(g < 2 ? 1u << (16 * g) : 0u, g >= 2 ? 1u << (16 * (g - 2)) : 0u,
-                            pos | (pos << 16), 0u);
-    }
-}
-
 __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const uint4* __restrict__ packed, const float* __restrict__ scale, const float* __restrict__ bias,
     int C, int M, int Mp, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y,
     int64_t ldy, int row_tiles, int64_t tiles) {
     __shared__ uint4 ring[NBUF * STAGE_VECS];  // 4 x 32 KiB table slabs
     __shared__ uint4 ibuf[4][TM][64];          // [wave][row block][lane]: one super-stage of indices
-    __shared__ uint4 lut[16];
+    __shared__ uint32_t plut[256];             // position words by byte pair, see IdxWords
 
     const int64_t t = xcd_tile(tiles);
     if (t < 0) return;
@@ -80,7 +72,10 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const int l32 = lane & 31, h = lane >> 5;
     const int64_t row_base = m0 + w * WAVE_ROWS;
 
-    init_sparse_lut(lut);
+    {  // position table: entry p0 | p1 << 4
+        const uint32_t p0 = tid & 15, p1 = tid >> 4;
+        plut[tid] = ((p0 & 3) << (4 * (p0 >> 2))) | ((p1 & 3) << (16 + 4 * (p1 >> 2)));
+    }
 
     const int supers = C / 32;  // C % 32 == 0
     const int stages = 2 * supers;
@@ -116,42 +111,51 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // Operand registers, double buffered over MFMA steps.  A step needs 16 LDS reads: read r < 8
-    // is half (r&1) of B tile r>>1, read r >= 8 is codebook (r&1) of A block (r-8)>>1.
-    v4i a[2][TM];
-    int apos[2][TM];
+    // Operand registers, double buffered over MFMA steps.  B: 8 LDS reads per step, read r is
+    // half (r&1) of column tile r>>1.  A: built from the index words, no memory access.
+    typedef unsigned long long u64;
+    typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+    u64x2 a[2][TM];
     v8i b[2][4];
-    uint32_t alo[TM];  // positions of the first codebook, waiting for the second
-    // wq[i][d] = dword d of row block i's 16 index bytes, as byte offsets into the operand table
-    auto load_operand = [&](int set, int sbuf, int sp, int j, const uint32_t (&wq)[TM][4], int r) {
-        if (r < 8) {
-            const int tn = r >> 1, half = r & 1;
-            const uint4 v = ring[sbuf * STAGE_VECS + (8 * half + 2 * j + h) * BN + tn * 32 + l32];
-            b[set][tn][4 * half + 0] = (int)v.x;
-            b[set][tn][4 * half + 1] = (int)v.y;
-            b[set][tn][4 * half + 2] = (int)v.z;
-            b[set][tn][4 * half + 3] = (int)v.w;
-        } else {
-            const int i = (r - 8) >> 1, second = r & 1;
-            const uint32_t word = wq[i][2 * sp + (j >> 1)];
-            const uint32_t off = (word >> (16 * (j & 1) + 8 * second)) & 0xffu;
-            const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(lut) + off);
-            a[set][i][2 * second + 0] = (int)v.x;
-            a[set][i][2 * second + 1] = (int)v.y;
-            if (!second)
-                alo[i] = v.z;
-            else
-                apos[set][i] = (int)((alo[i] & 0xffffu) | (v.z & 0xffff0000u));
-        }
+    auto load_b_operand = [&](int set, int sbuf, int j, int r) {
+        const int tn = r >> 1, half = r & 1;
+        const uint4 v = ring[sbuf * STAGE_VECS + (8 * half + 2 * j + h) * BN + tn * 32 + l32];
+        b[set][tn][4 * half + 0] = (int)v.x;
+        b[set][tn][4 * half + 1] = (int)v.y;
+        b[set][tn][4 * half + 2] = (int)v.z;
+        b[set][tn][4 * half + 3] = (int)v.w;
     };
-    auto read_idx = [&](uint32_t (&wq)[TM][4]) {
+    // Index words of one super-stage, per row block i:
+    //   raw[i][d]  the 16 index bytes as loaded
+    //   pos[i][t]  position word of step t (0..7 over the two stages): codebook 2t in the low
+    //              half, codebook 2t+1 in the high half, each (p & 3) << 4(p >> 2).  Looked up in
+    //              a 256-entry table indexed by the byte pair p0 | p1 << 4.
+    struct IdxWords {
+        uint32_t raw[TM][4];
+        uint32_t pos[TM][8];
+    };
+    auto make_a_operand = [&](int set, int sp, int j, const IdxWords& wq, int i) {
+        // values: stored byte 2(p>>2) = 1, i.e. the 64-bit value 1 << 16(p>>2)
+        const uint32_t word = wq.raw[i][2 * sp + (j >> 1)];
+        const uint32_t s0 = ((word >> (16 * (j & 1))) << 2) & 0x30u;
+        const uint32_t s1 = ((word >> (16 * (j & 1) + 8)) << 2) & 0x30u;
+        a[set][i][0] = (u64)1 << s0;
+        a[set][i][1] = (u64)1 << s1;
+    };
+    auto read_idx = [&](IdxWords& wq) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const uint4 v = ibuf[w][i][lane];
-            wq[i][0] = (v.x & 0x0f0f0f0fu) << 4;  // byte = 16 * index = offset of the table entry
-            wq[i][1] = (v.y & 0x0f0f0f0fu) << 4;
-            wq[i][2] = (v.z & 0x0f0f0f0fu) << 4;
-            wq[i][3] = (v.w & 0x0f0f0f0fu) << 4;
+            const uint32_t raw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                wq.raw[i][d] = raw[d];
+                const uint32_t pair = (raw[d] | (raw[d] >> 4)) << 2;  // bytes 0, 2: (p0 | p1<<4) * 4
+                wq.pos[i][2 * d + 0] = *reinterpret_cast<const uint32_t*>(
+                    reinterpret_cast<const char*>(plut) + (pair & 0x3fcu));
+                wq.pos[i][2 * d + 1] = *reinterpret_cast<const uint32_t*>(
+                    reinterpret_cast<const char*>(plut) + ((pair >> 16) & 0x3fcu));
+            }
         }
     };
 
@@ -165,7 +169,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
             for (int q = 0; q < B_LOADS; ++q) load_b(s, q);
     wait_loads<0>();
     __syncthreads();
-    uint32_t wcur[TM][4], wnext[TM][4];
+    IdxWords wcur, wnext;
     read_idx(wcur);
     __syncthreads();  // every lane has its words before the buffer is refilled
     if (supers > 1) {
@@ -173,7 +177,9 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
         for (int i = 0; i < TM; ++i) load_idx(1, i);
     }
 #pragma unroll
-    for (int r = 0; r < 16; ++r) load_operand(0, 0, 0, 0, wcur, r);
+    for (int r = 0; r < 8; ++r) load_b_operand(0, 0, 0, r);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) make_a_operand(0, 0, 0, wcur, i);
 
     // One stage s.  SB = s % 4 (ring buffer), SP = s % 2 (stage within the super-stage).
     // FULL = steady state: stage s+3 exists, and in the second stage of a super-stage the
@@ -191,28 +197,38 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
             // loads were issued a super-stage ago and awaited at the end of the previous stage;
             // past the last super-stage this reads stale, unused data)
             if (SP == 1 && j == 2) read_idx(wnext);
-            // 8 groups of two MFMAs; behind each group two LDS reads for the next step (after the
-            // last step: the first step of the next stage) and at most one load.
+            // 8 groups of two MFMAs; behind each group one LDS read of a B operand for the next
+            // step (after the last step: the first step of the next stage, in the first four
+            // groups so that the reads have returned when the barrier waits for the LDS counter),
+            // half an A operand, and at most one load.
+            const int tstep = 4 * SP + j;  // step within the super-stage
 #pragma unroll
             for (int g = 0; g < 8; ++g) {
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int q = 2 * g; q < 2 * g + 2; ++q)
-                    acc[q >> 2][q & 3] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(
-                        a[j & 1][q >> 2], b[j & 1][q & 3], acc[q >> 2][q & 3], apos[j & 1][q >> 2], 0,
-                        0);
+                for (int q = 2 * g; q < 2 * g + 2; ++q) {
+                    // column-tile major: the B tiles are read in this order a step earlier, so
+                    // the tile read last is also used last
+                    const int i = q & 3, tn = q >> 2;
+                    const u64x2 av = a[j & 1][i];
+                    const v4i a4 = {(int)(uint32_t)av[0], (int)(uint32_t)(av[0] >> 32),
+                                    (int)(uint32_t)av[1], (int)(uint32_t)(av[1] >> 32)};
+                    acc[i][tn] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(
+                        a4, b[j & 1][tn], acc[i][tn], (int)wcur.pos[i][tstep], 0, 0);
+                }
                 if (j + 1 < KSTEPS) {
-                    load_operand((j + 1) & 1, SB, SP, j + 1, wcur, 2 * g);
-                    load_operand((j + 1) & 1, SB, SP, j + 1, wcur, 2 * g + 1);
-                } else if (g < 4) {
-                    // first half of the last step only, so that the reads have returned when the
-                    // barrier waits for the LDS counter
-#pragma unroll
-                    for (int r = 4 * g; r < 4 * g + 4; ++r) {
+                    load_b_operand((j + 1) & 1, SB, j + 1, g);
+                    if (g & 1) make_a_operand((j + 1) & 1, SP, j + 1, wcur, g >> 1);
+                } else {
+                    if (g < 4) {
+                        load_b_operand(0, (SB + 1) % NBUF, 0, 2 * g);
+                        load_b_operand(0, (SB + 1) % NBUF, 0, 2 * g + 1);
+                    }
+                    if (g & 1) {
                         if (SP == 0)
-                            load_operand(0, (SB + 1) % NBUF, 1, 0, wcur, r);
+                            make_a_operand(0, 1, 0, wcur, g >> 1);
                         else
-                            load_operand(0, (SB + 1) % NBUF, 0, 0, wnext, r);
+                            make_a_operand(0, 0, 0, wnext, g >> 1);
                     }
                 }
                 if (do_fetch && (g == 1 || g == 5)) load_b(s + 3, 2 * j + (g == 5));
@@ -234,12 +250,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
             wait_loads<0>();
         }
         __syncthreads();
-        if (SP == 1) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int d = 0; d < 4; ++d) wcur[i][d] = wnext[i][d];
-        }
+        if (SP == 1) wcur = wnext;
     };
     using B0 = std::integral_constant<int, 0>;
     using B1 = std::integral_constant<int, 1>;
