@@ -31,6 +31,13 @@
 // lookup_mfma.hip for the reasoning behind each of these choices; this kernel has the same
 // structure with a different tile and operand format.
 //
+// Tiles are streamed: when a whole number of 4-stage ring turns fits (C % 64 == 0) the launch has
+// one workgroup per compute unit and each workgroup walks several output tiles as ONE continuous
+// stage stream - the last three stages of a tile already fetch the first three stages of the next
+// one, so there is no pipeline fill per tile, and the stores of a finished tile drain while the
+// next tile computes (with one wave per SIMD and all workgroups in step, a separate store phase
+// per tile would leave the matrix pipes idle about a sixth of the time).
+//
 // Needs C % 32 == 0 and a 16-byte aligned idx.
 #include <type_traits>
 
@@ -52,6 +59,7 @@ constexpr int KSTEPS = 4;             // MFMA steps per stage, 4 codebooks each
 constexpr int STAGE_VECS = SC * BN;   // uint4 per stage buffer (32 KiB)
 constexpr int B_LOADS = 8;            // table loads per wave per stage
 constexpr int I_LOADS = TM;           // index loads per wave per super-stage
+constexpr int kComputeUnits = 256;    // MI355X: 8 XCDs x 32 CUs
 
 __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const uint4* __restrict__ packed, const float* __restrict__ scale, const float* __restrict__ bias,
@@ -61,47 +69,75 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     __shared__ uint4 ibuf[4][TM][64];          // [wave][row block][lane]: one super-stage of indices
     __shared__ uint32_t plut[256];             // position words by byte pair, see IdxWords
 
-    const int64_t t = xcd_tile(tiles);
-    if (t < 0) return;
-    const int n0 = (int)(t / row_tiles) * BN;
-    const int64_t m0 = (t % row_tiles) * BM;
-
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform
     const int l32 = lane & 31, h = lane >> 5;
-    const int64_t row_base = m0 + w * WAVE_ROWS;
+
+    // XCD-aware tile schedule: consecutive workgroup ids land on different XCDs (8 of them, each
+    // with its own L2).  XCD x owns the contiguous tile range [x*per_xcd, (x+1)*per_xcd), tiles are
+    // ordered column-block major, and the workgroups of the XCD take its tiles round robin, so at
+    // any time they walk the same slab of the table.
+    const int64_t per_xcd = (tiles + 7) / 8;
+    const int wg_per_xcd = gridDim.x >> 3;
+    const int64_t xcd_end = min(((int64_t)(blockIdx.x & 7) + 1) * per_xcd, tiles);
+    int64_t t = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (t >= xcd_end) return;
+
+    // Per-tile addressing.  Indices of super-stage u: lane (row l32 of block i, half h) gets bytes
+    // [32u + 16h, +16); rows >= N re-read row N-1 (their results are never stored).
+    struct Tile {
+        int n0;
+        int64_t m0;
+        const uint4* tsrc;    // packed + n0 (wave-uniform)
+        const uint8_t* isrc;  // idx + m0 * C (wave-uniform)
+        uint32_t ioff[TM];    // per-lane byte offset of the lane's index bytes from isrc
+    };
+    auto setup_tile = [&](int64_t tt, Tile& T) {
+        T.n0 = (int)(tt / row_tiles) * BN;
+        T.m0 = (tt % row_tiles) * BM;
+        T.tsrc = packed + T.n0;
+        T.isrc = idx + T.m0 * C;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            int64_t row = w * WAVE_ROWS + i * 32 + l32;
+            if (T.m0 + row >= N) row = N - 1 - T.m0;
+            T.ioff[i] = (uint32_t)(row * C + 16 * h);
+        }
+    };
+    Tile cur, nxt;
+    setup_tile(t, cur);
+    bool has_next = t + wg_per_xcd < xcd_end;
+    setup_tile(has_next ? t + wg_per_xcd : t, nxt);
+
+    const int supers = C / 32;  // C % 32 == 0
+    const int stages = 2 * supers;
 
     {  // position table: entry p0 | p1 << 4
         const uint32_t p0 = tid & 15, p1 = tid >> 4;
         plut[tid] = ((p0 & 3) << (4 * (p0 >> 2))) | ((p1 & 3) << (16 + 4 * (p1 >> 2)));
     }
 
-    const int supers = C / 32;  // C % 32 == 0
-    const int stages = 2 * supers;
-
     // ---- load issue.  Slot g of stage s = 2u + s' holds codebook 32u + 16(g>>3) + 8s' + (g&7).
     // Wave w copies slots 4w .. 4w+3, both 64-column halves: load q -> slot 4w + (q>>1), half q&1.
+    // Stage / super-stage numbers past the end of the tile address the next tile of the stream.
     const uint32_t lane16 = lane * 16;
     const uint32_t ring0 = lds_offset(ring);
     auto load_b = [&](int s, int q) {
+        const bool in_cur = s < stages;
+        const uint4* src = in_cur ? cur.tsrc : nxt.tsrc;
+        if (!in_cur) s -= stages;
         const int g = 4 * w + (q >> 1);
         const int c = 32 * (s >> 1) + 16 * (g >> 3) + 8 * (s & 1) + (g & 7);
         dma16(ring0 + ((s & 3) * STAGE_VECS + g * BN + 64 * (q & 1)) * 16,
-              packed + (size_t)c * Mp + n0 + 64 * (q & 1), lane16);
+              src + (size_t)c * Mp + 64 * (q & 1), lane16);
     };
-    // Indices of super-stage u: lane (row l32 of block i, half h) gets bytes [32u + 16h, +16).
-    // Rows >= N re-read row N-1 (their results are never stored).
-    const uint8_t* __restrict__ isrc = idx + m0 * C;  // wave-uniform
-    uint32_t ioff[TM];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        int64_t row = w * WAVE_ROWS + i * 32 + l32;
-        if (m0 + row >= N) row = N - 1 - m0;
-        ioff[i] = (uint32_t)(row * C + 16 * h);
-    }
     const uint32_t ibuf0 = lds_offset(ibuf) + w * TM * 64 * 16;
-    auto load_idx = [&](int u, int i) { dma16(ibuf0 + i * 64 * 16, isrc + 32 * u, ioff[i]); };
+    auto load_idx = [&](int u, int i) {
+        const bool in_cur = u < supers;
+        dma16(ibuf0 + i * 64 * 16, (in_cur ? cur.isrc : nxt.isrc) + 32 * (in_cur ? u : u - supers),
+              in_cur ? cur.ioff[i] : nxt.ioff[i]);
+    };
 
     v16i acc[TM][4];
 #pragma unroll
@@ -172,7 +208,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     IdxWords wcur, wnext;
     read_idx(wcur);
     __syncthreads();  // every lane has its words before the buffer is refilled
-    if (supers > 1) {
+    if (supers > 1 || has_next) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) load_idx(1, i);
     }
@@ -257,25 +293,41 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     using B2 = std::integral_constant<int, 2>;
     using B3 = std::integral_constant<int, 3>;
 
-    // steady state while the last stage of the group of four still has stage s+3 and super-stage
-    // u+2 ahead of it: (s+3) + 3 < stages and (s+3)/2 + 2 < supers
-    int s = 0;
-    for (; s + 6 < stages && (s + 3) / 2 + 2 < supers; s += 4) {
-        run_stage(s + 0, B0{}, std::true_type{});
-        run_stage(s + 1, B1{}, std::true_type{});
-        run_stage(s + 2, B2{}, std::true_type{});
-        run_stage(s + 3, B3{}, std::true_type{});
-    }
-    for (; s < stages; s += 4) {
-        run_stage(s + 0, B0{}, std::false_type{});
-        run_stage(s + 1, B1{}, std::false_type{});  // stages come in pairs
-        if (s + 2 < stages) {
-            run_stage(s + 2, B2{}, std::false_type{});
-            run_stage(s + 3, B3{}, std::false_type{});
+    // The stage stream.  A group of four stages runs unconditionally (FULL) while its last stage
+    // still has stage s+3 and super-stage u+2 ahead of it - in this tile, or in the next one when
+    // the workgroup streams on (only launched when stages % 4 == 0 and supers >= 2, so that the
+    // ring phase and the index look-ahead carry over).
+    const float sc = *scale;
+    for (;;) {
+        int s = 0;
+        for (; s < stages && (has_next || (s + 6 < stages && (s + 3) / 2 + 2 < supers)); s += 4) {
+            run_stage(s + 0, B0{}, std::true_type{});
+            run_stage(s + 1, B1{}, std::true_type{});
+            run_stage(s + 2, B2{}, std::true_type{});
+            run_stage(s + 3, B3{}, std::true_type{});
         }
+        for (; s < stages; s += 4) {
+            run_stage(s + 0, B0{}, std::false_type{});
+            run_stage(s + 1, B1{}, std::false_type{});  // stages come in pairs
+            if (s + 2 < stages) {
+                run_stage(s + 2, B2{}, std::false_type{});
+                run_stage(s + 3, B3{}, std::false_type{});
+            }
+        }
+        mfma_store_tile<TM>(acc, sc, bias, M, N, cur.m0 + w * WAVE_ROWS, cur.n0, Y, ldy);
+        if (!has_next) break;
+        // next tile: its first stages and index words are already in LDS / registers
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+        t += wg_per_xcd;
+        cur = nxt;
+        has_next = t + wg_per_xcd < xcd_end;
+        if (has_next) setup_tile(t + wg_per_xcd, nxt);
     }
-
-    mfma_store_tile<TM>(acc, *scale, bias, M, N, row_base, n0, Y, ldy);
 }
 
 }  // namespace
@@ -292,8 +344,11 @@ hipError_t launch_lookup_smfmac_i8(const int8_t* packed, const float* scale, con
     const int64_t col_tiles = (M + BN - 1) / BN;  // the packed table is padded to 256 columns
     const int64_t row_tiles = (N + BM - 1) / BM;
     const int64_t tiles = row_tiles * col_tiles;
-    const int64_t blocks = (tiles + 7) / 8 * 8;
+    int64_t blocks = (tiles + 7) / 8 * 8;
     if (blocks > 0x7fffffffLL || row_tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    // Stream several tiles per workgroup when the ring phase carries over from tile to tile:
+    // one workgroup per compute unit (the kernel's LDS footprint allows only one anyway).
+    if (C % 64 == 0 && blocks > kComputeUnits) blocks = kComputeUnits;
     hipLaunchKernelGGL(lookup_smfmac_i8_kernel, dim3((unsigned)blocks), dim3(kMfmaThreads), 0, s,
                        reinterpret_cast<const uint4*>(packed), scale, bias, C, M, Mp, idx, N, Y, ldy,
                        (int)row_tiles, tiles);
