@@ -15,9 +15,8 @@
 //   D: as for the dense 32x32 MFMA.
 // A lane's operand for one codebook with index p is therefore: stored byte 2(p>>2) = 1 (a 64-bit
 // 1 << 16(p>>2)), position field of that byte = p&3, everything else 0.  The values are built in
-// registers with one 64-bit shift per codebook; the position words of a whole super-stage are
-// looked up (1 KiB table in LDS, indexed by a pair of index bytes) when its index bytes are picked
-// up, off the critical path.
+// registers with one 64-bit shift per codebook; the position words are looked up in a 1 KiB table
+// in LDS indexed by a pair of index bytes.
 //
 // Kernel shape.  Workgroup = 4 wavefronts stacked over rows, one per SIMD, output tile 512 rows x
 // 128 columns (each wave 128 x 128, 256 accumulator registers): with the matrix pipe twice as
@@ -26,17 +25,27 @@
 // 4 codebooks; step j of stage s' of super-stage u uses codebooks 32u + 16h + 8s' + 2j + {0,1} for
 // lane half h, so a lane's 16 index bytes per super-stage are contiguous.  Table slabs (32 KiB
 // per stage) and index bytes go global -> LDS directly (global_load_lds_dwordx4 from inline
-// assembly, explicit vmcnt waits) three stages ahead through a ring of four stage buffers; the
-// operands of the next step are read from LDS between the MFMAs of the current one.  See
-// lookup_mfma.hip for the reasoning behind each of these choices; this kernel has the same
-// structure with a different tile and operand format.
+// assembly, explicit vmcnt waits) three stages ahead through a ring of four stage buffers.
+//
+// Instruction schedule.  A wave issues in order, and the next SMFMAC cannot issue before the
+// previous one has left the pipe (32 cycles, about 8 issue slots).  Whatever sits between two
+// SMFMACs beyond ~6 instructions therefore delays the matrix pipe, and whatever is NOT placed
+// between two SMFMACs wastes slots that were free.  So the stage body is written as 64 slots of
+// "one SMFMAC + its share of the housekeeping", pinned with scheduling barriers, and every piece
+// of housekeeping is cut into units of at most ~5 instructions with a fixed slot:
+//   even slots          one LDS read of a B operand for the next step
+//   slots 2, 10         one table load (DMA) for stage s+3; slot 12 advances the load pointer
+//   slots 1, 5, 9, 13   half of the work on one 4-byte index word (position-word look-ups, the
+//                       shift word the A values are built from) - 32 such halves per super-stage,
+//                       done in the order their results are needed
+//   slots 3, 7, 11, 15  the two A values of one row block for the next step
+//   stage 1 of a super-stage, step 0: the four 16-byte LDS reads of the next super-stage's
+//                       index bytes; step 3: the loads (DMA) of the super-stage after that
 //
 // Tiles are streamed: when a whole number of 4-stage ring turns fits (C % 64 == 0) the launch has
 // one workgroup per compute unit and each workgroup walks several output tiles as ONE continuous
 // stage stream - the last three stages of a tile already fetch the first three stages of the next
-// one, so there is no pipeline fill per tile, and the stores of a finished tile drain while the
-// next tile computes (with one wave per SIMD and all workgroups in step, a separate store phase
-// per tile would leave the matrix pipes idle about a sixth of the time).
+// one, so there is no pipeline fill per tile.
 //
 // Needs C % 32 == 0 and a 16-byte aligned idx.
 #include <type_traits>
@@ -61,6 +70,18 @@ constexpr int B_LOADS = 8;            // table loads per wave per stage
 constexpr int I_LOADS = TM;           // index loads per wave per super-stage
 constexpr int kComputeUnits = 256;    // MI355X: 8 XCDs x 32 CUs
 
+// 64 lanes x 16 bytes global -> LDS at (lds_base + LDS_IMM) + 16 * lane; see dma16().
+template <int LDS_IMM>
+__device__ __forceinline__ void dma16_at(uint32_t lds_base, const void* sbase, uint32_t voff) {
+    asm volatile(
+        "s_add_u32 m0, %0, %3\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %2"
+        :
+        : "s"(lds_base), "v"(voff), "s"(sbase), "n"(LDS_IMM)
+        : "memory", "m0", "scc");
+}
+
 __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const uint4* __restrict__ packed, const float* __restrict__ scale, const float* __restrict__ bias,
     int C, int M, int Mp, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y,
@@ -83,35 +104,40 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const int64_t xcd_end = min(((int64_t)(blockIdx.x & 7) + 1) * per_xcd, tiles);
     int64_t t = (int64_t)(blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (t >= xcd_end) return;
-
-    // Per-tile addressing.  Indices of super-stage u: lane (row l32 of block i, half h) gets bytes
-    // [32u + 16h, +16); rows >= N re-read row N-1 (their results are never stored).
-    struct Tile {
-        int n0;
-        int64_t m0;
-        const uint4* tsrc;    // packed + n0 (wave-uniform)
-        const uint8_t* isrc;  // idx + m0 * C (wave-uniform)
-        uint32_t ioff[TM];    // per-lane byte offset of the lane's index bytes from isrc
-    };
-    auto setup_tile = [&](int64_t tt, Tile& T) {
-        T.n0 = (int)(tt / row_tiles) * BN;
-        T.m0 = (tt % row_tiles) * BM;
-        T.tsrc = packed + T.n0;
-        T.isrc = idx + T.m0 * C;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            int64_t row = w * WAVE_ROWS + i * 32 + l32;
-            if (T.m0 + row >= N) row = N - 1 - T.m0;
-            T.ioff[i] = (uint32_t)(row * C + 16 * h);
-        }
-    };
-    Tile cur, nxt;
-    setup_tile(t, cur);
     bool has_next = t + wg_per_xcd < xcd_end;
-    setup_tile(has_next ? t + wg_per_xcd : t, nxt);
 
     const int supers = C / 32;  // C % 32 == 0
     const int stages = 2 * supers;
+
+    // ---- the two streams.  Compute works on tile (ct_n0, ct_m0); the loads run three stages
+    // ahead and move on to the next tile of this workgroup while the current one is still being
+    // computed.  Load state: bp = address of the next table row this wave loads (rows of 128
+    // columns x 16 B at packed + n0, one per codebook; the wave owns rows 16(w>>1) + 4(w&1) + 0..3
+    // of each stage), ip = index bytes of the next super-stage to load (row 0 of the tile), fioff
+    // = per-lane byte offset of the lane's index bytes: lane (row l32 of block i, half h) gets
+    // bytes [32u + 16h, +16) of its row; rows >= N re-read row N-1 (never stored).
+    int ct_n0, ft_n0;
+    int64_t ct_m0, ft_m0;
+    const char* bp;
+    const uint8_t* ip;
+    uint32_t fioff[TM];
+    const uint32_t rs1 = (uint32_t)Mp * 16u;  // bytes from one codebook's row to the next
+    const int row0 = 16 * (w >> 1) + 4 * (w & 1);
+    auto aim_loads_at = [&](int64_t tt) {
+        ft_n0 = (int)(tt / row_tiles) * BN;
+        ft_m0 = (tt % row_tiles) * BM;
+        bp = reinterpret_cast<const char*>(packed + ft_n0) + (size_t)row0 * rs1;
+        ip = idx + ft_m0 * C;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            int64_t row = w * WAVE_ROWS + i * 32 + l32;
+            if (ft_m0 + row >= N) row = N - 1 - ft_m0;
+            fioff[i] = (uint32_t)(row * C + 16 * h);
+        }
+    };
+    aim_loads_at(t);
+    ct_n0 = ft_n0;
+    ct_m0 = ft_m0;
 
     {  // position table: entry p0 | p1 << 4
         const uint32_t p0 = tid & 15, p1 = tid >> 4;
@@ -120,23 +146,22 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
 
     // ---- load issue.  Slot g of stage s = 2u + s' holds codebook 32u + 16(g>>3) + 8s' + (g&7).
     // Wave w copies slots 4w .. 4w+3, both 64-column halves: load q -> slot 4w + (q>>1), half q&1.
-    // Stage / super-stage numbers past the end of the tile address the next tile of the stream.
     const uint32_t lane16 = lane * 16;
-    const uint32_t ring0 = lds_offset(ring);
-    auto load_b = [&](int s, int q) {
-        const bool in_cur = s < stages;
-        const uint4* src = in_cur ? cur.tsrc : nxt.tsrc;
-        if (!in_cur) s -= stages;
-        const int g = 4 * w + (q >> 1);
-        const int c = 32 * (s >> 1) + 16 * (g >> 3) + 8 * (s & 1) + (g & 7);
-        dma16(ring0 + ((s & 3) * STAGE_VECS + g * BN + 64 * (q & 1)) * 16,
-              src + (size_t)c * Mp + 64 * (q & 1), lane16);
+    const uint32_t lane16_hi = lane * 16 + 1024;  // second 64-column half of a row
+    const uint32_t ring_w = lds_offset(ring) + 4 * w * BN * 16;
+    const uint32_t ibuf_w = lds_offset(ibuf) + w * TM * 64 * 16;
+    auto load_b = [&](auto fb_c, auto q_c) {  // load q of the stage that goes to ring buffer FB
+        constexpr int FB = decltype(fb_c)::value, Q = decltype(q_c)::value;
+        dma16_at<(FB * STAGE_VECS + (Q >> 1) * BN + 64 * (Q & 1)) * 16>(ring_w, bp, (Q & 1) ? lane16_hi : lane16);
     };
-    const uint32_t ibuf0 = lds_offset(ibuf) + w * TM * 64 * 16;
-    auto load_idx = [&](int u, int i) {
-        const bool in_cur = u < supers;
-        dma16(ibuf0 + i * 64 * 16, (in_cur ? cur.isrc : nxt.isrc) + 32 * (in_cur ? u : u - supers),
-              in_cur ? cur.ioff[i] : nxt.ioff[i]);
+    auto load_idx = [&](auto i_c) {
+        constexpr int I = decltype(i_c)::value;
+        dma16_at<I * 64 * 16>(ibuf_w, ip, fioff[I]);
+    };
+    // after the four rows of a stage: on to the rows of the next stage (+8 codebooks within a
+    // super-stage, +24 to the next super-stage)
+    auto next_stage_rows = [&](int sp_of_loaded_stage) {
+        bp += (sp_of_loaded_stage == 0) ? 5 * (size_t)rs1 : 21 * (size_t)rs1;
     };
 
     v16i acc[TM][4];
@@ -161,61 +186,105 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
         b[set][tn][4 * half + 2] = (int)v.z;
         b[set][tn][4 * half + 3] = (int)v.w;
     };
-    // Index words of one super-stage, per row block i:
-    //   raw[i][d]  the 16 index bytes as loaded
+    // Index words of one super-stage, per row block i and 4-byte word d (codebooks 4d .. 4d+3 of
+    // the lane's 16):
+    //   sh[i][d]   first the index bytes as loaded; after the word's second half-operation, byte
+    //              b = 16 (p >> 2) of codebook 4d + b: the shift that builds its A values
     //   pos[i][t]  position word of step t (0..7 over the two stages): codebook 2t in the low
     //              half, codebook 2t+1 in the high half, each (p & 3) << 4(p >> 2).  Looked up in
     //              a 256-entry table indexed by the byte pair p0 | p1 << 4.
     struct IdxWords {
-        uint32_t raw[TM][4];
+        uint32_t sh[TM][4];
         uint32_t pos[TM][8];
     };
-    auto make_a_operand = [&](int set, int sp, int j, const IdxWords& wq, int i) {
-        // values: stored byte 2(p>>2) = 1, i.e. the 64-bit value 1 << 16(p>>2)
-        const uint32_t word = wq.raw[i][2 * sp + (j >> 1)];
-        const uint32_t s0 = ((word >> (16 * (j & 1))) << 2) & 0x30u;
-        const uint32_t s1 = ((word >> (16 * (j & 1) + 8)) << 2) & 0x30u;
-        a[set][i][0] = (u64)1 << s0;
-        a[set][i][1] = (u64)1 << s1;
+    auto read_ibuf = [&](IdxWords& wq, int i) {
+        const uint4 v = ibuf[w][i][lane];
+        wq.sh[i][0] = v.x;
+        wq.sh[i][1] = v.y;
+        wq.sh[i][2] = v.z;
+        wq.sh[i][3] = v.w;
     };
-    auto read_idx = [&](IdxWords& wq) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const uint4 v = ibuf[w][i][lane];
-            const uint32_t raw[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                wq.raw[i][d] = raw[d];
-                const uint32_t pair = (raw[d] | (raw[d] >> 4)) << 2;  // bytes 0, 2: (p0 | p1<<4) * 4
-                wq.pos[i][2 * d + 0] = *reinterpret_cast<const uint32_t*>(
-                    reinterpret_cast<const char*>(plut) + (pair & 0x3fcu));
-                wq.pos[i][2 * d + 1] = *reinterpret_cast<const uint32_t*>(
-                    reinterpret_cast<const char*>(plut) + ((pair >> 16) & 0x3fcu));
-            }
+    // Half-operation k = 0..31 of a super-stage's index words: word (i, d) = ((k >> 1) & 3, k >> 3),
+    // first half = position word of codebooks 4d, 4d+1; second half = that of 4d+2, 4d+3, and the
+    // shift word.  Words are finished in the order d = 0, 1, 2, 3, the order the steps use them.
+    uint32_t pair = 0;  // carried from the first half of a word to the second
+    auto plut_at = [&](uint32_t byte_off) {
+        return *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(plut) + byte_off);
+    };
+    auto idx_halfop = [&](IdxWords& wq, int k) {
+        const int d = k >> 3, i = (k >> 1) & 3;
+        if ((k & 1) == 0) {
+            const uint32_t raw = wq.sh[i][d];
+            // bits 2-9 = 4 (p0 | p1 << 4), bits 18-25 = 4 (p2 | p3 << 4): byte offsets into plut
+            pair = (raw << 2) | (raw >> 2);
+            wq.pos[i][2 * d + 0] = plut_at(pair & 0x3fcu);
+        } else {
+            wq.pos[i][2 * d + 1] = plut_at((pair >> 16) & 0x3fcu);
+            wq.sh[i][d] = (wq.sh[i][d] << 2) & 0x30303030u;
         }
     };
+    // A values of row block i for step j of stage sp: stored byte 2(p>>2) = 1, i.e. the 64-bit
+    // value 1 << 16(p>>2); a 64-bit shift takes its amount modulo 64.
+    auto make_a_operand = [&](int set, int sp, int j, const IdxWords& wq, int i) {
+        const uint32_t word = wq.sh[i][2 * sp + (j >> 1)];
+        a[set][i][0] = (u64)1 << ((word >> (16 * (j & 1))) & 63u);
+        a[set][i][1] = (u64)1 << ((word >> (16 * (j & 1) + 8)) & 63u);
+    };
 
-    // ---- prologue: stages 0..2, the indices of super-stage 0 (into registers) and 1 (in flight)
-#pragma unroll
-    for (int i = 0; i < TM; ++i) load_idx(0, i);
-#pragma unroll
-    for (int s = 0; s < 3; ++s)
-        if (s < stages)
-#pragma unroll
-            for (int q = 0; q < B_LOADS; ++q) load_b(s, q);
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+
+    // ---- prologue: stages 0..2 and the indices of super-stage 0 (into registers) and 1 (in
+    // flight); afterwards the load state points at stage 3 / super-stage 2.
+    load_idx(I0{});
+    load_idx(I1{});
+    load_idx(I2{});
+    load_idx(I3{});
+    ip += 32;
+    auto load_stage = [&](auto fb_c) {
+        load_b(fb_c, I0{});
+        load_b(fb_c, I1{});
+        bp += rs1;
+        load_b(fb_c, std::integral_constant<int, 2>{});
+        load_b(fb_c, std::integral_constant<int, 3>{});
+        bp += rs1;
+        load_b(fb_c, std::integral_constant<int, 4>{});
+        load_b(fb_c, std::integral_constant<int, 5>{});
+        bp += rs1;
+        load_b(fb_c, std::integral_constant<int, 6>{});
+        load_b(fb_c, std::integral_constant<int, 7>{});
+    };
+    load_stage(I0{});
+    next_stage_rows(0);
+    load_stage(I1{});
+    next_stage_rows(1);
+    if (stages > 2) {
+        load_stage(I2{});
+        next_stage_rows(0);
+    }
     wait_loads<0>();
     __syncthreads();
-    IdxWords wcur, wnext;
-    read_idx(wcur);
-    __syncthreads();  // every lane has its words before the buffer is refilled
-    if (supers > 1 || has_next) {
+    // Index words ping-pong between wq[0] (even super-stages) and wq[1] (odd ones); four stages
+    // are two super-stages, so the ring phase SB of a stage also fixes which of the two it uses.
+    IdxWords wq[2];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) load_idx(1, i);
+    for (int i = 0; i < TM; ++i) read_ibuf(wq[0], i);
+#pragma unroll
+    for (int k = 0; k < 14; ++k) idx_halfop(wq[0], k);  // the stage loop continues with k = 14
+    __syncthreads();  // every lane has its words before the buffer is refilled
+    if (supers > 1) {
+        load_idx(I0{});
+        load_idx(I1{});
+        load_idx(I2{});
+        load_idx(I3{});
+        ip += 32;
     }
 #pragma unroll
     for (int r = 0; r < 8; ++r) load_b_operand(0, 0, 0, r);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) make_a_operand(0, 0, 0, wcur, i);
+    for (int i = 0; i < TM; ++i) make_a_operand(0, 0, 0, wq[0], i);
 
     // One stage s.  SB = s % 4 (ring buffer), SP = s % 2 (stage within the super-stage).
     // FULL = steady state: stage s+3 exists, and in the second stage of a super-stage the
@@ -223,26 +292,21 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     auto run_stage = [&](int s, auto sb_c, auto full) {
         constexpr int SB = decltype(sb_c)::value;
         constexpr int SP = SB & 1;
+        constexpr int FB = (SB + 3) % NBUF;  // ring buffer of stage s + 3
         constexpr bool FULL = decltype(full)::value;
-        const int u = s >> 1;
+        IdxWords& wcur = wq[SB >> 1];
+        IdxWords& wnext = wq[(SB >> 1) ^ 1];
         const bool do_fetch = FULL || s + 3 < stages;
-        const bool do_idx = SP == 1 && (FULL || u + 2 < supers);
+        const bool do_idx = SP == 1 && (FULL || (s >> 1) + 2 < supers);
+        // stage s + 3 is the first stage of the next tile: the loads move on
+        if (FULL && SB == 1 && s + 3 == stages) aim_loads_at(t + wg_per_xcd);
 #pragma unroll
         for (int j = 0; j < KSTEPS; ++j) {
-            // second stage of a super-stage: pick up the next super-stage's index words (their
-            // loads were issued a super-stage ago and awaited at the end of the previous stage;
-            // past the last super-stage this reads stale, unused data)
-            if (SP == 1 && j == 2) read_idx(wnext);
-            // 8 groups of two MFMAs; behind each group one LDS read of a B operand for the next
-            // step (after the last step: the first step of the next stage, in the first four
-            // groups so that the reads have returned when the barrier waits for the LDS counter),
-            // half an A operand, and at most one load.
             const int tstep = 4 * SP + j;  // step within the super-stage
 #pragma unroll
-            for (int g = 0; g < 8; ++g) {
+            for (int q = 0; q < 16; ++q) {
                 __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int q = 2 * g; q < 2 * g + 2; ++q) {
+                {
                     // column-tile major: the B tiles are read in this order a step earlier, so
                     // the tile read last is also used last
                     const int i = q & 3, tn = q >> 2;
@@ -252,26 +316,64 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
                     acc[i][tn] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(
                         a4, b[j & 1][tn], acc[i][tn], (int)wcur.pos[i][tstep], 0, 0);
                 }
+                // B operands of the next step; after the last step: the first step of the next
+                // stage, in the first eight slots so that the reads have returned when the
+                // barrier waits for the LDS counter
                 if (j + 1 < KSTEPS) {
-                    load_b_operand((j + 1) & 1, SB, j + 1, g);
-                    if (g & 1) make_a_operand((j + 1) & 1, SP, j + 1, wcur, g >> 1);
-                } else {
-                    if (g < 4) {
-                        load_b_operand(0, (SB + 1) % NBUF, 0, 2 * g);
-                        load_b_operand(0, (SB + 1) % NBUF, 0, 2 * g + 1);
+                    if ((q & 1) == 0) load_b_operand((j + 1) & 1, SB, j + 1, q >> 1);
+                } else if (q < 8) {
+                    load_b_operand(0, (SB + 1) % NBUF, 0, q);
+                }
+                // second stage of a super-stage: pick up the next super-stage's index bytes
+                // (their loads were issued a super-stage ago and awaited at the end of the
+                // previous stage; past the last super-stage this reads stale, unused data)
+                if (SP == 1 && j == 0 && (q & 1) == 0 && q < 8) read_ibuf(wnext, q >> 1);
+                // index-word half-operations: 32 per super-stage, one every fourth slot; the
+                // sequence of a super-stage starts in slot 9 of step 0 of the stage before it
+                if ((q & 3) == 1) {
+                    const int n = (4 * SP + j) * 4 + (q >> 2);
+                    idx_halfop(n >= 18 ? wnext : wcur, (n - 18) & 31);
+                }
+                // A values of the next step, one row block at a time
+                if ((q & 3) == 3) {
+                    const int i = q >> 2;
+                    if (j + 1 < KSTEPS)
+                        make_a_operand((j + 1) & 1, SP, j + 1, wcur, i);
+                    else if (SP == 0)
+                        make_a_operand(0, 1, 0, wcur, i);
+                    else
+                        make_a_operand(0, 0, 0, wnext, i);
+                }
+                // table loads of stage s + 3: rows one per step, two halves
+                if (do_fetch) {
+                    if (q == 2) {
+                        if (j == 0) load_b(std::integral_constant<int, FB>{}, I0{});
+                        if (j == 1) load_b(std::integral_constant<int, FB>{}, I2{});
+                        if (j == 2) load_b(std::integral_constant<int, FB>{}, std::integral_constant<int, 4>{});
+                        if (j == 3) load_b(std::integral_constant<int, FB>{}, std::integral_constant<int, 6>{});
                     }
-                    if (g & 1) {
-                        if (SP == 0)
-                            make_a_operand(0, 1, 0, wcur, g >> 1);
+                    if (q == 10) {
+                        if (j == 0) load_b(std::integral_constant<int, FB>{}, I1{});
+                        if (j == 1) load_b(std::integral_constant<int, FB>{}, I3{});
+                        if (j == 2) load_b(std::integral_constant<int, FB>{}, std::integral_constant<int, 5>{});
+                        if (j == 3) load_b(std::integral_constant<int, FB>{}, std::integral_constant<int, 7>{});
+                    }
+                    if (q == 12) {
+                        if (j + 1 < KSTEPS)
+                            bp += rs1;
                         else
-                            make_a_operand(0, 0, 0, wnext, g >> 1);
+                            next_stage_rows(SP ^ 1);  // stage s + 3 has the other parity
                     }
                 }
-                if (do_fetch && (g == 1 || g == 5)) load_b(s + 3, 2 * j + (g == 5));
-                // the index buffer is free once read_idx above has returned (step 2); refill it in
+                // the index buffer is free once its reads (step 0) have returned; refill it in
                 // step 3 with the super-stage after next
-                if (do_idx && j == 3 && g < I_LOADS && g != 1) load_idx(u + 2, g);
-                if (do_idx && j == 3 && g == 6) load_idx(u + 2, 1);
+                if (do_idx && j == 3) {
+                    if (q == 4) load_idx(I0{});
+                    if (q == 6) load_idx(I1{});
+                    if (q == 12) load_idx(I2{});
+                    if (q == 14) load_idx(I3{});
+                    if (q == 15) ip += 32;
+                }
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -286,7 +388,6 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
             wait_loads<0>();
         }
         __syncthreads();
-        if (SP == 1) wcur = wnext;
     };
     using B0 = std::integral_constant<int, 0>;
     using B1 = std::integral_constant<int, 1>;
@@ -314,7 +415,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
                 run_stage(s + 3, B3{}, std::false_type{});
             }
         }
-        mfma_store_tile<TM>(acc, sc, bias, M, N, cur.m0 + w * WAVE_ROWS, cur.n0, Y, ldy);
+        mfma_store_tile<TM>(acc, sc, bias, M, N, ct_m0 + w * WAVE_ROWS, ct_n0, Y, ldy);
         if (!has_next) break;
         // next tile: its first stages and index words are already in LDS / registers
 #pragma unroll
@@ -324,9 +425,9 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
         t += wg_per_xcd;
-        cur = nxt;
+        ct_n0 = ft_n0;
+        ct_m0 = ft_m0;
         has_next = t + wg_per_xcd < xcd_end;
-        if (has_next) setup_tile(t + wg_per_xcd, nxt);
     }
 }
 
@@ -346,6 +447,7 @@ hipError_t launch_lookup_smfmac_i8(const int8_t* packed, const float* scale, con
     const int64_t tiles = row_tiles * col_tiles;
     int64_t blocks = (tiles + 7) / 8 * 8;
     if (blocks > 0x7fffffffLL || row_tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    if ((int64_t)Mp * 16 * 21 > 0xffffffffLL) return hipErrorInvalidValue;  // row strides are 32-bit
     // Stream several tiles per workgroup when the ring phase carries over from tile to tile:
     // one workgroup per compute unit (the kernel's LDS footprint allows only one anyway).
     if (C % 64 == 0 && blocks > kComputeUnits) blocks = kComputeUnits;

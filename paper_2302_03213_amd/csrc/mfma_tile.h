@@ -174,30 +174,77 @@ __device__ __forceinline__ void mfma_lookup_tile(const uint4* __restrict__ packe
 // 32x32 accumulator layout: lane -> column l32, register r -> row 8*(r/4) + 4*h + (r%4).
 //   row_base  first row of this wave's row block 0 (row block i starts at row_base + 32*i)
 //   col_base  first column of this wave's column tile 0
+// The bias values are fetched once, up front, and the stores of a tile that lies wholly inside
+// the matrix are issued without any test or wait in between (a wait on the load counter between
+// stores would wait for the stores before it as well: they share the counter).  For one (row
+// block, register) the four column tiles are written back to back: 4 x 128 contiguous bytes.
+template <int TM, bool BIAS>
+__device__ __forceinline__ void mfma_store_tile_impl(const v16i (&acc)[TM][4], float s,
+                                                     const float* __restrict__ bias, int M, int64_t N,
+                                                     int64_t row_base, int col_base,
+                                                     float* __restrict__ Y, int64_t ldy) {
+    const int lane = threadIdx.x & 63;
+    const int l32 = lane & 31, h = lane >> 5;
+    float bv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (BIAS) {
+#pragma unroll
+        for (int tn = 0; tn < 4; ++tn) {
+            const int col = col_base + tn * 32 + l32;
+            bv[tn] = col < M ? bias[col] : 0.f;
+        }
+        // have the four values here, once, instead of a wait in front of every store
+        asm volatile("" : "+v"(bv[0]), "+v"(bv[1]), "+v"(bv[2]), "+v"(bv[3]));
+    }
+    // wave-uniform: whole tile inside the matrix, and byte offsets within it fit 32 bits
+    const bool interior = row_base + TM * 32 <= N && col_base + 128 <= M && ldy < (1 << 22);
+    if (interior) {
+        // uniform base + 32-bit lane offset; rows advance the uniform part
+        char* __restrict__ base = reinterpret_cast<char*>(Y + row_base * ldy + col_base);
+        const uint32_t voff = (uint32_t)(4 * h * (int)ldy + l32) * 4u;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                char* __restrict__ rowp = base + (int64_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * ldy * 4;
+#pragma unroll
+                for (int tn = 0; tn < 4; ++tn) {
+                    const float a = (float)acc[i][tn][r];
+                    *reinterpret_cast<float*>(rowp + voff + tn * 128) =
+                        BIAS ? __fmaf_rn(a, s, bv[tn]) : __fmul_rn(a, s);
+                }
+            }
+        }
+    } else {
+        float* __restrict__ p = Y + (row_base + 4 * h) * ldy + col_base + l32;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int rr = i * 32 + 8 * (r >> 2) + (r & 3);
+                if (row_base + 4 * h + rr < N) {
+                    float* __restrict__ q = p + (int64_t)rr * ldy;
+#pragma unroll
+                    for (int tn = 0; tn < 4; ++tn) {
+                        if (col_base + tn * 32 + l32 < M) {
+                            const float a = (float)acc[i][tn][r];
+                            q[tn * 32] = BIAS ? __fmaf_rn(a, s, bv[tn]) : __fmul_rn(a, s);
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
 template <int TM>
 __device__ __forceinline__ void mfma_store_tile(const v16i (&acc)[TM][4], float s,
                                                 const float* __restrict__ bias, int M, int64_t N,
                                                 int64_t row_base, int col_base, float* __restrict__ Y,
                                                 int64_t ldy) {
-    const int lane = threadIdx.x & 63;
-    const int l32 = lane & 31, h = lane >> 5;
-#pragma unroll
-    for (int tn = 0; tn < 4; ++tn) {
-        const int col = col_base + tn * 32 + l32;
-        if (col >= M) continue;
-        const float bv = bias ? bias[col] : 0.f;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t row = row_base + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                if (row < N) {
-                    const float a = (float)acc[i][tn][r];
-                    Y[row * ldy + col] = bias ? __fmaf_rn(a, s, bv) : __fmul_rn(a, s);
-                }
-            }
-        }
-    }
+    if (bias)
+        mfma_store_tile_impl<TM, true>(acc, s, bias, M, N, row_base, col_base, Y, ldy);
+    else
+        mfma_store_tile_impl<TM, false>(acc, s, bias, M, N, row_base, col_base, Y, ldy);
 }
 
 }  // namespace lutnn
