@@ -16,6 +16,8 @@
 // 256 biased bytes cannot overflow 16 bits (256*255 < 65536); the partial sums are widened to
 // int32 at least that often and the bias (128 per codebook) is removed in the epilogue, so the
 // result is the exact integer sum.
+#include <type_traits>
+
 #include "lutnn_kernels.h"
 
 namespace lutnn {
@@ -261,6 +263,107 @@ __global__ __launch_bounds__(kThreads) void lookup_global_kernel(
     }
 }
 
+// ------------------------------------------------------------------------- few rows: no staging
+// Staging a K x MT slab per codebook pays off when many rows of a workgroup read it.  With few
+// rows (a batch of a few hundred) the staged grid cannot even fill the chip, and the slab is read
+// from L2 by every row tile anyway.  Here one wavefront owns one row and a run of 256 columns,
+// each lane four consecutive columns, and reads the selected table row straight from global
+// memory (one 4- or 16-byte load per lane and codebook, the wave's loads are contiguous).  The
+// index is wave-uniform (scalar load, four codebooks per dword) and the loads of several
+// codebooks are in flight at once.  Sums run over the codebooks in order, as in the staged
+// kernels.  Needs M % 4 == 0 and a table aligned for the vector load.
+constexpr int kGatherCols = 256;
+
+template <typename TT, bool IDX_DWORD>
+__global__ __launch_bounds__(kThreads) void lookup_gather_kernel(
+    const TT* __restrict__ T, const float* __restrict__ scale, const float* __restrict__ bias, int C,
+    int K, int M, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y, int64_t ldy,
+    int col_chunks) {
+    constexpr bool I8 = sizeof(TT) == 1;
+    typedef typename std::conditional<I8, uint32_t, float4>::type Vec;  // four columns
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t gw = (int64_t)blockIdx.x * kWaves + w;
+    const int64_t row = gw / col_chunks;
+    if (row >= N) return;
+    const int m = (int)(gw % col_chunks) * kGatherCols + lane * 4;
+    if (m >= M) return;  // M % 4 == 0: a lane's four columns are all inside or all outside
+    const uint8_t* __restrict__ irow = idx + row * C;
+    const TT* __restrict__ tcol = T + m;
+
+    float fa[4] = {0.f, 0.f, 0.f, 0.f};
+    int32_t ia[4] = {0, 0, 0, 0};
+    auto add = [&](int c, int k) {
+        k = k < K ? k : K - 1;
+        const Vec v = *reinterpret_cast<const Vec*>(tcol + ((size_t)c * K + k) * M);
+        if constexpr (I8) {
+            ia[0] += (int32_t)(int8_t)(v & 0xffu);
+            ia[1] += (int32_t)(int8_t)((v >> 8) & 0xffu);
+            ia[2] += (int32_t)(int8_t)((v >> 16) & 0xffu);
+            ia[3] += (int32_t)v >> 24;
+        } else {
+            fa[0] += v.x;
+            fa[1] += v.y;
+            fa[2] += v.z;
+            fa[3] += v.w;
+        }
+    };
+    int c = 0;
+    if (IDX_DWORD) {
+        for (; c + 4 <= C; c += 4) {
+            const uint32_t word =
+                __builtin_amdgcn_readfirstlane(*reinterpret_cast<const uint32_t*>(irow + c));
+#pragma unroll
+            for (int b = 0; b < 4; ++b) add(c + b, (int)((word >> (8 * b)) & 0xffu));
+        }
+    }
+    for (; c < C; ++c) add(c, (int)__builtin_amdgcn_readfirstlane((uint32_t)irow[c]));
+
+    float* __restrict__ y = Y + row * ldy + m;
+    float4 out;
+    if constexpr (I8) {
+        const float s = *scale;
+        if (bias) {
+            out = make_float4(__fmaf_rn((float)ia[0], s, bias[m]), __fmaf_rn((float)ia[1], s, bias[m + 1]),
+                              __fmaf_rn((float)ia[2], s, bias[m + 2]), __fmaf_rn((float)ia[3], s, bias[m + 3]));
+        } else {
+            out = make_float4(__fmul_rn((float)ia[0], s), __fmul_rn((float)ia[1], s),
+                              __fmul_rn((float)ia[2], s), __fmul_rn((float)ia[3], s));
+        }
+    } else {
+        out = bias ? make_float4(fa[0] + bias[m], fa[1] + bias[m + 1], fa[2] + bias[m + 2], fa[3] + bias[m + 3])
+                   : make_float4(fa[0], fa[1], fa[2], fa[3]);
+    }
+    y[0] = out.x;
+    y[1] = out.y;
+    y[2] = out.z;
+    y[3] = out.w;
+}
+
+// The staged kernels need at least this many workgroups to be worth their staging.
+constexpr int64_t kMinStagedBlocks = 512;
+
+template <typename TT>
+bool gather_ok(const TT* T, int M, int64_t staged_blocks) {
+    return staged_blocks < kMinStagedBlocks && M % 4 == 0 &&
+           (reinterpret_cast<uintptr_t>(T) & (4 * sizeof(TT) - 1)) == 0;
+}
+
+template <typename TT>
+hipError_t launch_gather(const TT* T, const float* scale, const float* bias, int C, int K, int M,
+                         const uint8_t* idx, int64_t N, float* Y, int64_t ldy, hipStream_t s) {
+    const int col_chunks = (M + kGatherCols - 1) / kGatherCols;
+    const int64_t blocks = (N * col_chunks + kWaves - 1) / kWaves;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if ((C % 4 == 0) && ((reinterpret_cast<uintptr_t>(idx) & 3) == 0))
+        hipLaunchKernelGGL((lookup_gather_kernel<TT, true>), dim3((unsigned)blocks), dim3(kThreads), 0, s,
+                           T, scale, bias, C, K, M, idx, N, Y, ldy, col_chunks);
+    else
+        hipLaunchKernelGGL((lookup_gather_kernel<TT, false>), dim3((unsigned)blocks), dim3(kThreads), 0, s,
+                           T, scale, bias, C, K, M, idx, N, Y, ldy, col_chunks);
+    return hipGetLastError();
+}
+
 constexpr int kLdsBudget = 64 * 1024;
 
 inline bool idx_dword_ok(const uint8_t* idx, int C) {
@@ -287,6 +390,7 @@ hipError_t launch_lookup_lds_i8(const int8_t* T, const float* scale, const float
     const int64_t row_tiles = (N + kRowsPerWaveI8 * kWaves - 1) / (kRowsPerWaveI8 * kWaves);
     const int64_t blocks = row_tiles * col_tiles;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (gather_ok(T, M, blocks)) return launch_gather(T, scale, bias, C, K, M, idx, N, Y, ldy, s);
     const int vec16 = (M % 16 == 0) && ((reinterpret_cast<uintptr_t>(T) & 15) == 0);
     const size_t shmem = (size_t)CC * per_codebook;
     if (idx_dword_ok(idx, C))
@@ -315,6 +419,8 @@ hipError_t launch_lookup_lds_f32(const float* T, const float* bias, int C, int K
     const int64_t row_tiles = (N + kRowsPerWaveF32 * kWaves - 1) / (kRowsPerWaveF32 * kWaves);
     const int64_t blocks = row_tiles * col_tiles;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (gather_ok(T, M, blocks))
+        return launch_gather(T, (const float*)nullptr, bias, C, K, M, idx, N, Y, ldy, s);
     const size_t shmem = (size_t)CC * per_codebook;
     if (idx_dword_ok(idx, C))
         hipLaunchKernelGGL((lookup_lds_f32_kernel<true>), dim3((unsigned)blocks), dim3(kThreads), shmem,

@@ -128,6 +128,8 @@ LOOKUP_SHAPES = [
     # N, C, K, M
     (1, 1, 16, 1), (130, 8, 16, 64), (257, 37, 16, 250), (64, 5, 16, 300), (200, 64, 16, 64),
     (129, 384, 16, 513), (70, 300, 16, 100), (90, 12, 7, 40), (50, 9, 1, 33), (128, 128, 16, 512),
+    # large enough grids for the LDS-staged kernels (few-row problems take the direct gather)
+    (2048, 8, 16, 4096), (1030, 6, 16, 2048),
 ]
 
 
@@ -204,6 +206,24 @@ def test_lookup_f32_within_tolerance(lut, N, C, K, M):
         layer = device_layer_from_oracle(lut, ol, with_bias)
         got = host(lut.lookup(layer, dev(idx), "lds"))
         assert_f32_close(got, oracle.lookup_f32(ol.Tf, idx, w.bias if with_bias else None))
+
+
+def test_lookup_index_matrix_at_odd_address(lut):
+    # idx only byte aligned: the dword / 16-byte index fetches must not be used
+    w = wl.make_layer("t", 1, 32, 16, 2, 128, "i8", seed=35)
+    ol = OracleLayer(w)
+    layer = device_layer_from_oracle(lut, ol, True)
+    for N in (100, 4100):  # direct gather / LDS-staged for the "lds" variant
+        idx = wl.random_indices(N, 32, 16, seed=36 + N)
+        raw = torch.zeros(N * 32 + 1, dtype=torch.uint8, device="cuda")
+        raw[1:] = dev(idx).reshape(-1)
+        view = raw[1:].view(N, 32)
+        ref = ol.lookup(idx)
+        for variant in ("lds", "mfma"):
+            np.testing.assert_array_equal(host(lut.lookup(layer, view, variant)), ref)
+        with pytest.raises(lut.LutnnError) as e:
+            lut.lookup(layer, view, "smfmac")
+        assert e.value.name == "LUTNN_E_ALIGN"
 
 
 def test_lookup_large_k_uses_global_gather(lut):
