@@ -22,8 +22,8 @@ if ROOT not in sys.path:
 # WRITE_SIZE runs, scaled by the same counters on a copy kernel of known size); the summaries
 # are under profiles/.  Keyed by (workload, kernel).  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/lutnn_linear_fc_large.md: fetch 630,149,120 (307,690 KiB raw x 2.0) + write 268,435,456
-    ("fc_large", "lookup_smfmac_i8"): 898584576,
+    # profiles/lutnn_linear_fc_large.md: fetch 629,760,000 (307,500 KiB raw x 2.0) + write 268,435,456
+    ("fc_large", "lookup_smfmac_i8"): 898195456,
     # dense MFMA variant, measured before the sparse kernel became the default:
     # fetch 403,578,922 (197,084 KiB raw x 2.0) + write 268,435,456
     ("fc_large", "lookup_mfma_i8"): 672014378,
@@ -44,8 +44,8 @@ def workload_by_name(name):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="fc_large",
                     choices=["fc_large", "fc_small", "conv_resnet18", "bert_ffn_up", "bert_layer"])
     ap.add_argument("--variant", default="auto", choices=["auto", "lds", "mfma", "smfmac", "fused"])
