@@ -38,6 +38,8 @@ def workload_by_name(name):
     }
     if name == "bert_layer":
         return wl.bert_layer(0)
+    if name == "paper_kv":
+        return wl.paper_kv_space(0)
     return [table[name](0)]
 
 
@@ -47,7 +49,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="fc_large",
-                    choices=["fc_large", "fc_small", "conv_resnet18", "bert_ffn_up", "bert_layer"])
+                    choices=["fc_large", "fc_small", "conv_resnet18", "bert_ffn_up", "bert_layer",
+                             "paper_kv"])
     ap.add_argument("--variant", default="auto", choices=["auto", "lds", "mfma", "smfmac", "fused"])
     ap.add_argument("--cpu-sample-rows", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -113,12 +116,11 @@ def main():
     enc_ms, look_ms, fused_ms = [], [], []
     variant_used = {}
     for (w, layer, Xs, Ys, ws) in dev_layers:
-        fused = args.variant == "fused" or (args.variant == "auto" and w.M <= 256)
+        fused = args.variant == "fused"
         if fused:
             variant_used[w.name] = "fused"
-        elif args.variant == "auto":  # mirrors the library's AUTO rule
-            variant_used[w.name] = "lds" if w.table_dtype != "i8" else (
-                "smfmac" if (w.C % 32 == 0 and w.N > 256) else "mfma")
+        elif args.variant == "auto":  # what the library's AUTO rule picks at this shape
+            variant_used[w.name] = lut.auto_variant(layer, w.N, ws)
         else:
             variant_used[w.name] = args.variant
         e_acc = l_acc = f_acc = 0.0

@@ -146,13 +146,23 @@ LUTNN_API lutnn_status lutnn_lookup(const lutnn_layer* layer, const uint8_t* idx
  *   variant FUSED  one kernel; the indices stay in LDS.  `idx_workspace` is ignored.
  *   variant LDS / MFMA / SMFMAC  lutnn_encode into idx_workspace, then lutnn_lookup with that
  *                  variant.
- *   variant AUTO   picks per shape; may need the workspace.
- *   idx_workspace  [N][C] uint8 device scratch; may be NULL only for FUSED.
+ *   variant AUTO   with a workspace: lutnn_encode, then lutnn_lookup with AUTO (the fastest
+ *                  lookup for the shape); without one: FUSED, if a fused kernel exists.
+ *   idx_workspace  [N][C] uint8 device scratch; may be NULL only for FUSED / AUTO.
  * Errors: as lutnn_encode and lutnn_lookup.
  */
 LUTNN_API lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, int64_t N,
                                     int64_t ldx, float* Y, int64_t ldy, int32_t variant,
                                     uint8_t* idx_workspace, void* stream);
+
+/*
+ * Host: the variant that LUTNN_VARIANT_AUTO stands for in lutnn_lookup(layer, idx, N, ...) - and in
+ * lutnn_linear when `idx` is its workspace - so that callers (and benchmarks) can report which
+ * kernel ran.  Pure function of the descriptor, N and the address of idx; nothing is launched
+ * and nothing dereferenced.  Returns LUTNN_VARIANT_LDS, _MFMA or _SMFMAC; for lutnn_linear with a
+ * NULL workspace AUTO means LUTNN_VARIANT_FUSED instead.  Returns -1 for a NULL layer.
+ */
+LUTNN_API int32_t lutnn_auto_variant(const lutnn_layer* layer, const uint8_t* idx, int64_t N);
 
 /* Host: static name of a status code. */
 LUTNN_API const char* lutnn_status_string(int32_t status);

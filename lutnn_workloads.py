@@ -107,6 +107,23 @@ def bert_layer(seed=0):
             for i, (nm, D, M) in enumerate(shapes)]
 
 
+def paper_kv_space(seed=0):
+    """Layers in the (K, V) settings the paper itself evaluates (Sec. 6.1, Table 2): (16, 32) and
+    (16, 16) for BERT-base linears, (8, 9) for the 3x3 convolution, (16, 4) for a 1x1 convolution
+    (ResNet bottleneck 64 -> 256 channels at 56x56).  INT8 tables."""
+    g = _gen(seed + 100)
+    inp = _normal(g, (1, 64, 56, 56))
+    conv = Workload("conv3x3_64x64_56x56_k8_v9_i8", 3136, 64, 8, 9, 64, "i8", im2col_3x3(inp),
+                    _normal(g, (64, 8, 9)), _normal(g, (576, 64), 0.05), _normal(g, (64,), 0.1))
+    return [
+        make_layer("bert_ffn_up_v32_i8", 4096, 24, 16, 32, 3072, "i8", seed=seed + 101),
+        make_layer("bert_ffn_up_v16_i8", 4096, 48, 16, 16, 3072, "i8", seed=seed + 102),
+        make_layer("bert_ffn_down_v32_i8", 4096, 96, 16, 32, 768, "i8", seed=seed + 103),
+        conv,
+        make_layer("conv1x1_64x256_56x56_v4_i8", 3136, 16, 16, 4, 256, "i8", seed=seed + 104),
+    ]
+
+
 def fc_large(seed=0):
     """Large LUT-FC stress: N=16384, D=4096, M=4096, V=4 (C=1024), K=16, INT8 table (64 MiB)."""
     return make_layer("fc_large_i8", 16384, 1024, 16, 4, 4096, "i8", seed=seed)

@@ -27,8 +27,8 @@ VARIANTS = {"auto": VARIANT_AUTO, "lds": VARIANT_LDS, "mfma": VARIANT_MFMA, "fus
             "smfmac": VARIANT_SMFMAC}
 
 EXPORTS = ["lutnn_table_bytes", "lutnn_packed_bytes", "lutnn_build_table", "lutnn_encode",
-           "lutnn_lookup", "lutnn_linear", "lutnn_status_string", "lutnn_last_error",
-           "lutnn_version"]
+           "lutnn_lookup", "lutnn_linear", "lutnn_auto_variant", "lutnn_status_string",
+           "lutnn_last_error", "lutnn_version"]
 
 
 class LutnnError(RuntimeError):
@@ -51,6 +51,13 @@ def _load():
     if not os.path.exists(path):
         _build.build()  # raises if hipcc is missing or the compile fails
     lib = ctypes.CDLL(path)
+    if not all(hasattr(lib, name) for name in EXPORTS):
+        # a library left over from older sources: unload it, rebuild, load again
+        import _ctypes
+        _ctypes.dlclose(lib._handle)
+        del lib
+        _build.build()
+        lib = ctypes.CDLL(path)
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     lib.lutnn_table_bytes.restype = ctypes.c_size_t
     lib.lutnn_table_bytes.argtypes = [i32, i32, i32, i32]
@@ -64,6 +71,8 @@ def _load():
     lib.lutnn_lookup.argtypes = [ctypes.POINTER(_CLayer), vp, i64, vp, i64, i32, vp]
     lib.lutnn_linear.restype = i32
     lib.lutnn_linear.argtypes = [ctypes.POINTER(_CLayer), vp, i64, i64, vp, i64, i32, vp, vp]
+    lib.lutnn_auto_variant.restype = i32
+    lib.lutnn_auto_variant.argtypes = [ctypes.POINTER(_CLayer), vp, i64]
     lib.lutnn_status_string.restype = ctypes.c_char_p
     lib.lutnn_status_string.argtypes = [i32]
     lib.lutnn_last_error.restype = ctypes.c_char_p
@@ -166,6 +175,12 @@ def lookup(layer, idx, variant="auto", out=None):
     _check(LIB.lutnn_lookup(ctypes.byref(layer.c), _ptr(idx), N, _ptr(out), out.stride(0),
                             _variant(variant), _stream()))
     return out
+
+
+def auto_variant(layer, N, idx=None):
+    """lutnn_auto_variant: name of the lookup variant that "auto" stands for at this shape."""
+    code = LIB.lutnn_auto_variant(ctypes.byref(layer.c), _ptr(idx), N)
+    return {v: k for k, v in VARIANTS.items()}[code]
 
 
 def linear(layer, X, variant="auto", out=None, idx_workspace=None):

@@ -53,6 +53,8 @@ constexpr int64_t kMaxRows = (int64_t)1 << 31;
 int resolve_lookup_variant(const lutnn_layer* L, int variant, const uint8_t* idx, int64_t N) {
     if (variant != LUTNN_VARIANT_AUTO) return variant;
     if (L->table_dtype == LUTNN_TABLE_I8 && L->table_packed && L->K <= 16) {
+        // small problems: rows gathered straight from L2 beat a matrix-core launch
+        if (lutnn::gather_preferred(L->table, 1, L->C, L->M, N)) return LUTNN_VARIANT_LDS;
         // the sparse kernel works on 512-row tiles; below that the dense 256-row tile wastes less
         if (N > 256 && lutnn::smfmac_supported(L->C, L->K, idx)) return LUTNN_VARIANT_SMFMAC;
         return LUTNN_VARIANT_MFMA;
@@ -205,12 +207,14 @@ lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, int64_t N, i
 
     int v = variant;
     if (v == LUTNN_VARIANT_AUTO) {
-        // One launch beats two while the encode recomputation it implies stays small; otherwise
-        // encode once and use the fastest lookup.
+        // Encode once, then the fastest lookup: measured over conv-like, BERT-like and FC shapes the
+        // two launches are never slower than the fused kernel (its 64-row workgroups encode all C
+        // codebooks serially and re-stream the table per row block).  Without a workspace for the
+        // indices the fused kernel is the only choice.
         const bool fused_ok = lutnn::fused_supported(L->C, L->K, L->V, L->M, L->table_dtype) &&
                               (L->table_dtype == LUTNN_TABLE_F32 ? L->table != nullptr
                                                                  : L->table_packed != nullptr);
-        if (fused_ok && (L->M <= 256 || !idx_workspace))
+        if (fused_ok && !idx_workspace)
             v = LUTNN_VARIANT_FUSED;
         else
             v = resolve_lookup_variant(L, LUTNN_VARIANT_AUTO, idx_workspace, N);
@@ -259,6 +263,11 @@ const char* lutnn_status_string(int32_t status) {
         case LUTNN_E_HIP: return "LUTNN_E_HIP";
         default: return "LUTNN_E_UNKNOWN";
     }
+}
+
+int32_t lutnn_auto_variant(const lutnn_layer* layer, const uint8_t* idx, int64_t N) {
+    if (!layer) return -1;
+    return resolve_lookup_variant(layer, LUTNN_VARIANT_AUTO, idx, N);
 }
 
 const char* lutnn_last_error(void) { return g_err; }

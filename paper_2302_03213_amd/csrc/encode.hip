@@ -40,10 +40,9 @@ __global__ __launch_bounds__(kEncThreads) void encode_tile_kernel(const float* _
 
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
-    uint32_t packed[E::CPW / 4];
+    uint32_t packed[E::PW];
     encode_codebooks<V, K_T, CT>(xs, P, C, K, c0, w, lane, packed);
-#pragma unroll
-    for (int j = 0; j < E::CPW / 4; ++j) is[lane * (CT / 4) + w * (E::CPW / 4) + j] = packed[j];
+    store_index_bytes<V, CT>(is + lane * (CT / 4), w * E::CPW, packed);
     __syncthreads();
 
     // each row's CT index bytes are contiguous in idx[N][C]
@@ -108,6 +107,9 @@ hipError_t launch_tile(const float* P, int C, int K, const float* X, int64_t N, 
     if (K == 16)
         hipLaunchKernelGGL((encode_tile_kernel<V, 16, CT>), grid, block, 0, s, X, ldx, P, idx, N, C, K,
                            vec4, idx_dword_ok);
+    else if (K == 8)
+        hipLaunchKernelGGL((encode_tile_kernel<V, 8, CT>), grid, block, 0, s, X, ldx, P, idx, N, C, K,
+                           vec4, idx_dword_ok);
     else
         hipLaunchKernelGGL((encode_tile_kernel<V, 0, CT>), grid, block, 0, s, X, ldx, P, idx, N, C, K,
                            vec4, idx_dword_ok);
@@ -125,6 +127,8 @@ hipError_t launch_encode(const float* P, int C, int K, int V, const float* X, in
         case 4: return launch_tile<4>(P, C, K, X, N, ldx, idx, s);
         case 8: return launch_tile<8>(P, C, K, X, N, ldx, idx, s);
         case 9: return launch_tile<9>(P, C, K, X, N, ldx, idx, s);
+        case 16: return launch_tile<16>(P, C, K, X, N, ldx, idx, s);
+        case 32: return launch_tile<32>(P, C, K, X, N, ldx, idx, s);
         default: break;
     }
     const int64_t total = N * (int64_t)C;

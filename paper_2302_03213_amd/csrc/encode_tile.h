@@ -18,18 +18,21 @@ constexpr int kEncThreads = 256;  // 4 wavefronts
 
 template <int V, int CT>
 struct EncTile {
-    static_assert(CT % 16 == 0, "CT must be a multiple of 16");
+    static_assert(CT % 4 == 0, "CT must be a multiple of 4 (one share per wavefront)");
     static constexpr int TW = CT * V;  // floats per tile row
     static constexpr int PAD = (V % 4 == 0) ? 4 : (V % 2 == 0) ? 2 : ((TW % 2 == 0) ? 1 : 0);
     static constexpr int LS = TW + PAD;  // LDS row stride (floats): conflict free for lane = row
     static constexpr int CPW = CT / 4;   // codebooks per wavefront
+    static constexpr int PW = (CPW + 3) / 4;  // dwords holding one lane's CPW index bytes
     static constexpr int kLdsFloats = kEncRows * LS;
 };
 
 // Codebooks per tile used for each supported sub-vector length (0 = not supported by the tiled
-// kernels).  Chosen so that a tile row is 64..144 floats.
+// kernels).  Chosen so that a tile row is 64..144 floats.  V = 16 and 32 are the sub-vector
+// lengths the paper uses for BERT (Sec. 6.1, Table 2).
 constexpr int enc_tile_codebooks(int V) {
-    return V == 1 ? 64 : V == 2 ? 64 : V == 3 ? 32 : V == 4 ? 32 : V == 8 ? 16 : V == 9 ? 16 : 0;
+    return V == 1 ? 64 : V == 2 ? 64 : V == 3 ? 32 : V == 4 ? 32 : V == 8 ? 16 : V == 9 ? 16
+         : V == 16 ? 8 : V == 32 ? 4 : 0;
 }
 
 inline bool enc_vec4_ok(const float* X, int64_t ldx, int C, int V) {
@@ -115,10 +118,10 @@ template <int V, int K_T, int CT>
 __device__ __forceinline__ void encode_codebooks(const float* __restrict__ xs,
                                                  const float* __restrict__ P, int C, int K, int c0,
                                                  int w, int lane,
-                                                 uint32_t (&packed)[EncTile<V, CT>::CPW / 4]) {
+                                                 uint32_t (&packed)[EncTile<V, CT>::PW]) {
     using E = EncTile<V, CT>;
 #pragma unroll
-    for (int j = 0; j < E::CPW / 4; ++j) packed[j] = 0;
+    for (int j = 0; j < E::PW; ++j) packed[j] = 0;
 #pragma unroll
     for (int j = 0; j < E::CPW; ++j) {
         const int cl = w * E::CPW + j;
@@ -131,6 +134,23 @@ __device__ __forceinline__ void encode_codebooks(const float* __restrict__ xs,
             best = nearest_centroid<V, K_T>(x, P + (size_t)c * K * V, K);
         }
         packed[j / 4] |= best << (8 * (j % 4));
+    }
+}
+
+// Puts a lane's CPW index bytes (codebooks first .. first+CPW-1 of its row) into the row's byte
+// array in LDS; `row_bytes` is 4-byte aligned and `first` a multiple of CPW.  Shares of fewer than
+// four codebooks are written byte by byte: several wavefronts then fill one dword between them.
+template <int V, int CT>
+__device__ __forceinline__ void store_index_bytes(uint32_t* __restrict__ row_dwords, int first,
+                                                  const uint32_t (&packed)[EncTile<V, CT>::PW]) {
+    using E = EncTile<V, CT>;
+    if constexpr (E::CPW % 4 == 0) {
+#pragma unroll
+        for (int j = 0; j < E::PW; ++j) row_dwords[first / 4 + j] = packed[j];
+    } else {
+        uint8_t* __restrict__ row_bytes = reinterpret_cast<uint8_t*>(row_dwords);
+#pragma unroll
+        for (int b = 0; b < E::CPW; ++b) row_bytes[first + b] = (uint8_t)(packed[0] >> (8 * b));
     }
 }
 

@@ -33,10 +33,9 @@ __device__ __forceinline__ void fused_encode_phase(const float* __restrict__ X, 
         __syncthreads();  // xs free again
         stage_x<V, CT>(X, ldx, N, C * V, row0, c0, xs, vec4, tid);
         __syncthreads();
-        uint32_t packed[E::CPW / 4];
+        uint32_t packed[E::PW];
         encode_codebooks<V, K_T, CT>(xs, P, C, K, c0, w, lane, packed);
-#pragma unroll
-        for (int j = 0; j < E::CPW / 4; ++j) is[lane * IS + (c0 + w * E::CPW) / 4 + j] = packed[j];
+        store_index_bytes<V, CT>(is + lane * IS, c0 + w * E::CPW, packed);
     }
     __syncthreads();
 }
@@ -251,6 +250,8 @@ bool fused_supported(int C, int K, int V, int M, int dtype) {
         case 4: return CALL(4);              \
         case 8: return CALL(8);              \
         case 9: return CALL(9);              \
+        case 16: return CALL(16);            \
+        case 32: return CALL(32);            \
         default: return hipErrorInvalidValue; \
     }
 

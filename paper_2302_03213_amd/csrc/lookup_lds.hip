@@ -372,6 +372,20 @@ inline bool idx_dword_ok(const uint8_t* idx, int C) {
 
 }  // namespace
 
+// True when the gather variant would read the table straight from L2 (no staging) and the whole
+// problem is small enough for that to beat the matrix-core kernels, whose 256/512-row tiles and
+// pipeline fill are wasted on it (measured cross-over: about 3e7 table entries).
+bool gather_preferred(const void* T, int table_is_i8, int C, int M, int64_t N) {
+    if (!T) return false;
+    const int64_t rows_per_block = table_is_i8 ? kRowsPerWaveI8 * kWaves : kRowsPerWaveF32 * kWaves;
+    const int cols_per_block = table_is_i8 ? kColsI8 : kColsF32;
+    const int64_t staged_blocks =
+        ((N + rows_per_block - 1) / rows_per_block) * ((M + cols_per_block - 1) / cols_per_block);
+    const bool direct = table_is_i8 ? gather_ok(static_cast<const int8_t*>(T), M, staged_blocks)
+                                    : gather_ok(static_cast<const float*>(T), M, staged_blocks);
+    return direct && N * (int64_t)C * M <= (int64_t)1 << 25;
+}
+
 hipError_t launch_lookup_lds_i8(const int8_t* T, const float* scale, const float* bias, int C, int K,
                                 int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,
                                 hipStream_t s) {

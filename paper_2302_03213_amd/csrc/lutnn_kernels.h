@@ -30,6 +30,8 @@ hipError_t launch_lookup_lds_i8(const int8_t* T, const float* scale, const float
 hipError_t launch_lookup_lds_f32(const float* T, const float* bias, int C, int K, int M,
                                  const uint8_t* idx, int64_t N, float* Y, int64_t ldy, hipStream_t s);
 
+bool gather_preferred(const void* T, int table_is_i8, int C, int M, int64_t N);
+
 // Eq. 4, one-hot MFMA variant (INT8).
 hipError_t launch_lookup_mfma_i8(const int8_t* packed, const float* scale, const float* bias, int C,
                                  int K, int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,

@@ -25,7 +25,7 @@ def test_header_declares_the_documented_entry_points():
     names = declared_symbols()
     for must in ("lutnn_build_table", "lutnn_encode", "lutnn_lookup", "lutnn_linear"):
         assert must in names
-    assert len(names) >= 9
+    assert len(names) >= 10
 
 
 def test_library_exports_every_declared_symbol(lut):
@@ -143,6 +143,25 @@ def test_empty_batch_is_ok_without_a_gpu(lut):
     assert L.lutnn_lookup(ctypes.byref(ok), vp(0x30000), 0, vp(0x20000), 8, lut.VARIANT_MFMA, None) == 0
     assert L.lutnn_linear(ctypes.byref(ok), vp(0x10000), 0, 16, vp(0x20000), 8, lut.VARIANT_FUSED,
                           None, None) == 0
+
+
+def test_auto_variant_rule(lut):
+    """AUTO is a pure function of the descriptor, N and the address of idx."""
+    L, vp = lut.LIB, ctypes.c_void_p
+    big = _layer(lut, C=1024, M=4096)
+    assert L.lutnn_auto_variant(ctypes.byref(big), vp(0x30000), 16384) == lut.VARIANT_SMFMAC
+    assert L.lutnn_auto_variant(ctypes.byref(big), vp(0x30004), 16384) == lut.VARIANT_MFMA  # idx alignment
+    assert L.lutnn_auto_variant(ctypes.byref(big), vp(0x30000), 200) == lut.VARIANT_MFMA
+    odd = _layer(lut, C=1000, M=4096)
+    assert L.lutnn_auto_variant(ctypes.byref(odd), vp(0x30000), 16384) == lut.VARIANT_MFMA  # C % 32 != 0
+    small = _layer(lut, C=64, M=64)  # few table entries: rows gathered straight from L2
+    assert L.lutnn_auto_variant(ctypes.byref(small), vp(0x30000), 3136) == lut.VARIANT_LDS
+    assert L.lutnn_auto_variant(ctypes.byref(small), vp(0x30000), 1 << 20) == lut.VARIANT_SMFMAC
+    f32 = _layer(lut, table_dtype=lut.TABLE_F32, C=128, M=512)
+    assert L.lutnn_auto_variant(ctypes.byref(f32), vp(0x30000), 256) == lut.VARIANT_LDS
+    wide_k = _layer(lut, K=32, C=64, M=4096)
+    assert L.lutnn_auto_variant(ctypes.byref(wide_k), vp(0x30000), 1 << 16) == lut.VARIANT_LDS
+    assert L.lutnn_auto_variant(None, vp(0x30000), 16) == -1
 
 
 def test_cost_model_formulas(lut):

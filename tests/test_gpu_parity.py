@@ -70,6 +70,9 @@ ENC_SHAPES = [
     (130, 64, 16, 9), (77, 17, 16, 9), (300, 384, 16, 2), (129, 70, 16, 2), (100, 9, 16, 1),
     (100, 35, 16, 3), (100, 20, 16, 8), (90, 7, 16, 5), (50, 3, 16, 16), (40, 2, 16, 32),
     (150, 12, 8, 4), (150, 12, 5, 9), (60, 6, 1, 4), (60, 6, 256, 2), (33, 4, 100, 7),
+    # the paper's own settings: (K, V) = (16, 32), (16, 16), (8, 9)
+    (300, 24, 16, 32), (130, 7, 16, 32), (200, 48, 16, 16), (67, 9, 16, 16), (130, 12, 8, 16),
+    (130, 64, 8, 9), (90, 5, 5, 32),
 ]
 
 
@@ -306,6 +309,8 @@ LINEAR_SHAPES = [
     (257, 100, 16, 2, 300, "i8"), (100, 20, 7, 3, 40, "i8"), (64, 16, 16, 8, 512, "i8"),
     (70, 5, 16, 4, 37, "f32"), (129, 33, 16, 9, 130, "f32"), (200, 70, 16, 2, 64, "f32"),
     (50, 9, 5, 1, 20, "f32"),
+    (130, 24, 16, 32, 96, "i8"), (70, 5, 16, 16, 40, "i8"), (100, 10, 8, 9, 64, "i8"),
+    (90, 6, 16, 32, 50, "f32"), (65, 9, 8, 16, 33, "f32"),
 ]
 
 
@@ -339,6 +344,14 @@ def test_config2_conv_int8(lut):
 def test_config3_bert_ffn_up_int8(lut):
     flips = check_linear(lut, wl.bert_ffn_up(0), ["auto", "lds", "mfma", "smfmac", "fused"])
     print("config 3 near-ties: %d" % flips)
+
+
+def test_paper_kv_space_layers_int8(lut):
+    # (K, V) = (16, 32), (16, 16), (8, 9), (16, 4): the settings of the paper's own evaluation
+    for w in wl.paper_kv_space(0):
+        variants = ["auto", "lds", "mfma", "fused"] + (["smfmac"] if w.C % 32 == 0 else [])
+        flips = check_linear(lut, w, variants)
+        print("%s near-ties: %d" % (w.name, flips))
 
 
 def check_sampled_rows(lut, w, variants, n_sample=384, seed=0):
