@@ -93,15 +93,15 @@ __global__ __launch_bounds__(kEncThreads) void encode_generic_kernel(const float
     idx[i] = (uint8_t)best;
 }
 
-template <int V>
-hipError_t launch_tile(const float* P, int C, int K, const float* X, int64_t N, int64_t ldx,
-                       uint8_t* idx, hipStream_t s) {
-    constexpr int CT = enc_tile_codebooks(V);
+template <int V, int CT>
+hipError_t launch_tile_ct(const float* P, int C, int K, const float* X, int64_t N, int64_t ldx,
+                          uint8_t* idx, hipStream_t s) {
     const int64_t row_tiles = (N + kEncRows - 1) / kEncRows;
     const int64_t col_tiles = (C + CT - 1) / CT;
     const int64_t blocks = row_tiles * col_tiles;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    const int vec4 = enc_vec4_ok(X, ldx, C, V);
+    const int vec4 = ((CT * V) % 4 == 0) && (((int64_t)C * V) % 4 == 0) && (ldx % 4 == 0) &&
+                     ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
     const int idx_dword_ok = (C % 4 == 0) && ((reinterpret_cast<uintptr_t>(idx) & 3) == 0);
     dim3 grid((unsigned)blocks), block(kEncThreads);
     if (K == 16)
@@ -114,6 +114,22 @@ hipError_t launch_tile(const float* P, int C, int K, const float* X, int64_t N, 
         hipLaunchKernelGGL((encode_tile_kernel<V, 0, CT>), grid, block, 0, s, X, ldx, P, idx, N, C, K,
                            vec4, idx_dword_ok);
     return hipGetLastError();
+}
+
+// Tile width.  The full tile (a row of 64-144 floats) amortises the staging best, but a workgroup
+// then encodes CT/4 codebooks per wavefront one after the other: with few rows that serial chain
+// and the load latency in front of it are the whole run time, and the grid is too small to hide
+// them.  Below ~1024 workgroups a quarter-width tile (never under one codebook per wavefront)
+// gives four times the workgroups and a quarter of the chain.
+template <int V>
+hipError_t launch_tile(const float* P, int C, int K, const float* X, int64_t N, int64_t ldx,
+                       uint8_t* idx, hipStream_t s) {
+    constexpr int CT = enc_tile_codebooks(V);
+    constexpr int CT_SMALL = CT / 4 >= 4 ? CT / 4 : 4;
+    const int64_t full_blocks = ((N + kEncRows - 1) / kEncRows) * ((C + CT - 1) / CT);
+    if (CT_SMALL < CT && full_blocks < 1024)
+        return launch_tile_ct<V, CT_SMALL>(P, C, K, X, N, ldx, idx, s);
+    return launch_tile_ct<V, CT>(P, C, K, X, N, ldx, idx, s);
 }
 
 }  // namespace
