@@ -34,7 +34,7 @@ def workload_by_name(name):
     import lutnn_workloads as wl
     table = {
         "fc_large": wl.fc_large, "fc_small": wl.fc_small, "conv_resnet18": wl.conv_resnet18,
-        "bert_ffn_up": wl.bert_ffn_up,
+        "bert_ffn_up": wl.bert_ffn_up, "conv_resnet18_b32": wl.conv_resnet18_batch,
     }
     if name == "bert_layer":
         return wl.bert_layer(0)
@@ -50,7 +50,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="fc_large",
                     choices=["fc_large", "fc_small", "conv_resnet18", "bert_ffn_up", "bert_layer",
-                             "paper_kv"])
+                             "paper_kv", "conv_resnet18_b32"])
     ap.add_argument("--variant", default="auto", choices=["auto", "lds", "mfma", "smfmac", "fused"])
     ap.add_argument("--cpu-sample-rows", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -80,7 +80,7 @@ def main():
         P, W = torch.from_numpy(w.P).cuda(), torch.from_numpy(w.W).cuda()
         bias = torch.from_numpy(w.bias).cuda() if w.bias is not None else None
         layer = lut.build_table(P, W, dt, bias=bias)
-        X0 = torch.from_numpy(w.X).cuda()
+        X0 = torch.from_numpy(w.conv["inp"] if w.conv else w.X).cuda()
         Xs = [X0, X0.flip(0).contiguous()]
         Ys = [torch.empty((w.N, w.M), dtype=torch.float32, device="cuda") for _ in range(2)]
         ws = torch.empty((w.N, w.C), dtype=torch.uint8, device="cuda")
@@ -94,9 +94,22 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    def run_layer(w, layer, X, variant, Y, ws):
+        if w.conv:  # the image batch, no im2col matrix
+            lut.conv2d(layer, X, w.conv["kernel"], w.conv["stride"], w.conv["pad"], variant, out=Y,
+                       idx_workspace=ws)
+        else:
+            lut.linear(layer, X, variant, out=Y, idx_workspace=ws)
+
+    def run_encode(w, layer, X, ws):
+        if w.conv:
+            lut.encode_conv2d(layer, X, w.conv["kernel"], w.conv["stride"], w.conv["pad"], out=ws)
+        else:
+            lut.encode(layer, X, out=ws)
+
     def step(i):
         for (w, layer, Xs, Ys, ws) in dev_layers:
-            lut.linear(layer, Xs[i & 1], args.variant, out=Ys[i & 1], idx_workspace=ws)
+            run_layer(w, layer, Xs[i & 1], args.variant, Ys[i & 1], ws)
 
     for i in range(args.warmup):
         step(i)
@@ -128,13 +141,13 @@ def main():
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
             if fused:
                 ev[0].record()
-                lut.linear(layer, Xs[i & 1], "fused", out=Ys[i & 1])
+                run_layer(w, layer, Xs[i & 1], "fused", Ys[i & 1], ws)
                 ev[1].record()
                 ev[1].synchronize()
                 f_acc += ev[0].elapsed_time(ev[1])
             else:
                 ev[0].record()
-                lut.encode(layer, Xs[i & 1], out=ws)
+                run_encode(w, layer, Xs[i & 1], ws)
                 ev[1].record()
                 lut.lookup(layer, ws, variant_used[w.name], out=Ys[i & 1])
                 ev[2].record()
@@ -190,6 +203,8 @@ def main():
             kernels[w.name] = {"fused_ms": round(f, 4)}
         else:
             eb = cost.encode_bytes(w.N, w.C, w.V)
+            if w.conv:  # the image is read instead of the kh*kw times larger matrix
+                eb = 4 * w.conv["inp"].size + 4 * w.C * w.K * w.V + w.N * w.C
             kernels[w.name] = {"encode_ms": round(e, 4), "lookup_ms": round(l, 4),
                                "encode_hbm_GBps": round(eb / (e * 1e-3) / 1e9, 1),
                                "encode_hbm_frac": round(eb / (e * 1e-3) / cost.PEAK_HBM_BYTES_PER_S, 4)}
@@ -200,7 +215,7 @@ def main():
         import oracle
         t_cpu, n_cpu = 0.0, 0
         for (w, *_r) in dev_layers:
-            n = min(w.N, args.cpu_sample_rows)
+            n = min(w.N, len(w.X), args.cpu_sample_rows)
             Tf = oracle.build_table_f32(w.P, w.W)  # offline, untimed like on the GPU
             Xs = np.ascontiguousarray(w.X[:n])
             if w.table_dtype == "i8":
@@ -220,7 +235,7 @@ def main():
         cpu = {"value": round(n_cpu / t_cpu, 1), "unit": "rows/s", "cores": oracle.threads(),
                "kind": "oracle",
                "sample": "first %d rows of each layer of %s, encode+lookup, tables prebuilt; "
-                         "%.2f s wall" % (args.cpu_sample_rows, args.workload, t_cpu)}
+                         "%.2f s wall" % (n_cpu // len(dev_layers), args.workload, t_cpu)}
 
     w_desc = "; ".join("%s N=%d D=%d M=%d V=%d C=%d K=%d %s table" %
                        (w.name, w.N, w.D, w.M, w.V, w.C, w.K, w.table_dtype)
@@ -233,8 +248,8 @@ def main():
         "vs_baseline": None, "dtype": "i8" if w0.table_dtype == "i8" else "f32",
         "data": "synthetic",
         "config": {"workload": w_desc, "variant": args.variant, "variant_used": variant_used,
-                   "step": "lutnn_linear per layer (encode fp32 + lookup), inputs resident in HBM, "
-                           "two rotating X/Y buffer sets"},
+                   "step": "lutnn_linear (lutnn_conv2d for an image batch) per layer: encode fp32 + "
+                           "lookup, inputs resident in HBM, two rotating X/Y buffer sets"},
         "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
     }
     print(json.dumps(out))

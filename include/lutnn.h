@@ -156,6 +156,54 @@ LUTNN_API lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, in
                                     uint8_t* idx_workspace, void* stream);
 
 /*
+ * A 2-D convolution as the operator above (Sec. 4: a convolution becomes a matrix product by
+ * im2col, with M = output channels, D = input channels x filter size and N = output pixels).
+ * Row n = (image b, output pixel ho, wo), b slowest; column j = (input channel ci, filter row r,
+ * filter column s), ci slowest, holding input[b][ci][ho*stride_h + r - pad_h][wo*stride_w + s - pad_w]
+ * or 0 outside the image.  Sub-vector c of a row is columns [c*V, (c+1)*V): with V = kh*kw it is
+ * one channel's patch, the paper's (K, V) = (16, 9) for 3x3 filters; with a 1x1 filter and V = 4
+ * it is four consecutive channels of one pixel, the paper's (16, 4).
+ */
+typedef struct {
+    int32_t Cin, H, W;          /* input channels, height, width                      */
+    int32_t kh, kw;             /* filter height, width                               */
+    int32_t stride_h, stride_w; /* >= 1                                               */
+    int32_t pad_h, pad_w;       /* zero padding on each side, >= 0                    */
+    int32_t reserved;           /* must be 0                                          */
+} lutnn_conv2d_geom;
+
+/*
+ * Host: rows of the im2col matrix, N = B * Ho * Wo with Ho = (H + 2*pad_h - kh) / stride_h + 1
+ * (Wo likewise).  Returns -1 for an invalid geometry or B < 0.
+ */
+LUTNN_API int64_t lutnn_conv2d_rows(const lutnn_conv2d_geom* geom, int64_t B);
+
+/*
+ * lutnn_encode on the rows of the im2col matrix, read straight from the image batch: the matrix
+ * (kh*kw times the input) is never written.
+ *
+ *   input  [B][Cin][H][W] fp32, dense (NCHW)
+ *   idx    [N][C] uint8, dense, N = lutnn_conv2d_rows(geom, B)
+ * Needs Cin*kh*kw == C*V and V in {1, 2, 3, 4, 8, 9, 16}.
+ * Errors: E_NULL, E_SHAPE, E_UNSUPPORTED (V), E_ALIGN, E_HIP.
+ */
+LUTNN_API lutnn_status lutnn_encode_conv2d(const lutnn_layer* layer, const float* input, int64_t B,
+                                           const lutnn_conv2d_geom* geom, uint8_t* idx,
+                                           void* stream);
+
+/*
+ * The convolution: lutnn_encode_conv2d into idx_workspace, then lutnn_lookup.
+ *
+ *   Y              [N][M] fp32, row stride ldy >= M: output pixels by output channels (NHWC)
+ *   variant        AUTO, LDS, MFMA or SMFMAC (as lutnn_lookup); FUSED is not available
+ *   idx_workspace  [N][C] uint8 device scratch, required
+ * Errors: as lutnn_encode_conv2d and lutnn_lookup.
+ */
+LUTNN_API lutnn_status lutnn_conv2d(const lutnn_layer* layer, const float* input, int64_t B,
+                                    const lutnn_conv2d_geom* geom, float* Y, int64_t ldy,
+                                    int32_t variant, uint8_t* idx_workspace, void* stream);
+
+/*
  * Host: the variant that LUTNN_VARIANT_AUTO stands for in lutnn_lookup(layer, idx, N, ...) - and in
  * lutnn_linear when `idx` is its workspace - so that callers (and benchmarks) can report which
  * kernel ran.  Pure function of the descriptor, N and the address of idx; nothing is launched

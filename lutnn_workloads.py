@@ -33,6 +33,9 @@ class Workload:
     P: np.ndarray = field(repr=False)
     W: np.ndarray = field(repr=False)
     bias: Optional[np.ndarray] = field(repr=False, default=None)
+    # convolutions given by their image batch: {"inp": [B,Cin,H,W], "kernel", "stride", "pad"};
+    # X then holds the unfolded rows of the first image only
+    conv: Optional[dict] = field(repr=False, default=None)
 
     @property
     def D(self):
@@ -80,6 +83,18 @@ def fc_small(seed=0):
     return make_layer("fc_small_f32", 256, 128, 16, 4, 512, "f32", seed=seed)
 
 
+def conv_resnet18_input(seed=0, batch=1):
+    """The NCHW input of conv_resnet18 (image 0 is the one its rows are unfolded from); further
+    images of a batch are drawn from the same stream after the layer's parameters."""
+    g = _gen(seed)
+    inp = _normal(g, (1, 64, 56, 56), 1.0)
+    if batch > 1:
+        for shape in ((64, 16, 9), (576, 64), (64,)):
+            _normal(g, shape)
+        inp = np.concatenate([inp, _normal(g, (batch - 1, 64, 56, 56), 1.0)], axis=0)
+    return inp
+
+
 def conv_resnet18(seed=0):
     """3x3 conv 64->64 on 56x56 as a LUT op (the conv of the paper's Sec. 6.4 breakdown):
     im2col rows N=3136, D=576, V=9 (C=64), K=16, M=64, INT8 table."""
@@ -90,6 +105,14 @@ def conv_resnet18(seed=0):
     W = _normal(g, (576, 64), 0.05)
     b = _normal(g, (64,), 0.1)
     return Workload("conv3x3_64x64_56x56_i8", 3136, 64, 16, 9, 64, "i8", X, P, W, b)
+
+
+def conv_resnet18_batch(seed=0, batch=32):
+    """conv_resnet18 on a batch of images, handed over as the NCHW batch (N = batch * 3136 rows)."""
+    w = conv_resnet18(seed)
+    inp = conv_resnet18_input(seed, batch)
+    return Workload("conv3x3_64x64_56x56_b%d_nchw_i8" % batch, batch * 3136, 64, 16, 9, 64, "i8", w.X,
+                    w.P, w.W, w.bias, conv={"inp": inp, "kernel": 3, "stride": 1, "pad": 1})
 
 
 def bert_ffn_up(seed=0):

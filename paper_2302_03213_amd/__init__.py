@@ -2,5 +2,6 @@
 liblutnn.so.  Importing this package loads the HIP library and fails if it is absent."""
 from .binding import (LIB, TABLE_F32, TABLE_I8, VARIANT_AUTO, VARIANT_FUSED, VARIANT_LDS,  # noqa: F401
                       VARIANT_MFMA, VARIANT_SMFMAC, LutLayer, LutnnError, auto_variant, build_table,
-                      encode, linear, lookup, packed_bytes, table_bytes, version)
+                      conv2d, conv2d_rows, conv_geom, encode, encode_conv2d, linear, lookup,
+                      packed_bytes, table_bytes, version)
 from . import cost  # noqa: F401

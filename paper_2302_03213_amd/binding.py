@@ -27,8 +27,8 @@ VARIANTS = {"auto": VARIANT_AUTO, "lds": VARIANT_LDS, "mfma": VARIANT_MFMA, "fus
             "smfmac": VARIANT_SMFMAC}
 
 EXPORTS = ["lutnn_table_bytes", "lutnn_packed_bytes", "lutnn_build_table", "lutnn_encode",
-           "lutnn_lookup", "lutnn_linear", "lutnn_auto_variant", "lutnn_status_string",
-           "lutnn_last_error", "lutnn_version"]
+           "lutnn_lookup", "lutnn_linear", "lutnn_conv2d_rows", "lutnn_encode_conv2d", "lutnn_conv2d",
+           "lutnn_auto_variant", "lutnn_status_string", "lutnn_last_error", "lutnn_version"]
 
 
 class LutnnError(RuntimeError):
@@ -44,6 +44,11 @@ class _CLayer(ctypes.Structure):
                 ("reserved", ctypes.c_int32), ("centroids", ctypes.c_void_p),
                 ("table", ctypes.c_void_p), ("table_packed", ctypes.c_void_p),
                 ("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p)]
+
+
+class _CConvGeom(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("Cin", "H", "W", "kh", "kw", "stride_h", "stride_w",
+                                              "pad_h", "pad_w", "reserved")]
 
 
 def _load():
@@ -71,6 +76,13 @@ def _load():
     lib.lutnn_lookup.argtypes = [ctypes.POINTER(_CLayer), vp, i64, vp, i64, i32, vp]
     lib.lutnn_linear.restype = i32
     lib.lutnn_linear.argtypes = [ctypes.POINTER(_CLayer), vp, i64, i64, vp, i64, i32, vp, vp]
+    lib.lutnn_conv2d_rows.restype = i64
+    lib.lutnn_conv2d_rows.argtypes = [ctypes.POINTER(_CConvGeom), i64]
+    lib.lutnn_encode_conv2d.restype = i32
+    lib.lutnn_encode_conv2d.argtypes = [ctypes.POINTER(_CLayer), vp, i64, ctypes.POINTER(_CConvGeom), vp, vp]
+    lib.lutnn_conv2d.restype = i32
+    lib.lutnn_conv2d.argtypes = [ctypes.POINTER(_CLayer), vp, i64, ctypes.POINTER(_CConvGeom), vp, i64,
+                                 i32, vp, vp]
     lib.lutnn_auto_variant.restype = i32
     lib.lutnn_auto_variant.argtypes = [ctypes.POINTER(_CLayer), vp, i64]
     lib.lutnn_status_string.restype = ctypes.c_char_p
@@ -174,6 +186,53 @@ def lookup(layer, idx, variant="auto", out=None):
     assert out.dtype == torch.float32 and out.stride(1) == 1 and out.shape == (N, layer.M)
     _check(LIB.lutnn_lookup(ctypes.byref(layer.c), _ptr(idx), N, _ptr(out), out.stride(0),
                             _variant(variant), _stream()))
+    return out
+
+
+def _pair(v):
+    return (int(v), int(v)) if isinstance(v, int) else (int(v[0]), int(v[1]))
+
+
+def conv_geom(inp, kernel, stride=1, pad=0):
+    """Geometry descriptor for an NCHW batch `inp` and a kh x kw filter."""
+    (kh, kw), (sh, sw), (ph, pw) = _pair(kernel), _pair(stride), _pair(pad)
+    return _CConvGeom(inp.shape[1], inp.shape[2], inp.shape[3], kh, kw, sh, sw, ph, pw, 0)
+
+
+def conv2d_rows(geom, B):
+    return int(LIB.lutnn_conv2d_rows(ctypes.byref(geom), B))
+
+
+def encode_conv2d(layer, inp, kernel, stride=1, pad=0, out=None):
+    """lutnn_encode_conv2d: Eq. 2 on the rows of the im2col matrix of `inp` [B, Cin, H, W], read
+    in place.  Returns idx [B*Ho*Wo, C] uint8."""
+    assert inp.is_cuda and inp.dtype == torch.float32 and inp.is_contiguous() and inp.dim() == 4
+    geom = conv_geom(inp, kernel, stride, pad)
+    N = conv2d_rows(geom, inp.shape[0])
+    if N < 0:
+        raise ValueError("invalid convolution geometry")
+    if out is None:
+        out = torch.empty((N, layer.C), dtype=torch.uint8, device=inp.device)
+    assert out.is_contiguous() and out.shape == (N, layer.C) and out.dtype == torch.uint8
+    _check(LIB.lutnn_encode_conv2d(ctypes.byref(layer.c), _ptr(inp), inp.shape[0], ctypes.byref(geom),
+                                   _ptr(out), _stream()))
+    return out
+
+
+def conv2d(layer, inp, kernel, stride=1, pad=0, variant="auto", out=None, idx_workspace=None):
+    """lutnn_conv2d: the convolution, Y [B*Ho*Wo, M] (output pixels by output channels)."""
+    assert inp.is_cuda and inp.dtype == torch.float32 and inp.is_contiguous() and inp.dim() == 4
+    geom = conv_geom(inp, kernel, stride, pad)
+    N = conv2d_rows(geom, inp.shape[0])
+    if N < 0:
+        raise ValueError("invalid convolution geometry")
+    if out is None:
+        out = torch.empty((N, layer.M), dtype=torch.float32, device=inp.device)
+    assert out.dtype == torch.float32 and out.stride(1) == 1 and out.shape == (N, layer.M)
+    if idx_workspace is None:
+        idx_workspace = torch.empty((N, layer.C), dtype=torch.uint8, device=inp.device)
+    _check(LIB.lutnn_conv2d(ctypes.byref(layer.c), _ptr(inp), inp.shape[0], ctypes.byref(geom), _ptr(out),
+                            out.stride(0), _variant(variant), _ptr(idx_workspace), _stream()))
     return out
 
 

@@ -129,6 +129,46 @@ lutnn_status check_encode(const lutnn_layer* L, const float* X, int64_t N, int64
     return LUTNN_OK;
 }
 
+// Validates a convolution geometry against the layer and derives the output size.
+lutnn_status check_conv(const lutnn_layer* L, const lutnn_conv2d_geom* g, int64_t B, lutnn::ConvGeom* out,
+                        int64_t* rows) {
+    if (!g) return fail(LUTNN_E_NULL, "geom is NULL");
+    if (g->reserved != 0) return fail(LUTNN_E_SHAPE, "geom->reserved must be 0");
+    if (B < 0 || B >= kMaxRows) return fail(LUTNN_E_SHAPE, "B=%lld out of range", (long long)B);
+    if (g->Cin <= 0 || g->H <= 0 || g->W <= 0 || g->kh <= 0 || g->kw <= 0 || g->stride_h <= 0 ||
+        g->stride_w <= 0 || g->pad_h < 0 || g->pad_w < 0)
+        return fail(LUTNN_E_SHAPE, "invalid convolution geometry");
+    if (g->kh > 64 || g->kw > 64 || g->pad_h > 64 || g->pad_w > 64)
+        return fail(LUTNN_E_SHAPE, "filter size and padding are limited to 64");
+    const int64_t eh = (int64_t)g->H + 2 * g->pad_h - g->kh, ew = (int64_t)g->W + 2 * g->pad_w - g->kw;
+    if (eh < 0 || ew < 0) return fail(LUTNN_E_SHAPE, "the filter is larger than the padded image");
+    const int64_t Ho = eh / g->stride_h + 1, Wo = ew / g->stride_w + 1;
+    if (Ho * Wo >= (int64_t)1 << 30 || (int64_t)g->Cin * g->H * g->W >= (int64_t)1 << 31)
+        return fail(LUTNN_E_SHAPE, "image too large");
+    const int64_t N = B * Ho * Wo;
+    if (N >= kMaxRows) return fail(LUTNN_E_SHAPE, "N=B*Ho*Wo=%lld out of range", (long long)N);
+    if (L) {
+        if ((int64_t)g->Cin * g->kh * g->kw != (int64_t)L->C * L->V)
+            return fail(LUTNN_E_SHAPE, "Cin*kh*kw=%lld differs from C*V=%lld",
+                        (long long)g->Cin * g->kh * g->kw, (long long)L->C * L->V);
+        if (!lutnn::encode_conv_supported(L->V))
+            return fail(LUTNN_E_UNSUPPORTED, "no convolution encoder for V=%d", L->V);
+    }
+    if (out)
+        *out = lutnn::ConvGeom{g->Cin, g->H,     g->W,     g->kh,   g->kw, g->stride_h,
+                               g->stride_w, g->pad_h, g->pad_w, (int)Ho, (int)Wo};
+    *rows = N;
+    return LUTNN_OK;
+}
+
+lutnn_status check_conv_input(const lutnn_layer* L, const float* input) {
+    if (!L->centroids) return fail(LUTNN_E_NULL, "layer->centroids is NULL");
+    if (!input) return fail(LUTNN_E_NULL, "input is NULL");
+    if (!aligned(input, 4) || !aligned(L->centroids, 4))
+        return fail(LUTNN_E_ALIGN, "input and centroids must be 4-byte aligned");
+    return LUTNN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -263,6 +303,47 @@ const char* lutnn_status_string(int32_t status) {
         case LUTNN_E_HIP: return "LUTNN_E_HIP";
         default: return "LUTNN_E_UNKNOWN";
     }
+}
+
+int64_t lutnn_conv2d_rows(const lutnn_conv2d_geom* geom, int64_t B) {
+    int64_t rows = -1;
+    return check_conv(nullptr, geom, B, nullptr, &rows) == LUTNN_OK ? rows : -1;
+}
+
+lutnn_status lutnn_encode_conv2d(const lutnn_layer* layer, const float* input, int64_t B,
+                                 const lutnn_conv2d_geom* geom, uint8_t* idx, void* stream) {
+    if (lutnn_status st = check_layer(layer)) return st;
+    lutnn::ConvGeom g;
+    int64_t N = 0;
+    if (lutnn_status st = check_conv(layer, geom, B, &g, &N)) return st;
+    if (N == 0) return LUTNN_OK;
+    if (lutnn_status st = check_conv_input(layer, input)) return st;
+    if (!idx) return fail(LUTNN_E_NULL, "idx is NULL");
+    return hip_result(lutnn::launch_encode_conv(layer->centroids, layer->C, layer->K, layer->V, input, B,
+                                                g, idx, static_cast<hipStream_t>(stream)),
+                      "convolution encode launch");
+}
+
+lutnn_status lutnn_conv2d(const lutnn_layer* layer, const float* input, int64_t B,
+                          const lutnn_conv2d_geom* geom, float* Y, int64_t ldy, int32_t variant,
+                          uint8_t* idx_workspace, void* stream) {
+    if (lutnn_status st = check_layer(layer)) return st;
+    lutnn::ConvGeom g;
+    int64_t N = 0;
+    if (lutnn_status st = check_conv(layer, geom, B, &g, &N)) return st;
+    if (N == 0) return LUTNN_OK;
+    if (lutnn_status st = check_conv_input(layer, input)) return st;
+    if (variant == LUTNN_VARIANT_FUSED)
+        return fail(LUTNN_E_UNSUPPORTED, "there is no fused convolution kernel");
+    if (!idx_workspace) return fail(LUTNN_E_NULL, "lutnn_conv2d needs idx_workspace");
+    const int v = resolve_lookup_variant(layer, variant, idx_workspace, N);
+    if (lutnn_status st = check_lookup(layer, v, idx_workspace, Y, N, ldy)) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (lutnn_status st = hip_result(lutnn::launch_encode_conv(layer->centroids, layer->C, layer->K,
+                                                               layer->V, input, B, g, idx_workspace, s),
+                                     "convolution encode launch"))
+        return st;
+    return do_lookup(layer, v, idx_workspace, N, Y, ldy, s);
 }
 
 int32_t lutnn_auto_variant(const lutnn_layer* layer, const uint8_t* idx, int64_t N) {

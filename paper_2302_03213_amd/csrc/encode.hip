@@ -18,13 +18,14 @@
 namespace lutnn {
 namespace {
 
-template <int V, int K_T, int CT>
+// CONV: X is an NCHW image batch and the tile is gathered through `geom` (implicit im2col).
+template <int V, int K_T, int CT, bool CONV = false>
 __global__ __launch_bounds__(kEncThreads) void encode_tile_kernel(const float* __restrict__ X,
                                                                   int64_t ldx,
                                                                   const float* __restrict__ P,
                                                                   uint8_t* __restrict__ idx,
                                                                   int64_t N, int C, int K_rt, int vec4,
-                                                                  int idx_dword_ok) {
+                                                                  int idx_dword_ok, ConvGeom geom) {
     using E = EncTile<V, CT>;
     __shared__ float xs[E::kLdsFloats];
     __shared__ uint32_t is[kEncRows * (CT / 4)];
@@ -35,7 +36,10 @@ __global__ __launch_bounds__(kEncThreads) void encode_tile_kernel(const float* _
     const int c0 = (int)(blockIdx.x % col_tiles) * CT;
     const int tid = threadIdx.x;
 
-    stage_x<V, CT>(X, ldx, N, C * V, row0, c0, xs, vec4, tid);
+    if (CONV)
+        stage_x_conv<V, CT>(X, geom, N, C * V, row0, c0, xs, tid);
+    else
+        stage_x<V, CT>(X, ldx, N, C * V, row0, c0, xs, vec4, tid);
     __syncthreads();
 
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -93,9 +97,9 @@ __global__ __launch_bounds__(kEncThreads) void encode_generic_kernel(const float
     idx[i] = (uint8_t)best;
 }
 
-template <int V, int CT>
+template <int V, int CT, bool CONV = false>
 hipError_t launch_tile_ct(const float* P, int C, int K, const float* X, int64_t N, int64_t ldx,
-                          uint8_t* idx, hipStream_t s) {
+                          uint8_t* idx, hipStream_t s, const ConvGeom& geom = ConvGeom{}) {
     const int64_t row_tiles = (N + kEncRows - 1) / kEncRows;
     const int64_t col_tiles = (C + CT - 1) / CT;
     const int64_t blocks = row_tiles * col_tiles;
@@ -105,14 +109,14 @@ hipError_t launch_tile_ct(const float* P, int C, int K, const float* X, int64_t 
     const int idx_dword_ok = (C % 4 == 0) && ((reinterpret_cast<uintptr_t>(idx) & 3) == 0);
     dim3 grid((unsigned)blocks), block(kEncThreads);
     if (K == 16)
-        hipLaunchKernelGGL((encode_tile_kernel<V, 16, CT>), grid, block, 0, s, X, ldx, P, idx, N, C, K,
-                           vec4, idx_dword_ok);
+        hipLaunchKernelGGL((encode_tile_kernel<V, 16, CT, CONV>), grid, block, 0, s, X, ldx, P, idx, N, C,
+                           K, vec4, idx_dword_ok, geom);
     else if (K == 8)
-        hipLaunchKernelGGL((encode_tile_kernel<V, 8, CT>), grid, block, 0, s, X, ldx, P, idx, N, C, K,
-                           vec4, idx_dword_ok);
+        hipLaunchKernelGGL((encode_tile_kernel<V, 8, CT, CONV>), grid, block, 0, s, X, ldx, P, idx, N, C,
+                           K, vec4, idx_dword_ok, geom);
     else
-        hipLaunchKernelGGL((encode_tile_kernel<V, 0, CT>), grid, block, 0, s, X, ldx, P, idx, N, C, K,
-                           vec4, idx_dword_ok);
+        hipLaunchKernelGGL((encode_tile_kernel<V, 0, CT, CONV>), grid, block, 0, s, X, ldx, P, idx, N, C,
+                           K, vec4, idx_dword_ok, geom);
     return hipGetLastError();
 }
 
@@ -121,18 +125,37 @@ hipError_t launch_tile_ct(const float* P, int C, int K, const float* X, int64_t 
 // and the load latency in front of it are the whole run time, and the grid is too small to hide
 // them.  Below ~1024 workgroups a quarter-width tile (never under one codebook per wavefront)
 // gives four times the workgroups and a quarter of the chain.
-template <int V>
+template <int V, bool CONV = false>
 hipError_t launch_tile(const float* P, int C, int K, const float* X, int64_t N, int64_t ldx,
-                       uint8_t* idx, hipStream_t s) {
+                       uint8_t* idx, hipStream_t s, const ConvGeom& geom = ConvGeom{}) {
     constexpr int CT = enc_tile_codebooks(V);
     constexpr int CT_SMALL = CT / 4 >= 4 ? CT / 4 : 4;
     const int64_t full_blocks = ((N + kEncRows - 1) / kEncRows) * ((C + CT - 1) / CT);
     if (CT_SMALL < CT && full_blocks < 1024)
-        return launch_tile_ct<V, CT_SMALL>(P, C, K, X, N, ldx, idx, s);
-    return launch_tile_ct<V, CT>(P, C, K, X, N, ldx, idx, s);
+        return launch_tile_ct<V, CT_SMALL, CONV>(P, C, K, X, N, ldx, idx, s, geom);
+    return launch_tile_ct<V, CT, CONV>(P, C, K, X, N, ldx, idx, s, geom);
 }
 
 }  // namespace
+
+// Sub-vector lengths of the convolution settings in the paper (Sec. 6.1: 9 for a 3x3 filter, 4 for
+// 1x1) plus the other tiled lengths that divide common Cin * kh * kw.
+bool encode_conv_supported(int V) { return V == 1 || V == 2 || V == 3 || V == 4 || V == 8 || V == 9 || V == 16; }
+
+hipError_t launch_encode_conv(const float* P, int C, int K, int V, const float* input, int64_t B,
+                              const ConvGeom& g, uint8_t* idx, hipStream_t s) {
+    const int64_t N = B * g.Ho * g.Wo;
+    switch (V) {
+        case 1: return launch_tile<1, true>(P, C, K, input, N, 0, idx, s, g);
+        case 2: return launch_tile<2, true>(P, C, K, input, N, 0, idx, s, g);
+        case 3: return launch_tile<3, true>(P, C, K, input, N, 0, idx, s, g);
+        case 4: return launch_tile<4, true>(P, C, K, input, N, 0, idx, s, g);
+        case 8: return launch_tile<8, true>(P, C, K, input, N, 0, idx, s, g);
+        case 9: return launch_tile<9, true>(P, C, K, input, N, 0, idx, s, g);
+        case 16: return launch_tile<16, true>(P, C, K, input, N, 0, idx, s, g);
+        default: return hipErrorInvalidValue;
+    }
+}
 
 hipError_t launch_encode(const float* P, int C, int K, int V, const float* X, int64_t N, int64_t ldx,
                          uint8_t* idx, hipStream_t s) {

@@ -71,6 +71,42 @@ __device__ __forceinline__ void stage_x(const float* __restrict__ X, int64_t ldx
     }
 }
 
+// The same tile for a convolution (Sec. 4: convolution as a matrix product by im2col), gathered
+// from the NCHW input instead of a materialised matrix.  Row r of the tile is the thread's lane, so
+// the 64 lanes of a wavefront read 64 consecutive output pixels of one (channel, filter tap):
+// contiguous input words for stride 1.  The column (channel, tap) is wave-uniform.
+//   g      geometry; row n = (b, ho, wo), column j = (ci, r, s)
+//   N      rows = B * Ho * Wo;  D = Cin * kh * kw
+template <int V, int CT, class Geom>
+__device__ __forceinline__ void stage_x_conv(const float* __restrict__ input, const Geom& g, int64_t N,
+                                             int D, int64_t row0, int c0, float* __restrict__ xs,
+                                             int tid) {
+    using E = EncTile<V, CT>;
+    const int r = tid & 63;
+    const int64_t n = row0 + r;
+    const bool row_ok = n < N;
+    const int pix = g.Ho * g.Wo;
+    const int64_t b = row_ok ? n / pix : 0;
+    const int p = row_ok ? (int)(n % pix) : 0;
+    const int hi0 = (p / g.Wo) * g.sh - g.ph;
+    const int wi0 = (p % g.Wo) * g.sw - g.pw;
+    // offset of (b, ci = 0, hi0, wi0); may lie outside the image, only used where in bounds
+    const int64_t off0 = ((b * g.Cin) * g.H + hi0) * (int64_t)g.W + wi0;
+    const int taps = g.kh * g.kw;
+    for (int col = __builtin_amdgcn_readfirstlane(tid >> 6); col < E::TW; col += 4) {
+        const int j = c0 * V + col;  // wave-uniform
+        float val = 0.f;
+        if (j < D) {
+            const int ci = j / taps, rs = j - ci * taps;
+            const int rk = rs / g.kw, sk = rs - rk * g.kw;
+            const int hi = hi0 + rk, wi = wi0 + sk;
+            if (row_ok && (unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W)
+                val = input[off0 + ((int64_t)ci * g.H + rk) * g.W + sk];
+        }
+        xs[r * E::LS + col] = val;
+    }
+}
+
 template <int V, int K_T>
 __device__ __forceinline__ uint32_t nearest_centroid(const float (&x)[V], const float* __restrict__ pc,
                                                      int K) {

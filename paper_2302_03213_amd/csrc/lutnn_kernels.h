@@ -13,6 +13,18 @@ constexpr int kPackedColPad = 256;
 inline int64_t packed_cols(int64_t M) { return (M + kPackedColPad - 1) / kPackedColPad * kPackedColPad; }
 inline int kblocks(int K) { return (K + 15) / 16; }
 
+// A convolution seen as a matrix product (Sec. 4): row n = (image b, output pixel ho, wo),
+// column j = (input channel ci, filter row r, filter column s) with ci slowest, element
+// input[b][ci][ho*sh + r - ph][wo*sw + s - pw] or 0 outside the image.
+struct ConvGeom {
+    int Cin, H, W, kh, kw, sh, sw, ph, pw, Ho, Wo;
+};
+
+// Eq. 2 on the rows of that matrix, read from the NCHW input without materialising it.
+bool encode_conv_supported(int V);
+hipError_t launch_encode_conv(const float* P, int C, int K, int V, const float* input, int64_t B,
+                              const ConvGeom& g, uint8_t* idx, hipStream_t s);
+
 // Eq. 2.
 hipError_t launch_encode(const float* P, int C, int K, int V, const float* X, int64_t N, int64_t ldx,
                          uint8_t* idx, hipStream_t s);

@@ -25,7 +25,7 @@ def test_header_declares_the_documented_entry_points():
     names = declared_symbols()
     for must in ("lutnn_build_table", "lutnn_encode", "lutnn_lookup", "lutnn_linear"):
         assert must in names
-    assert len(names) >= 10
+    assert len(names) >= 13
 
 
 def test_library_exports_every_declared_symbol(lut):
@@ -143,6 +143,44 @@ def test_empty_batch_is_ok_without_a_gpu(lut):
     assert L.lutnn_lookup(ctypes.byref(ok), vp(0x30000), 0, vp(0x20000), 8, lut.VARIANT_MFMA, None) == 0
     assert L.lutnn_linear(ctypes.byref(ok), vp(0x10000), 0, 16, vp(0x20000), 8, lut.VARIANT_FUSED,
                           None, None) == 0
+
+
+def test_conv2d_geometry_and_validation(lut):
+    from paper_2302_03213_amd.binding import _CConvGeom
+    L, vp = lut.LIB, ctypes.c_void_p
+    g = _CConvGeom(64, 56, 56, 3, 3, 1, 1, 1, 1, 0)
+    assert L.lutnn_conv2d_rows(ctypes.byref(g), 1) == 56 * 56  # "same" convolution
+    assert L.lutnn_conv2d_rows(ctypes.byref(g), 0) == 0
+    assert L.lutnn_conv2d_rows(ctypes.byref(_CConvGeom(64, 56, 56, 3, 3, 2, 2, 1, 1, 0)), 4) == 4 * 28 * 28
+    assert L.lutnn_conv2d_rows(ctypes.byref(_CConvGeom(8, 7, 9, 1, 1, 1, 1, 0, 0, 0)), 2) == 2 * 63
+    assert L.lutnn_conv2d_rows(ctypes.byref(_CConvGeom(8, 7, 9, 3, 5, 2, 3, 0, 1, 0)), 1) == 3 * 3
+    assert L.lutnn_conv2d_rows(ctypes.byref(_CConvGeom(8, 2, 2, 3, 3, 1, 1, 0, 0, 0)), 1) == -1  # filter > image
+    assert L.lutnn_conv2d_rows(ctypes.byref(_CConvGeom(8, 7, 9, 3, 3, 0, 1, 0, 0, 0)), 1) == -1  # stride 0
+    assert L.lutnn_conv2d_rows(ctypes.byref(g), -1) == -1
+    assert L.lutnn_conv2d_rows(None, 1) == -1
+    ok = _layer(lut, C=64, V=9, M=64)
+    X, Y, IDX = vp(0x10000), vp(0x20000), vp(0x30000)
+    cases = [
+        (L.lutnn_encode_conv2d(ctypes.byref(ok), X, 1, None, IDX, None), "LUTNN_E_NULL"),
+        (L.lutnn_encode_conv2d(ctypes.byref(ok), None, 1, ctypes.byref(g), IDX, None), "LUTNN_E_NULL"),
+        (L.lutnn_encode_conv2d(ctypes.byref(ok), X, 1, ctypes.byref(g), None, None), "LUTNN_E_NULL"),
+        (L.lutnn_encode_conv2d(ctypes.byref(_layer(lut, C=64, V=4)), X, 1, ctypes.byref(g), IDX, None),
+         "LUTNN_E_SHAPE"),  # Cin*kh*kw != C*V
+        (L.lutnn_encode_conv2d(ctypes.byref(_layer(lut, C=18, V=32)), X, 1, ctypes.byref(g), IDX, None),
+         "LUTNN_E_UNSUPPORTED"),  # 64*9 = 18*32, but no convolution encoder for V = 32
+        (L.lutnn_encode_conv2d(ctypes.byref(ok), X, 1, ctypes.byref(_CConvGeom(64, 56, 56, 3, 3, 1, 1, 1, 1, 7)),
+                               IDX, None), "LUTNN_E_SHAPE"),  # reserved
+        (L.lutnn_conv2d(ctypes.byref(ok), X, 1, ctypes.byref(g), Y, 64, lut.VARIANT_FUSED, IDX, None),
+         "LUTNN_E_UNSUPPORTED"),
+        (L.lutnn_conv2d(ctypes.byref(ok), X, 1, ctypes.byref(g), Y, 64, lut.VARIANT_AUTO, None, None),
+         "LUTNN_E_NULL"),  # workspace required
+        (L.lutnn_conv2d(ctypes.byref(ok), X, 1, ctypes.byref(g), Y, 63, lut.VARIANT_LDS, IDX, None),
+         "LUTNN_E_SHAPE"),  # ldy < M
+    ]
+    for i, (code, want) in enumerate(cases):
+        name, detail = _status(lut, code)
+        assert name == want, "case %d: got %s (%s), wanted %s" % (i, name, detail, want)
+    assert L.lutnn_encode_conv2d(ctypes.byref(ok), X, 0, ctypes.byref(g), IDX, None) == 0  # empty batch
 
 
 def test_auto_variant_rule(lut):

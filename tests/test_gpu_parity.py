@@ -389,6 +389,64 @@ def test_config5_fc_large_int8(lut):
     print("config 5 near-ties: %d" % flips)
 
 
+# ------------------------------------------------------------------ convolutions (Sec. 4: im2col)
+def unfold_rows(inp, kernel, stride, pad):
+    """The im2col matrix with torch's own unfold: rows (b, ho, wo), columns (ci, r, s)."""
+    cols = torch.nn.functional.unfold(torch.from_numpy(inp), kernel, padding=pad, stride=stride)
+    return cols.permute(0, 2, 1).reshape(-1, cols.shape[1]).contiguous().numpy()
+
+
+CONV_SHAPES = [
+    # B, Cin, H, W, kernel, stride, pad, V, K
+    (1, 16, 13, 17, (3, 3), (1, 1), (1, 1), 9, 16),   # the paper's 3x3 setting, ragged image
+    (2, 8, 20, 20, (3, 3), (2, 2), (1, 1), 9, 8),     # stride 2, (K, V) = (8, 9)
+    (3, 16, 9, 11, (1, 1), (1, 1), (0, 0), 4, 16),    # 1x1 filter, V = 4 spans four channels
+    (1, 12, 10, 10, (3, 3), (1, 1), (0, 0), 3, 16),   # no padding, sub-vector = one filter row
+    (2, 4, 15, 9, (3, 5), (2, 1), (1, 2), 2, 16),     # rectangular filter, mixed stride / padding
+    (1, 32, 8, 8, (1, 1), (2, 2), (0, 0), 16, 16),    # strided 1x1, V = 16
+    (1, 5, 6, 6, (5, 5), (1, 1), (2, 2), 1, 5),       # padding wider than the image border, V = 1
+]
+
+
+@pytest.mark.parametrize("B,Cin,H,W,kernel,stride,pad,V,K", CONV_SHAPES)
+def test_encode_conv2d_matches_oracle_on_unfolded_rows(lut, B, Cin, H, W, kernel, stride, pad, V, K):
+    rng = np.random.default_rng(B + Cin + H + W + V)
+    inp = rng.standard_normal((B, Cin, H, W)).astype(np.float32)
+    X = unfold_rows(inp, kernel, stride, pad)
+    C = X.shape[1] // V
+    P = rng.standard_normal((C, K, V)).astype(np.float32)
+    layer = lut.LutLayer(dev(P), None, lut.TABLE_F32, 8)
+    got = host(lut.encode_conv2d(layer, dev(inp), kernel, stride, pad))
+    assert got.shape == (X.shape[0], C)
+    np.testing.assert_array_equal(got, oracle.encode(P, X))
+    # and it is the same encoder as the one for a materialised matrix
+    np.testing.assert_array_equal(got, host(lut.encode(layer, dev(X))))
+
+
+def test_conv2d_config2_from_the_image(lut):
+    """Config 2 without the im2col matrix: same indices and outputs as lutnn_linear on it."""
+    w = wl.conv_resnet18(0)
+    inp = wl.conv_resnet18_input(0)
+    np.testing.assert_array_equal(unfold_rows(inp, (3, 3), (1, 1), (1, 1)), w.X)
+    ol = OracleLayer(w)
+    idx_ref = ol.encode()
+    ref = ol.lookup(idx_ref)
+    layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8, bias=dev(w.bias))
+    idx = host(lut.encode_conv2d(layer, dev(inp), 3, 1, 1))
+    clean = (idx == idx_ref).all(axis=1)
+    assert near_tie_report(w, idx, idx_ref) <= 1
+    for variant in ("auto", "lds", "mfma", "smfmac"):
+        got = host(lut.conv2d(layer, dev(inp), 3, 1, 1, variant))
+        np.testing.assert_array_equal(got[clean], ref[clean], err_msg=variant)
+    # a batch of images: rows of image b follow those of image b-1
+    batch = np.concatenate([inp, inp[:, ::-1].copy()], axis=0)
+    got = host(lut.conv2d(layer, dev(batch), 3, 1, 1))
+    np.testing.assert_array_equal(got[:w.N][clean], ref[clean])
+    Xb = unfold_rows(batch, (3, 3), (1, 1), (1, 1))
+    np.testing.assert_array_equal(host(lut.encode_conv2d(layer, dev(batch), 3, 1, 1)),
+                                  oracle.encode(w.P, Xb))
+
+
 def test_identity_on_centroid_inputs(lut):
     # end-to-end property independent of the oracle: rows made of centroids reproduce X @ W + b
     w = wl.make_layer("t", 1, 24, 16, 4, 80, "f32", seed=9)
