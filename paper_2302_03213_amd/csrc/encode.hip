@@ -18,8 +18,9 @@
 namespace lutnn {
 namespace {
 
-// CONV: X is an NCHW image batch and the tile is gathered through `geom` (implicit im2col).
-template <int V, int K_T, int CT, bool CONV = false>
+// CONV != 0: X is an NCHW image batch and the tile is gathered through `geom` (implicit im2col);
+// CONV > 0 is the number of filter taps when known at compile time, -1 any filter.
+template <int V, int K_T, int CT, int CONV = 0>
 __global__ __launch_bounds__(kEncThreads) void encode_tile_kernel(const float* __restrict__ X,
                                                                   int64_t ldx,
                                                                   const float* __restrict__ P,
@@ -36,7 +37,9 @@ __global__ __launch_bounds__(kEncThreads) void encode_tile_kernel(const float* _
     const int c0 = (int)(blockIdx.x % col_tiles) * CT;
     const int tid = threadIdx.x;
 
-    if (CONV)
+    if constexpr (CONV > 0)
+        stage_x_conv_taps<V, CT, CONV>(X, geom, N, C * V, row0, c0, xs, tid);
+    else if constexpr (CONV < 0)
         stage_x_conv<V, CT>(X, geom, N, C * V, row0, c0, xs, tid);
     else
         stage_x<V, CT>(X, ldx, N, C * V, row0, c0, xs, vec4, tid);
@@ -97,7 +100,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_generic_kernel(const float
     idx[i] = (uint8_t)best;
 }
 
-template <int V, int CT, bool CONV = false>
+template <int V, int CT, int CONV = 0>
 hipError_t launch_tile_ct(const float* P, int C, int K, const float* X, int64_t N, int64_t ldx,
                           uint8_t* idx, hipStream_t s, const ConvGeom& geom = ConvGeom{}) {
     const int64_t row_tiles = (N + kEncRows - 1) / kEncRows;
@@ -125,7 +128,7 @@ hipError_t launch_tile_ct(const float* P, int C, int K, const float* X, int64_t 
 // and the load latency in front of it are the whole run time, and the grid is too small to hide
 // them.  Below ~1024 workgroups a quarter-width tile (never under one codebook per wavefront)
 // gives four times the workgroups and a quarter of the chain.
-template <int V, bool CONV = false>
+template <int V, int CONV = 0>
 hipError_t launch_tile(const float* P, int C, int K, const float* X, int64_t N, int64_t ldx,
                        uint8_t* idx, hipStream_t s, const ConvGeom& geom = ConvGeom{}) {
     constexpr int CT = enc_tile_codebooks(V);
@@ -142,17 +145,28 @@ hipError_t launch_tile(const float* P, int C, int K, const float* X, int64_t N, 
 // 1x1) plus the other tiled lengths that divide common Cin * kh * kw.
 bool encode_conv_supported(int V) { return V == 1 || V == 2 || V == 3 || V == 4 || V == 8 || V == 9 || V == 16; }
 
+template <int V>
+hipError_t launch_conv_v(const float* P, int C, int K, const float* input, int64_t N, const ConvGeom& g,
+                         uint8_t* idx, hipStream_t s) {
+    const int taps = g.kh * g.kw;
+    if (taps == 1) return launch_tile<V, 1>(P, C, K, input, N, 0, idx, s, g);
+    if constexpr (V % 9 == 0) {
+        if (taps == 9) return launch_tile<V, 9>(P, C, K, input, N, 0, idx, s, g);
+    }
+    return launch_tile<V, -1>(P, C, K, input, N, 0, idx, s, g);
+}
+
 hipError_t launch_encode_conv(const float* P, int C, int K, int V, const float* input, int64_t B,
                               const ConvGeom& g, uint8_t* idx, hipStream_t s) {
     const int64_t N = B * g.Ho * g.Wo;
     switch (V) {
-        case 1: return launch_tile<1, true>(P, C, K, input, N, 0, idx, s, g);
-        case 2: return launch_tile<2, true>(P, C, K, input, N, 0, idx, s, g);
-        case 3: return launch_tile<3, true>(P, C, K, input, N, 0, idx, s, g);
-        case 4: return launch_tile<4, true>(P, C, K, input, N, 0, idx, s, g);
-        case 8: return launch_tile<8, true>(P, C, K, input, N, 0, idx, s, g);
-        case 9: return launch_tile<9, true>(P, C, K, input, N, 0, idx, s, g);
-        case 16: return launch_tile<16, true>(P, C, K, input, N, 0, idx, s, g);
+        case 1: return launch_conv_v<1>(P, C, K, input, N, g, idx, s);
+        case 2: return launch_conv_v<2>(P, C, K, input, N, g, idx, s);
+        case 3: return launch_conv_v<3>(P, C, K, input, N, g, idx, s);
+        case 4: return launch_conv_v<4>(P, C, K, input, N, g, idx, s);
+        case 8: return launch_conv_v<8>(P, C, K, input, N, g, idx, s);
+        case 9: return launch_conv_v<9>(P, C, K, input, N, g, idx, s);
+        case 16: return launch_conv_v<16>(P, C, K, input, N, g, idx, s);
         default: return hipErrorInvalidValue;
     }
 }

@@ -82,7 +82,9 @@ __device__ __forceinline__ void stage_x_conv(const float* __restrict__ input, co
                                              int D, int64_t row0, int c0, float* __restrict__ xs,
                                              int tid) {
     using E = EncTile<V, CT>;
+    static_assert(E::TW % 4 == 0, "tile rows are walked four columns at a time");
     const int r = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t n = row0 + r;
     const bool row_ok = n < N;
     const int pix = g.Ho * g.Wo;
@@ -93,17 +95,96 @@ __device__ __forceinline__ void stage_x_conv(const float* __restrict__ input, co
     // offset of (b, ci = 0, hi0, wi0); may lie outside the image, only used where in bounds
     const int64_t off0 = ((b * g.Cin) * g.H + hi0) * (int64_t)g.W + wi0;
     const int taps = g.kh * g.kw;
-    for (int col = __builtin_amdgcn_readfirstlane(tid >> 6); col < E::TW; col += 4) {
-        const int j = c0 * V + col;  // wave-uniform
+    // Per lane, one bit per filter tap: does the tap fall inside the image for this output pixel?
+    // (Filters of more than 32 taps test the coordinates per element instead.)
+    const bool use_mask = taps <= 32;  // uniform
+    uint32_t ok = 0;
+    if (use_mask && row_ok) {
+        int t = 0;
+        for (int rk = 0; rk < g.kh; ++rk) {
+            const bool h_ok = (unsigned)(hi0 + rk) < (unsigned)g.H;
+            for (int sk = 0; sk < g.kw; ++sk, ++t)
+                if (h_ok && (unsigned)(wi0 + sk) < (unsigned)g.W) ok |= 1u << t;
+        }
+    }
+    // Wave-uniform walk over the tile's columns: wave w takes columns w, w + 4, ...; the
+    // (channel, filter row, filter column) of the column advances by additions only.
+    int j = c0 * V + w;
+    int ci = j / taps;
+    int rk = (j - ci * taps) / g.kw;
+    int sk = j - ci * taps - rk * g.kw;
+    float* __restrict__ dst = xs + r * E::LS + w;
+#pragma unroll 4
+    for (int it = 0; it < E::TW / 4; ++it) {
         float val = 0.f;
         if (j < D) {
-            const int ci = j / taps, rs = j - ci * taps;
-            const int rk = rs / g.kw, sk = rs - rk * g.kw;
-            const int hi = hi0 + rk, wi = wi0 + sk;
-            if (row_ok && (unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W)
-                val = input[off0 + ((int64_t)ci * g.H + rk) * g.W + sk];
+            const bool inside = use_mask ? ((ok >> (rk * g.kw + sk)) & 1u) != 0
+                                         : (row_ok && (unsigned)(hi0 + rk) < (unsigned)g.H &&
+                                            (unsigned)(wi0 + sk) < (unsigned)g.W);
+            if (inside) val = input[off0 + ((int64_t)ci * g.H + rk) * g.W + sk];
         }
-        xs[r * E::LS + col] = val;
+        dst[4 * it] = val;
+        j += 4;
+        sk += 4;
+        while (sk >= g.kw) {
+            sk -= g.kw;
+            ++rk;
+        }
+        while (rk >= g.kh) {
+            rk -= g.kh;
+            ++ci;
+        }
+    }
+}
+
+// The same gather when the filter has TAPS = kh * kw taps known at compile time and a sub-vector
+// is whole channels' patches or whole pixels (V % TAPS == 0): 3x3 filters with V = 9 and 1x1
+// filters, the paper's two convolution settings (Sec. 6.1).  Wave w stages the columns of its own
+// codebooks, so (channel, tap) of every column is known when the loop is unrolled: per element
+// there remain one bit test, one address add, the load and the LDS write.
+template <int V, int CT, int TAPS, class Geom>
+__device__ __forceinline__ void stage_x_conv_taps(const float* __restrict__ input, const Geom& g,
+                                                  int64_t N, int D, int64_t row0, int c0,
+                                                  float* __restrict__ xs, int tid) {
+    using E = EncTile<V, CT>;
+    static_assert(V % TAPS == 0 && TAPS <= 32, "sub-vectors must be whole patches");
+    constexpr int COLS = E::CPW * V;  // columns per wavefront
+    const int r = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t n = row0 + r;
+    const bool row_ok = n < N;
+    const int pix = g.Ho * g.Wo;
+    const int64_t b = row_ok ? n / pix : 0;
+    const int p = row_ok ? (int)(n % pix) : 0;
+    const int hi0 = (p / g.Wo) * g.sh - g.ph;
+    const int wi0 = (p % g.Wo) * g.sw - g.pw;
+    const int64_t off0 = ((b * g.Cin) * g.H + hi0) * (int64_t)g.W + wi0;
+    uint32_t ok = 0;       // per lane: bit t = tap t lies inside the image
+    int tapoff[TAPS];      // uniform: offset of tap t from the patch origin
+    {
+        int rk = 0, sk = 0;
+#pragma unroll
+        for (int t = 0; t < TAPS; ++t) {
+            tapoff[t] = rk * g.W + sk;
+            if (row_ok && (unsigned)(hi0 + rk) < (unsigned)g.H && (unsigned)(wi0 + sk) < (unsigned)g.W)
+                ok |= 1u << t;
+            if (++sk == g.kw) {
+                sk = 0;
+                ++rk;
+            }
+        }
+    }
+    const int j0 = c0 * V + w * COLS;
+    const int64_t HW = (int64_t)g.H * g.W;
+    const int64_t ch_off = (int64_t)(j0 / TAPS) * HW;  // first channel of this wavefront
+    float* __restrict__ dst = xs + r * E::LS + w * COLS;
+#pragma unroll
+    for (int it = 0; it < COLS; ++it) {
+        constexpr int kT = TAPS;
+        const int tap = it % kT, chl = it / kT;
+        float val = 0.f;
+        if (j0 + it < D && (ok & (1u << tap))) val = input[off0 + ch_off + chl * HW + tapoff[tap]];
+        dst[it] = val;
     }
 }
 
