@@ -12,6 +12,8 @@
 // the chosen indices go back through LDS so that each row's CT index bytes leave as one segment.
 // The paper's second optimisation (splitting the arg-min compare chain for ILP) is unnecessary
 // here: 64 rows per wave already give independent chains.
+#include <algorithm>
+
 #include "encode_tile.h"
 #include "lutnn_kernels.h"
 
@@ -65,6 +67,116 @@ __global__ __launch_bounds__(kEncThreads) void encode_tile_kernel(const float* _
 #pragma unroll
             for (int b = 0; b < 4; ++b)
                 if (c + b < C) dst[b] = (uint8_t)(wv >> (8 * b));
+        }
+    }
+}
+
+// Convolution with a 9-tap filter and V = 9 (a sub-vector is one channel's patch; Sec. 6.1's
+// setting for 3x3 filters), staged by INPUT ROWS.  A workgroup owns 64 consecutive output pixels of
+// one image and CT channels.  Instead of the 64 x 9 patch values per channel it stages the band of
+// input rows those pixels touch - nrows x ncols floats per channel, zero filled outside the image,
+// read as contiguous runs - so every input element is loaded once, not once per tap, and the
+// arg-min code reads a lane's patch from LDS at (pixel offset) + (tap offset): consecutive lanes
+// are consecutive pixels, hence consecutive LDS words.
+//   bs_max  floats reserved per channel (the largest band of any tile; computed by the launcher)
+template <int K_T, int CT>
+__global__ __launch_bounds__(kEncThreads) void encode_conv9_band_kernel(
+    const float* __restrict__ input, const float* __restrict__ P, uint8_t* __restrict__ idx, int C,
+    int K_rt, ConvGeom g, int pix_tiles, int bs_max, int idx_dword_ok) {
+    constexpr int V = 9;
+    using E = EncTile<V, CT>;
+    extern __shared__ float band[];  // [CT][bs_max], then the index bytes [64][CT/4] dwords
+    uint32_t* is = reinterpret_cast<uint32_t*>(band + (size_t)CT * bs_max);
+
+    const int K = K_T ? K_T : K_rt;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col_tiles = (C + CT - 1) / CT;
+    const int c0 = (int)(blockIdx.x % col_tiles) * CT;
+    const int64_t rt = blockIdx.x / col_tiles;
+    const int64_t b = rt / pix_tiles;
+    const int pix = g.Ho * g.Wo;
+    const int p0 = (int)(rt % pix_tiles) * kEncRows;
+    const int p1 = min(p0 + kEncRows - 1, pix - 1);
+
+    // the band of this tile (all wave-uniform)
+    const int ho0 = p0 / g.Wo, ho1 = p1 / g.Wo;
+    const int h_lo = ho0 * g.sh - g.ph;
+    const int nrows = (ho1 - ho0) * g.sh + g.kh;
+    const bool one_row = ho0 == ho1;
+    const int w_lo = one_row ? (p0 - ho0 * g.Wo) * g.sw - g.pw : -g.pw;
+    const int ncols = one_row ? (p1 - p0) * g.sw + g.kw : (g.Wo - 1) * g.sw + g.kw;
+
+    // ---- stage: wave w takes channels w*CPW .. of the tile, lanes run along the columns
+    for (int j = 0; j < E::CPW; ++j) {
+        const int cl = w * E::CPW + j;
+        const int ci = c0 + cl;
+        const float* __restrict__ src = input + ((b * g.Cin + ci) * (int64_t)g.H) * g.W;
+        float* __restrict__ dst = band + (size_t)cl * bs_max;
+        for (int rr = 0; rr < nrows; ++rr) {
+            const int hi = h_lo + rr;
+            const bool row_in = ci < C && (unsigned)hi < (unsigned)g.H;  // uniform
+            for (int cc = lane; cc < ncols; cc += 64) {
+                const int wi = w_lo + cc;
+                float v = 0.f;
+                if (row_in && (unsigned)wi < (unsigned)g.W) v = src[(int64_t)hi * g.W + wi];
+                dst[rr * ncols + cc] = v;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- this lane's pixel and the LDS offsets of its nine taps within a channel's band
+    const int p = min(p0 + lane, p1);  // lanes past the last pixel repeat it (never stored)
+    const int ho = p / g.Wo, wo = p - ho * g.Wo;
+    const int base = (ho - ho0) * g.sh * ncols + (wo * g.sw - g.pw - w_lo);
+    int toff[V];
+    {
+        int rk = 0, sk = 0;
+#pragma unroll
+        for (int t = 0; t < V; ++t) {
+            toff[t] = base + rk * ncols + sk;
+            if (++sk == g.kw) {
+                sk = 0;
+                ++rk;
+            }
+        }
+    }
+    uint32_t packed[E::PW];
+#pragma unroll
+    for (int j = 0; j < E::PW; ++j) packed[j] = 0;
+#pragma unroll
+    for (int j = 0; j < E::CPW; ++j) {
+        const int cl = w * E::CPW + j;
+        const int c = c0 + cl;  // wave-uniform
+        uint32_t best = 0;
+        if (c < C) {
+            const float* __restrict__ ch = band + (size_t)cl * bs_max;
+            float x[V];
+#pragma unroll
+            for (int t = 0; t < V; ++t) x[t] = ch[toff[t]];
+            best = nearest_centroid<V, K_T>(x, P + (size_t)c * K * V, K);
+        }
+        packed[j / 4] |= best << (8 * (j % 4));
+    }
+    store_index_bytes<V, CT>(is + lane * (CT / 4), w * E::CPW, packed);
+    __syncthreads();
+
+    const int64_t n0 = b * pix + p0;
+    const int rows = p1 - p0 + 1;
+    for (int i = tid; i < kEncRows * (CT / 4); i += kEncThreads) {
+        const int r = i / (CT / 4), j = i % (CT / 4);
+        const int c = c0 + 4 * j;
+        if (r >= rows || c >= C) continue;
+        const uint32_t wv = is[i];
+        uint8_t* dst = idx + (n0 + r) * (int64_t)C + c;
+        if (idx_dword_ok) {
+            *reinterpret_cast<uint32_t*>(dst) = wv;
+        } else {
+#pragma unroll
+            for (int bb = 0; bb < 4; ++bb)
+                if (c + bb < C) dst[bb] = (uint8_t)(wv >> (8 * bb));
         }
     }
 }
@@ -145,13 +257,53 @@ hipError_t launch_tile(const float* P, int C, int K, const float* X, int64_t N, 
 // 1x1) plus the other tiled lengths that divide common Cin * kh * kw.
 bool encode_conv_supported(int V) { return V == 1 || V == 2 || V == 3 || V == 4 || V == 8 || V == 9 || V == 16; }
 
+// Largest band (floats per channel) of any 64-pixel tile of this geometry; see the band kernel.
+int64_t conv_band_floats(const ConvGeom& g) {
+    const int64_t one_row = (int64_t)g.kh * ((int64_t)std::min(kEncRows - 1, g.Wo - 1) * g.sw + g.kw);
+    const int64_t span = std::min<int64_t>(g.Ho, (kEncRows - 2 + g.Wo) / g.Wo + 1);  // output rows a tile can touch
+    const int64_t many = ((span - 1) * g.sh + g.kh) * ((int64_t)(g.Wo - 1) * g.sw + g.kw);
+    return span >= 2 ? std::max(one_row, many) : one_row;
+}
+
+template <int CT>
+hipError_t launch_conv9_band(const float* P, int C, int K, const float* input, int64_t B,
+                             const ConvGeom& g, uint8_t* idx, int64_t bs_max, hipStream_t s) {
+    const int64_t pix_tiles = ((int64_t)g.Ho * g.Wo + kEncRows - 1) / kEncRows;
+    const int64_t blocks = B * pix_tiles * ((C + CT - 1) / CT);
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const size_t shmem = (size_t)CT * bs_max * 4 + (size_t)kEncRows * (CT / 4) * 4;
+    const int idx_dword_ok = (C % 4 == 0) && ((reinterpret_cast<uintptr_t>(idx) & 3) == 0);
+    dim3 grid((unsigned)blocks), block(kEncThreads);
+    if (K == 16)
+        hipLaunchKernelGGL((encode_conv9_band_kernel<16, CT>), grid, block, shmem, s, input, P, idx, C, K, g,
+                           (int)pix_tiles, (int)bs_max, idx_dword_ok);
+    else if (K == 8)
+        hipLaunchKernelGGL((encode_conv9_band_kernel<8, CT>), grid, block, shmem, s, input, P, idx, C, K, g,
+                           (int)pix_tiles, (int)bs_max, idx_dword_ok);
+    else
+        hipLaunchKernelGGL((encode_conv9_band_kernel<0, CT>), grid, block, shmem, s, input, P, idx, C, K, g,
+                           (int)pix_tiles, (int)bs_max, idx_dword_ok);
+    return hipGetLastError();
+}
+
 template <int V>
-hipError_t launch_conv_v(const float* P, int C, int K, const float* input, int64_t N, const ConvGeom& g,
-                         uint8_t* idx, hipStream_t s) {
+hipError_t launch_conv_v(const float* P, int C, int K, const float* input, int64_t B, int64_t N,
+                         const ConvGeom& g, uint8_t* idx, hipStream_t s) {
     const int taps = g.kh * g.kw;
     if (taps == 1) return launch_tile<V, 1>(P, C, K, input, N, 0, idx, s, g);
-    if constexpr (V % 9 == 0) {
-        if (taps == 9) return launch_tile<V, 9>(P, C, K, input, N, 0, idx, s, g);
+    if constexpr (V == 9) {
+        if (taps == 9) {
+            // rows of the input staged once, if the widest band fits 48 KiB of LDS
+            constexpr int CT = enc_tile_codebooks(9), CT_SMALL = 4;
+            const int64_t bs = conv_band_floats(g);
+            const int64_t pix_tiles = ((int64_t)g.Ho * g.Wo + kEncRows - 1) / kEncRows;
+            const bool small_grid = B * pix_tiles * ((C + CT - 1) / CT) < 1024;
+            if (small_grid && CT_SMALL * bs * 4 <= 48 * 1024)
+                return launch_conv9_band<CT_SMALL>(P, C, K, input, B, g, idx, bs, s);
+            if (!small_grid && CT * bs * 4 <= 48 * 1024)
+                return launch_conv9_band<CT>(P, C, K, input, B, g, idx, bs, s);
+            return launch_tile<V, 9>(P, C, K, input, N, 0, idx, s, g);
+        }
     }
     return launch_tile<V, -1>(P, C, K, input, N, 0, idx, s, g);
 }
@@ -160,13 +312,13 @@ hipError_t launch_encode_conv(const float* P, int C, int K, int V, const float* 
                               const ConvGeom& g, uint8_t* idx, hipStream_t s) {
     const int64_t N = B * g.Ho * g.Wo;
     switch (V) {
-        case 1: return launch_conv_v<1>(P, C, K, input, N, g, idx, s);
-        case 2: return launch_conv_v<2>(P, C, K, input, N, g, idx, s);
-        case 3: return launch_conv_v<3>(P, C, K, input, N, g, idx, s);
-        case 4: return launch_conv_v<4>(P, C, K, input, N, g, idx, s);
-        case 8: return launch_conv_v<8>(P, C, K, input, N, g, idx, s);
-        case 9: return launch_conv_v<9>(P, C, K, input, N, g, idx, s);
-        case 16: return launch_conv_v<16>(P, C, K, input, N, g, idx, s);
+        case 1: return launch_conv_v<1>(P, C, K, input, B, N, g, idx, s);
+        case 2: return launch_conv_v<2>(P, C, K, input, B, N, g, idx, s);
+        case 3: return launch_conv_v<3>(P, C, K, input, B, N, g, idx, s);
+        case 4: return launch_conv_v<4>(P, C, K, input, B, N, g, idx, s);
+        case 8: return launch_conv_v<8>(P, C, K, input, B, N, g, idx, s);
+        case 9: return launch_conv_v<9>(P, C, K, input, B, N, g, idx, s);
+        case 16: return launch_conv_v<16>(P, C, K, input, B, N, g, idx, s);
         default: return hipErrorInvalidValue;
     }
 }

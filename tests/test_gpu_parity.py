@@ -405,6 +405,13 @@ CONV_SHAPES = [
     (2, 4, 15, 9, (3, 5), (2, 1), (1, 2), 2, 16),     # rectangular filter, mixed stride / padding
     (1, 32, 8, 8, (1, 1), (2, 2), (0, 0), 16, 16),    # strided 1x1, V = 16
     (1, 5, 6, 6, (5, 5), (1, 1), (2, 2), 1, 5),       # padding wider than the image border, V = 1
+    # nine-tap filters with V = 9: input rows staged once (band kernel)
+    (2, 10, 7, 7, (3, 3), (1, 1), (1, 1), 9, 16),     # 49 pixels per image: a tile spans 7+ rows
+    (1, 6, 5, 150, (3, 3), (1, 1), (1, 1), 9, 16),    # wide image: tiles inside one row and across two
+    (1, 20, 9, 70, (3, 3), (2, 2), (0, 0), 9, 5),     # stride 2, no padding, run-time K, ragged channels
+    (1, 8, 12, 40, (1, 9), (1, 1), (0, 4), 9, 16),    # 1 x 9 filter
+    (1, 8, 40, 12, (9, 1), (1, 2), (4, 0), 9, 8),     # 9 x 1 filter, mixed strides
+    (3, 33, 14, 14, (3, 3), (1, 1), (1, 1), 9, 16),   # batch of 3, 33 channels
 ]
 
 
