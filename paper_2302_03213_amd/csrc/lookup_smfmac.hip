@@ -58,16 +58,12 @@ namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 
-constexpr int TM = 4;                 // 32-row blocks per wave
-constexpr int WAVE_ROWS = TM * 32;    // 128
-constexpr int BM = 4 * WAVE_ROWS;     // rows per workgroup (512)
 constexpr int BN = 128;               // columns per workgroup
 constexpr int NBUF = 4;               // LDS ring depth, stages
 constexpr int SC = 16;                // codebooks per stage
 constexpr int KSTEPS = 4;             // MFMA steps per stage, 4 codebooks each
 constexpr int STAGE_VECS = SC * BN;   // uint4 per stage buffer (32 KiB)
 constexpr int B_LOADS = 8;            // table loads per wave per stage
-constexpr int I_LOADS = TM;           // index loads per wave per super-stage
 constexpr int kComputeUnits = 256;    // MI355X: 8 XCDs x 32 CUs
 
 // 64 lanes x 16 bytes global -> LDS at (lds_base + LDS_IMM) + 16 * lane; see dma16().
@@ -82,10 +78,22 @@ __device__ __forceinline__ void dma16_at(uint32_t lds_base, const void* sbase, u
         : "memory", "m0", "scc");
 }
 
+// TM = 32-row blocks per wavefront: the workgroup tile is 128*TM rows x 128 columns.  TM = 4 is
+// the efficient shape; 2 and 1 exist so that problems with few rows still spread over the chip.
+template <int TM>
 __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const uint4* __restrict__ packed, const float* __restrict__ scale, const float* __restrict__ bias,
     int C, int M, int Mp, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y,
     int64_t ldy, int row_tiles, int64_t tiles) {
+    constexpr int WAVE_ROWS = TM * 32;
+    constexpr int BM = 4 * WAVE_ROWS;  // rows per workgroup
+    constexpr int I_LOADS = TM;        // index loads per wave per super-stage
+    constexpr int S = 4 * TM;          // SMFMAC slots per step
+    // index-word half-operations: 8*TM per super-stage, TM per step; the sequence of a super-stage
+    // starts at this position of the one before it (after its index bytes were read from LDS in
+    // step 0 of the second stage, early enough that the words of d = 0 are finished two steps later)
+    constexpr int HSEQ = 8 * TM;
+    constexpr int HSTART = TM == 1 ? 5 : 4 * TM + TM / 2;
     __shared__ uint4 ring[NBUF * STAGE_VECS];  // 4 x 32 KiB table slabs
     __shared__ uint4 ibuf[4][TM][64];          // [wave][row block][lane]: one super-stage of indices
     __shared__ uint32_t plut[256];             // position words by byte pair, see IdxWords
@@ -204,7 +212,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
         wq.sh[i][2] = v.z;
         wq.sh[i][3] = v.w;
     };
-    // Half-operation k = 0..31 of a super-stage's index words: word (i, d) = ((k >> 1) & 3, k >> 3),
+    // Half-operation k = 0..8*TM-1 of a super-stage's index words: word (i, d) = ((k>>1) % TM, (k>>1) / TM),
     // first half = position word of codebooks 4d, 4d+1; second half = that of 4d+2, 4d+3, and the
     // shift word.  Words are finished in the order d = 0, 1, 2, 3, the order the steps use them.
     uint32_t pair = 0;  // carried from the first half of a word to the second
@@ -212,7 +220,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
         return *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(plut) + byte_off);
     };
     auto idx_halfop = [&](IdxWords& wq, int k) {
-        const int d = k >> 3, i = (k >> 1) & 3;
+        const int d = (k >> 1) / TM, i = (k >> 1) % TM;
         if ((k & 1) == 0) {
             const uint32_t raw = wq.sh[i][d];
             // bits 2-9 = 4 (p0 | p1 << 4), bits 18-25 = 4 (p2 | p3 << 4): byte offsets into plut
@@ -238,11 +246,16 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
 
     // ---- prologue: stages 0..2 and the indices of super-stage 0 (into registers) and 1 (in
     // flight); afterwards the load state points at stage 3 / super-stage 2.
-    load_idx(I0{});
-    load_idx(I1{});
-    load_idx(I2{});
-    load_idx(I3{});
-    ip += 32;
+    auto load_idx_all = [&]() {
+        load_idx(I0{});
+        if constexpr (TM > 1) load_idx(I1{});
+        if constexpr (TM > 2) {
+            load_idx(I2{});
+            load_idx(I3{});
+        }
+        ip += 32;
+    };
+    load_idx_all();
     auto load_stage = [&](auto fb_c) {
         load_b(fb_c, I0{});
         load_b(fb_c, I1{});
@@ -272,15 +285,9 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
 #pragma unroll
     for (int i = 0; i < TM; ++i) read_ibuf(wq[0], i);
 #pragma unroll
-    for (int k = 0; k < 14; ++k) idx_halfop(wq[0], k);  // the stage loop continues with k = 14
+    for (int k = 0; k < HSEQ - HSTART; ++k) idx_halfop(wq[0], k);  // the stage loop continues from here
     __syncthreads();  // every lane has its words before the buffer is refilled
-    if (supers > 1) {
-        load_idx(I0{});
-        load_idx(I1{});
-        load_idx(I2{});
-        load_idx(I3{});
-        ip += 32;
-    }
+    if (supers > 1) load_idx_all();
 #pragma unroll
     for (int r = 0; r < 8; ++r) load_b_operand(0, 0, 0, r);
 #pragma unroll
@@ -304,35 +311,46 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
         for (int j = 0; j < KSTEPS; ++j) {
             const int tstep = 4 * SP + j;  // step within the super-stage
 #pragma unroll
-            for (int q = 0; q < 16; ++q) {
+            for (int q = 0; q < S; ++q) {
                 __builtin_amdgcn_sched_barrier(0);
                 {
                     // column-tile major: the B tiles are read in this order a step earlier, so
                     // the tile read last is also used last
-                    const int i = q & 3, tn = q >> 2;
+                    const int i = q % TM, tn = q / TM;
                     const u64x2 av = a[j & 1][i];
                     const v4i a4 = {(int)(uint32_t)av[0], (int)(uint32_t)(av[0] >> 32),
                                     (int)(uint32_t)av[1], (int)(uint32_t)(av[1] >> 32)};
                     acc[i][tn] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(
                         a4, b[j & 1][tn], acc[i][tn], (int)wcur.pos[i][tstep], 0, 0);
                 }
-                // B operands of the next step; after the last step: the first step of the next
-                // stage, in the first eight slots so that the reads have returned when the
-                // barrier waits for the LDS counter
+                // B operands of the next step, eight LDS reads spread over the slots; after the
+                // last step: the first step of the next stage, in the first slots so that the
+                // reads have returned when the barrier waits for the LDS counter
                 if (j + 1 < KSTEPS) {
-                    if ((q & 1) == 0) load_b_operand((j + 1) & 1, SB, j + 1, q >> 1);
-                } else if (q < 8) {
-                    load_b_operand(0, (SB + 1) % NBUF, 0, q);
+                    if constexpr (S == 16) {
+                        if ((q & 1) == 0) load_b_operand((j + 1) & 1, SB, j + 1, q >> 1);
+                    } else if constexpr (S == 8) {
+                        load_b_operand((j + 1) & 1, SB, j + 1, q);
+                    } else {
+                        load_b_operand((j + 1) & 1, SB, j + 1, 2 * q);
+                        load_b_operand((j + 1) & 1, SB, j + 1, 2 * q + 1);
+                    }
+                } else {
+                    if constexpr (S >= 8) {
+                        if (q < 8) load_b_operand(0, (SB + 1) % NBUF, 0, q);
+                    } else {
+                        load_b_operand(0, (SB + 1) % NBUF, 0, 2 * q);
+                        load_b_operand(0, (SB + 1) % NBUF, 0, 2 * q + 1);
+                    }
                 }
                 // second stage of a super-stage: pick up the next super-stage's index bytes
                 // (their loads were issued a super-stage ago and awaited at the end of the
                 // previous stage; past the last super-stage this reads stale, unused data)
-                if (SP == 1 && j == 0 && (q & 1) == 0 && q < 8) read_ibuf(wnext, q >> 1);
-                // index-word half-operations: 32 per super-stage, one every fourth slot; the
-                // sequence of a super-stage starts in slot 9 of step 0 of the stage before it
+                if (SP == 1 && j == 0 && (q & 1) == 0 && q / 2 < TM) read_ibuf(wnext, q / 2);
+                // index-word half-operations, one every fourth slot
                 if ((q & 3) == 1) {
-                    const int n = (4 * SP + j) * 4 + (q >> 2);
-                    idx_halfop(n >= 18 ? wnext : wcur, (n - 18) & 31);
+                    const int n = (4 * SP + j) * TM + (q >> 2);
+                    idx_halfop(n >= HSTART ? wnext : wcur, (n - HSTART + HSEQ) % HSEQ);
                 }
                 // A values of the next step, one row block at a time
                 if ((q & 3) == 3) {
@@ -346,19 +364,19 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
                 }
                 // table loads of stage s + 3: rows one per step, two halves
                 if (do_fetch) {
-                    if (q == 2) {
+                    if (q == (S >= 8 ? 2 : 0)) {
                         if (j == 0) load_b(std::integral_constant<int, FB>{}, I0{});
                         if (j == 1) load_b(std::integral_constant<int, FB>{}, I2{});
                         if (j == 2) load_b(std::integral_constant<int, FB>{}, std::integral_constant<int, 4>{});
                         if (j == 3) load_b(std::integral_constant<int, FB>{}, std::integral_constant<int, 6>{});
                     }
-                    if (q == 10) {
+                    if (q == (S >= 8 ? 2 + S / 2 : 2)) {
                         if (j == 0) load_b(std::integral_constant<int, FB>{}, I1{});
                         if (j == 1) load_b(std::integral_constant<int, FB>{}, I3{});
                         if (j == 2) load_b(std::integral_constant<int, FB>{}, std::integral_constant<int, 5>{});
                         if (j == 3) load_b(std::integral_constant<int, FB>{}, std::integral_constant<int, 7>{});
                     }
-                    if (q == 12) {
+                    if (q == S - 1) {
                         if (j + 1 < KSTEPS)
                             bp += rs1;
                         else
@@ -368,11 +386,17 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
                 // the index buffer is free once its reads (step 0) have returned; refill it in
                 // step 3 with the super-stage after next
                 if (do_idx && j == 3) {
-                    if (q == 4) load_idx(I0{});
-                    if (q == 6) load_idx(I1{});
-                    if (q == 12) load_idx(I2{});
-                    if (q == 14) load_idx(I3{});
-                    if (q == 15) ip += 32;
+                    if constexpr (TM == 1) {
+                        if (q == 3) load_idx(I0{});
+                    } else {
+                        if (q == 4) load_idx(I0{});
+                        if (q == 6) load_idx(I1{});
+                    }
+                    if constexpr (TM > 2) {
+                        if (q == 12) load_idx(I2{});
+                        if (q == 14) load_idx(I3{});
+                    }
+                    if (q == S - 1) ip += 32;
                 }
             }
         }
@@ -431,16 +455,10 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     }
 }
 
-}  // namespace
-
-bool smfmac_supported(int C, int K, const uint8_t* idx) {
-    return K <= 16 && C % 32 == 0 && (reinterpret_cast<uintptr_t>(idx) & 15) == 0;
-}
-
-hipError_t launch_lookup_smfmac_i8(const int8_t* packed, const float* scale, const float* bias, int C,
-                                   int K, int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,
-                                   hipStream_t s) {
-    if (!smfmac_supported(C, K, idx)) return hipErrorInvalidValue;
+template <int TM>
+hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias, int C, int M,
+                     const uint8_t* idx, int64_t N, float* Y, int64_t ldy, hipStream_t s) {
+    constexpr int BM = 128 * TM;
     const int Mp = (int)packed_cols(M);
     const int64_t col_tiles = (M + BN - 1) / BN;  // the packed table is padded to 256 columns
     const int64_t row_tiles = (N + BM - 1) / BM;
@@ -451,10 +469,34 @@ hipError_t launch_lookup_smfmac_i8(const int8_t* packed, const float* scale, con
     // Stream several tiles per workgroup when the ring phase carries over from tile to tile:
     // one workgroup per compute unit (the kernel's LDS footprint allows only one anyway).
     if (C % 64 == 0 && blocks > kComputeUnits) blocks = kComputeUnits;
-    hipLaunchKernelGGL(lookup_smfmac_i8_kernel, dim3((unsigned)blocks), dim3(kMfmaThreads), 0, s,
+    hipLaunchKernelGGL(lookup_smfmac_i8_kernel<TM>, dim3((unsigned)blocks), dim3(kMfmaThreads), 0, s,
                        reinterpret_cast<const uint4*>(packed), scale, bias, C, M, Mp, idx, N, Y, ldy,
                        (int)row_tiles, tiles);
     return hipGetLastError();
+}
+
+}  // namespace
+
+bool smfmac_supported(int C, int K, const uint8_t* idx) {
+    return K <= 16 && C % 32 == 0 && (reinterpret_cast<uintptr_t>(idx) & 15) == 0;
+}
+
+hipError_t launch_lookup_smfmac_i8(const int8_t* packed, const float* scale, const float* bias, int C,
+                                   int K, int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,
+                                   hipStream_t s) {
+    if (!smfmac_supported(C, K, idx)) return hipErrorInvalidValue;
+    // Tile height.  512 rows amortise the table slab best, but the tiles have to cover the chip:
+    // price each height as (rounds of 256 workgroups) x (measured time of one tile relative to
+    // the 512-row tile: 0.56 for 256 rows, 0.42 for 128 - the slab traffic does not shrink).
+    const int64_t col_tiles = (M + BN - 1) / BN;
+    auto cost = [&](int64_t bm, double rel) {
+        const int64_t tiles = ((N + bm - 1) / bm) * col_tiles;
+        return (double)((tiles + kComputeUnits - 1) / kComputeUnits) * rel;
+    };
+    const double c4 = cost(512, 1.0), c2 = cost(256, 0.56), c1 = cost(128, 0.42);
+    if (c4 <= c2 && c4 <= c1) return launch_tm<4>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
+    if (c2 <= c1) return launch_tm<2>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
+    return launch_tm<1>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
 }
 
 }  // namespace lutnn

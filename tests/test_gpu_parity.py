@@ -155,6 +155,10 @@ SMFMAC_SHAPES = [
     # N, C, K, M   (C % 32 == 0)
     (1, 32, 16, 1), (130, 64, 16, 64), (513, 96, 16, 250), (1025, 384, 16, 513), (700, 32, 7, 100),
     (512, 160, 16, 128), (300, 128, 1, 40), (2000, 224, 16, 130),
+    # tile heights: the shapes above take 128-row tiles; 512 rows here ...
+    (2100, 64, 16, 3968),
+    # ... and 256 rows, several tiles per workgroup, here
+    (4700, 64, 16, 4096),
 ]
 
 
