@@ -36,6 +36,7 @@ def _lib():
         lib.lutnn_oracle_build_table_f32.argtypes = [_f32p, _f32p, ctypes.c_int64, ctypes.c_int,
                                                      ctypes.c_int, ctypes.c_int, ctypes.c_int, _f32p]
         lib.lutnn_oracle_quantize_i8.argtypes = [_f32p, ctypes.c_int64, _i8p, _f32p]
+        lib.lutnn_oracle_quantize.argtypes = [_f32p, ctypes.c_int64, ctypes.c_int, _i8p, _f32p]
         lib.lutnn_oracle_encode.argtypes = [_f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int, _f32p,
                                             ctypes.c_int64, ctypes.c_int64, _u8p]
         lib.lutnn_oracle_distances_f64.argtypes = [_f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -88,6 +89,27 @@ def quantize_i8(Tf):
     s = np.zeros(1, dtype=np.float32)
     _lib().lutnn_oracle_quantize_i8(_ptr(Tf, _f32p), Tf.size, _ptr(q, _i8p), _ptr(s, _f32p))
     return q, np.float32(s[0])
+
+
+def quantize(Tf, bits):
+    """Sec. 3.3 with n = bits: symmetric, one scale per layer, |q| <= 2^(bits-1) - 1.  Returns
+    (q int8 - one entry per byte also for bits < 8 -, s float32)."""
+    assert 2 <= bits <= 8
+    Tf = _c(Tf, np.float32)
+    q = np.empty(Tf.shape, dtype=np.int8)
+    s = np.zeros(1, dtype=np.float32)
+    _lib().lutnn_oracle_quantize(_ptr(Tf, _f32p), Tf.size, bits, _ptr(q, _i8p), _ptr(s, _f32p))
+    return q, np.float32(s[0])
+
+
+def pack_nibbles(q):
+    """Storage format of a 4-bit table: [..., M] int8 in [-8, 7] -> [..., ceil(M/2)] uint8, even
+    column in the low nibble, two's complement.  Layout only, no arithmetic of the method."""
+    q = np.asarray(q, dtype=np.int8)
+    if q.shape[-1] % 2:
+        q = np.concatenate([q, np.zeros(q.shape[:-1] + (1,), np.int8)], axis=-1)
+    u = q.astype(np.uint8) & 0xF
+    return (u[..., 0::2] | (u[..., 1::2] << 4)).astype(np.uint8)
 
 
 def encode(P, X):

@@ -82,24 +82,32 @@ ORACLE_API void lutnn_oracle_build_table_f32(const float* P, const float* W, int
 }
 
 /*
- * Sec. 3.3: r = s*(q - z) with z = 0, n = 8: s = max|value| / (2^(n-1) - 1).
- * One scale for the whole layer table of `count` entries.
+ * Sec. 3.3: r = s*(q - z) with z = 0 and n bits: s = max|value| / (2^(n-1) - 1),
+ * q = round(value / s) in [-(2^(n-1) - 1), 2^(n-1) - 1].  One scale for the whole layer table of
+ * `count` entries; q is returned one entry per int8 whatever n is (2 <= n <= 8).
  */
-ORACLE_API void lutnn_oracle_quantize_i8(const float* Tf, int64_t count, int8_t* q,
-                                         float* scale_out) {
+ORACLE_API void lutnn_oracle_quantize(const float* Tf, int64_t count, int bits, int8_t* q,
+                                      float* scale_out) {
+    const float qmax = (float)((1 << (bits - 1)) - 1);
     float amax = 0.0f;
     for (int64_t i = 0; i < count; ++i) {
         float a = fabsf(Tf[i]);
         if (a > amax) amax = a;
     }
-    float s = (amax == 0.0f) ? 1.0f : amax / 127.0f;
+    float s = (amax == 0.0f) ? 1.0f : amax / qmax;
     for (int64_t i = 0; i < count; ++i) {
         float r = nearbyintf(Tf[i] / s); /* default rounding mode: half to even */
-        if (r > 127.0f) r = 127.0f;
-        if (r < -127.0f) r = -127.0f;
+        if (r > qmax) r = qmax;
+        if (r < -qmax) r = -qmax;
         q[i] = (int8_t)r;
     }
     *scale_out = s;
+}
+
+/* n = 8, the paper's deployed setting. */
+ORACLE_API void lutnn_oracle_quantize_i8(const float* Tf, int64_t count, int8_t* q,
+                                         float* scale_out) {
+    lutnn_oracle_quantize(Tf, count, 8, q, scale_out);
 }
 
 /*

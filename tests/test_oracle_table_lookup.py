@@ -62,6 +62,42 @@ def test_quantize_rounds_half_to_even_and_handles_zero_table():
     assert s == np.float32(1.0) and not q.any()
 
 
+@pytest.mark.parametrize("bits", [4, 8, 6])
+def test_quantize_n_bits_closed_forms(bits):
+    """Sec. 3.3 with n bits: s = max|value| / (2^(n-1) - 1); checked for n = 4 (the INT4 table of
+    Sec. 6.4) against the same closed forms as n = 8."""
+    qmax = 2 ** (bits - 1) - 1
+    w = wl.make_layer("t", 1, 5, 16, 4, 37, "i8", seed=34)
+    Tf = oracle.build_table_f32(w.P, w.W)
+    q, s = oracle.quantize(Tf, bits)
+    assert s == np.float32(np.abs(Tf).max()) / np.float32(qmax)
+    where = np.unravel_index(np.abs(Tf).argmax(), Tf.shape)
+    assert int(q[where]) == qmax * int(np.sign(Tf[where]))
+    assert q.min() >= -qmax and q.max() <= qmax
+    err = np.abs(q.astype(np.float64) * float(s) - Tf.astype(np.float64))
+    assert err.max() <= float(s) * 0.5 * (1 + 1e-5)
+    # independent formula, evaluated in double where the fp32 quotient is far from a half
+    ratio = Tf.astype(np.float64) / float(s)
+    safe = np.abs(ratio - np.floor(ratio) - 0.5) > 1e-3
+    np.testing.assert_array_equal(q[safe], np.rint(ratio[safe]).astype(np.int8))
+    if bits == 8:
+        q8, s8 = oracle.quantize_i8(Tf)
+        assert s8 == s
+        np.testing.assert_array_equal(q8, q)
+
+
+def test_quantize_4_bits_half_to_even_and_nibble_packing():
+    Tf = np.array([[7.0, 0.5, 1.5, 2.5, -0.5], [-1.5, -2.5, 3.49, -6.5, -7.0]], dtype=np.float32)
+    q, s = oracle.quantize(Tf, 4)
+    assert s == np.float32(1.0)
+    np.testing.assert_array_equal(q, [[7, 0, 2, 2, 0], [-2, -2, 3, -6, -7]])
+    packed = oracle.pack_nibbles(q)  # even column in the low nibble, two's complement, zero padded
+    assert packed.dtype == np.uint8 and packed.shape == (2, 3)
+    np.testing.assert_array_equal(packed, [[0x07, 0x22, 0x00], [0xEE, 0xA3, 0x09]])
+    q0, s0 = oracle.quantize(np.zeros((3, 4), np.float32), 4)
+    assert s0 == np.float32(1.0) and not q0.any()
+
+
 def test_quantize_is_symmetric():
     w = wl.make_layer("t", 1, 3, 16, 2, 9, "i8", seed=33)
     Tf = oracle.build_table_f32(w.P, w.W)
