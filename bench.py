@@ -52,6 +52,8 @@ def main():
                     choices=["fc_large", "fc_small", "conv_resnet18", "bert_ffn_up", "bert_layer",
                              "paper_kv", "conv_resnet18_b32"])
     ap.add_argument("--variant", default="auto", choices=["auto", "lds", "mfma", "smfmac", "fused"])
+    ap.add_argument("--int4", action="store_true",
+                    help="quantise the INT8 workloads' tables to 4 bits instead (Sec. 3.3 with n = 4)")
     ap.add_argument("--cpu-sample-rows", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -77,6 +79,8 @@ def main():
     dev_layers = []
     for w in layers:
         dt = lut.TABLE_I8 if w.table_dtype == "i8" else lut.TABLE_F32
+        if args.int4 and dt == lut.TABLE_I8:
+            dt = lut.TABLE_I4
         P, W = torch.from_numpy(w.P).cuda(), torch.from_numpy(w.W).cuda()
         bias = torch.from_numpy(w.bias).cuda() if w.bias is not None else None
         layer = lut.build_table(P, W, dt, bias=bias)
@@ -219,7 +223,7 @@ def main():
             Tf = oracle.build_table_f32(w.P, w.W)  # offline, untimed like on the GPU
             Xs = np.ascontiguousarray(w.X[:n])
             if w.table_dtype == "i8":
-                q, s = oracle.quantize_i8(Tf)
+                q, s = oracle.quantize(Tf, 4 if args.int4 else 8)
                 c0 = time.perf_counter()
                 y = oracle.linear_i8(w.P, q, s, Xs, w.bias)
             else:
@@ -238,7 +242,8 @@ def main():
                          "%.2f s wall" % (n_cpu // len(dev_layers), args.workload, t_cpu)}
 
     w_desc = "; ".join("%s N=%d D=%d M=%d V=%d C=%d K=%d %s table" %
-                       (w.name, w.N, w.D, w.M, w.V, w.C, w.K, w.table_dtype)
+                       (w.name, w.N, w.D, w.M, w.V, w.C, w.K,
+                        "i4" if (args.int4 and w.table_dtype == "i8") else w.table_dtype)
                        for (w, *_r) in dev_layers)
     out = {
         "metric": "lut_linear_rows_per_s", "value": round(rows / sec_per_step, 1), "unit": "rows/s",

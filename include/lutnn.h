@@ -48,7 +48,10 @@ typedef enum {
 
 typedef enum {
     LUTNN_TABLE_F32 = 0, /* T[C][K][M] fp32                                   */
-    LUTNN_TABLE_I8 = 1   /* T[C][K][M] int8 + one fp32 scale (Sec. 3.3, n = 8) */
+    LUTNN_TABLE_I8 = 1,  /* T[C][K][M] int8 + one fp32 scale (Sec. 3.3, n = 8) */
+    LUTNN_TABLE_I4 = 2   /* T[C][K][ceil(M/2)] bytes, two 4-bit two's-complement entries per
+                            byte, even column in the low nibble, + one fp32 scale (Sec. 3.3 with
+                            n = 4: the INT4 table of Sec. 6.4)                        */
 } lutnn_table_dtype;
 
 typedef enum {
@@ -73,10 +76,12 @@ typedef struct {
     int32_t table_dtype;     /* lutnn_table_dtype                                              */
     int32_t reserved;        /* must be 0                                                      */
     const float* centroids;  /* P[C][K][V] fp32 (needed by encode / linear)                    */
-    const void* table;       /* T[C][K][M], m fastest, int8 or fp32 (needed by the LDS variant) */
-    const void* table_packed;/* INT8 only: MFMA operand layout written by lutnn_build_table,
-                                lutnn_packed_bytes() bytes, 16-byte aligned; NULL if absent    */
-    const float* scale;      /* INT8 only: device pointer to the layer's single fp32 scale      */
+    const void* table;       /* T[C][K][M], m fastest, in the layout of table_dtype (needed by the
+                                LDS variant)                                                   */
+    const void* table_packed;/* INT8 / INT4: MFMA operand layout (one int8 per entry for both)
+                                written by lutnn_build_table, lutnn_packed_bytes() bytes,
+                                16-byte aligned; NULL if absent                                */
+    const float* scale;      /* INT8 / INT4: device pointer to the layer's single fp32 scale    */
     const float* bias;       /* [M] fp32 or NULL                                               */
 } lutnn_layer;
 
@@ -84,8 +89,8 @@ typedef struct {
 LUTNN_API size_t lutnn_table_bytes(int32_t C, int32_t K, int32_t M, int32_t dtype);
 
 /*
- * Size in bytes of the MFMA operand copy of an INT8 table (padded; see lutnn_build_table).
- * Host; returns 0 for fp32 tables or invalid arguments.
+ * Size in bytes of the MFMA operand copy of an INT8 or INT4 table (padded; see
+ * lutnn_build_table).  Host; returns 0 for fp32 tables or invalid arguments.
  */
 LUTNN_API size_t lutnn_packed_bytes(int32_t C, int32_t K, int32_t M, int32_t dtype);
 
@@ -98,11 +103,13 @@ LUTNN_API size_t lutnn_packed_bytes(int32_t C, int32_t K, int32_t M, int32_t dty
  *   table_out  T[C][K][M]: fp32 entries  T = sum_v P[c][k][v] * W[cV+v][m]  (fp32, v
  *              ascending, fused multiply-add), or for INT8
  *              q = clamp(round_half_even(T / s), -127, 127) with
- *              s = max|T| / 127 over the whole layer (s = 1 when the table is all zero)
- *   packed_out INT8 only, nullable: the same q re-laid out for the MFMA variant:
+ *              s = max|T| / 127 over the whole layer (s = 1 when the table is all zero);
+ *              for INT4 the same with 7 in place of 127, two entries per byte
+ *   packed_out INT8 / INT4, nullable: the same q re-laid out for the MFMA variants, one int8 per
+ *              entry for both dtypes:
  *              [C * ceil(K/16)][Mp][16] int8 with Mp = M rounded up to 256, k fastest,
  *              zero padded.  Must be 16-byte aligned.
- *   scale_out  INT8 only: receives s (one fp32).  Also used as scratch during the call.
+ *   scale_out  INT8 / INT4: receives s (one fp32).  Also used as scratch during the call.
  *
  * Errors: E_NULL, E_SHAPE, E_UNSUPPORTED (unknown dtype), E_ALIGN, E_HIP.
  */
@@ -126,7 +133,7 @@ LUTNN_API lutnn_status lutnn_encode(const lutnn_layer* layer, const float* X, in
 
 /*
  * Lookup + aggregation (Eq. 4; "table read and accumulation", Sec. 5.2):
- *   INT8 table:  acc = sum_c (int32) q[c][idx[n][c]][m]  (exact),
+ *   INT8 / INT4: acc = sum_c (int32) q[c][idx[n][c]][m]  (exact),
  *                Y[n][m] = fma((float)acc, s, bias[m])   (or (float)acc * s without bias)
  *   fp32 table:  Y[n][m] = sum_c T[c][idx[n][c]][m] (+ bias[m]), fp32 accumulation
  *

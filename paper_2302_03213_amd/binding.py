@@ -16,6 +16,7 @@ from . import build as _build
 
 TABLE_F32 = 0
 TABLE_I8 = 1
+TABLE_I4 = 2
 
 VARIANT_AUTO = 0
 VARIANT_LDS = 1
@@ -143,7 +144,7 @@ class LutLayer:
 
 
 def build_table(centroids, W, table_dtype, bias=None, packed=True):
-    """lutnn_build_table: Eq. 3 (+ Sec. 3.3 for INT8).  centroids [C,K,V], W [D,M] on the GPU."""
+    """lutnn_build_table: Eq. 3 (+ Sec. 3.3 for INT8 / INT4).  centroids [C,K,V], W [D,M] on the GPU."""
     assert centroids.is_cuda and W.is_cuda and centroids.dtype == torch.float32
     assert centroids.is_contiguous() and W.dtype == torch.float32 and W.stride(1) == 1
     C, K, V = centroids.shape
@@ -155,7 +156,10 @@ def build_table(centroids, W, table_dtype, bias=None, packed=True):
         table = torch.empty((C, K, M), dtype=torch.float32, device=dev)
         pk, scale = None, None
     else:
-        table = torch.empty((C, K, M), dtype=torch.int8, device=dev)
+        if table_dtype == TABLE_I4:  # two 4-bit entries per byte, even column in the low nibble
+            table = torch.empty((C, K, (M + 1) // 2), dtype=torch.uint8, device=dev)
+        else:
+            table = torch.empty((C, K, M), dtype=torch.int8, device=dev)
         scale = torch.empty(1, dtype=torch.float32, device=dev)
         pk = None
         if packed:

@@ -39,10 +39,12 @@ lutnn_status check_dims(int32_t C, int32_t K, int32_t V, int32_t M) {
     return LUTNN_OK;
 }
 
+inline bool is_int_table(int dtype) { return dtype == LUTNN_TABLE_I8 || dtype == LUTNN_TABLE_I4; }
+
 lutnn_status check_layer(const lutnn_layer* L) {
     if (!L) return fail(LUTNN_E_NULL, "layer is NULL");
     if (L->reserved != 0) return fail(LUTNN_E_SHAPE, "layer->reserved must be 0");
-    if (L->table_dtype != LUTNN_TABLE_F32 && L->table_dtype != LUTNN_TABLE_I8)
+    if (L->table_dtype != LUTNN_TABLE_F32 && !is_int_table(L->table_dtype))
         return fail(LUTNN_E_UNSUPPORTED, "unknown table dtype %d", L->table_dtype);
     return check_dims(L->C, L->K, L->V, L->M);
 }
@@ -52,9 +54,10 @@ constexpr int64_t kMaxRows = (int64_t)1 << 31;
 // Which lookup kernel AUTO resolves to.
 int resolve_lookup_variant(const lutnn_layer* L, int variant, const uint8_t* idx, int64_t N) {
     if (variant != LUTNN_VARIANT_AUTO) return variant;
-    if (L->table_dtype == LUTNN_TABLE_I8 && L->table_packed && L->K <= 16) {
+    if (is_int_table(L->table_dtype) && L->table_packed && L->K <= 16) {
         // small problems: rows gathered straight from L2 beat a matrix-core launch
-        if (lutnn::gather_preferred(L->table, 1, L->C, L->M, N)) return LUTNN_VARIANT_LDS;
+        if (lutnn::gather_preferred(L->table, L->table_dtype == LUTNN_TABLE_I4 ? 2 : 1, L->C, L->M, N))
+            return LUTNN_VARIANT_LDS;
         // the sparse kernel works on 512-row tiles; below that the dense 256-row tile wastes less
         if (N > 256 && lutnn::smfmac_supported(L->C, L->K, idx)) return LUTNN_VARIANT_SMFMAC;
         return LUTNN_VARIANT_MFMA;
@@ -69,8 +72,8 @@ lutnn_status check_lookup(const lutnn_layer* L, int variant, const uint8_t* idx,
     if (ldy < L->M) return fail(LUTNN_E_SHAPE, "ldy=%lld is smaller than M=%d", (long long)ldy, L->M);
     if (!aligned(Y, 4)) return fail(LUTNN_E_ALIGN, "Y must be 4-byte aligned");
     if (L->bias && !aligned(L->bias, 4)) return fail(LUTNN_E_ALIGN, "bias must be 4-byte aligned");
-    if (L->table_dtype == LUTNN_TABLE_I8 && !L->scale)
-        return fail(LUTNN_E_NULL, "INT8 table needs layer->scale");
+    if (is_int_table(L->table_dtype) && !L->scale)
+        return fail(LUTNN_E_NULL, "an integer table needs layer->scale");
     switch (variant) {
         case LUTNN_VARIANT_LDS:
             if (!L->table) return fail(LUTNN_E_NULL, "the LDS variant needs layer->table");
@@ -79,8 +82,8 @@ lutnn_status check_lookup(const lutnn_layer* L, int variant, const uint8_t* idx,
             break;
         case LUTNN_VARIANT_MFMA:
         case LUTNN_VARIANT_SMFMAC:
-            if (L->table_dtype != LUTNN_TABLE_I8)
-                return fail(LUTNN_E_UNSUPPORTED, "the MFMA variants need an INT8 table");
+            if (!is_int_table(L->table_dtype))
+                return fail(LUTNN_E_UNSUPPORTED, "the MFMA variants need an INT8 or INT4 table");
             if (L->K > 16)
                 return fail(LUTNN_E_UNSUPPORTED, "the MFMA variants support K <= 16 (got %d)", L->K);
             if (!L->table_packed) return fail(LUTNN_E_NULL, "the MFMA variants need layer->table_packed");
@@ -109,6 +112,9 @@ lutnn_status do_lookup(const lutnn_layer* L, int variant, const uint8_t* idx, in
                                          L->C, L->K, L->M, idx, N, Y, ldy, s);
     } else if (L->table_dtype == LUTNN_TABLE_I8) {
         e = lutnn::launch_lookup_lds_i8(static_cast<const int8_t*>(L->table), L->scale, L->bias, L->C,
+                                        L->K, L->M, idx, N, Y, ldy, s);
+    } else if (L->table_dtype == LUTNN_TABLE_I4) {
+        e = lutnn::launch_lookup_lds_i4(static_cast<const uint8_t*>(L->table), L->scale, L->bias, L->C,
                                         L->K, L->M, idx, N, Y, ldy, s);
     } else {
         e = lutnn::launch_lookup_lds_f32(static_cast<const float*>(L->table), L->bias, L->C, L->K, L->M,
@@ -177,12 +183,13 @@ size_t lutnn_table_bytes(int32_t C, int32_t K, int32_t M, int32_t dtype) {
     if (C <= 0 || K <= 0 || M <= 0) return 0;
     const size_t n = (size_t)C * (size_t)K * (size_t)M;
     if (dtype == LUTNN_TABLE_I8) return n;
+    if (dtype == LUTNN_TABLE_I4) return (size_t)C * (size_t)K * (((size_t)M + 1) / 2);
     if (dtype == LUTNN_TABLE_F32) return n * 4;
     return 0;
 }
 
 size_t lutnn_packed_bytes(int32_t C, int32_t K, int32_t M, int32_t dtype) {
-    if (C <= 0 || K <= 0 || K > 256 || M <= 0 || dtype != LUTNN_TABLE_I8) return 0;
+    if (C <= 0 || K <= 0 || K > 256 || M <= 0 || !is_int_table(dtype)) return 0;
     return (size_t)C * (size_t)lutnn::kblocks(K) * (size_t)lutnn::packed_cols(M) * 16;
 }
 
@@ -201,14 +208,15 @@ lutnn_status lutnn_build_table(const float* centroids, const float* W, int64_t l
                                                         static_cast<float*>(table_out), s),
                           "build_table launch");
     }
-    if (dtype == LUTNN_TABLE_I8) {
-        if (!scale_out) return fail(LUTNN_E_NULL, "INT8 table needs scale_out");
+    if (is_int_table(dtype)) {
+        if (!scale_out) return fail(LUTNN_E_NULL, "an integer table needs scale_out");
         if (!aligned(scale_out, 4)) return fail(LUTNN_E_ALIGN, "scale_out must be 4-byte aligned");
         if (packed_out && !aligned(packed_out, 16))
             return fail(LUTNN_E_ALIGN, "packed_out must be 16-byte aligned");
         return hip_result(lutnn::launch_build_table_i8(centroids, W, ldw, C, K, V, M,
                                                        static_cast<int8_t*>(table_out),
-                                                       static_cast<int8_t*>(packed_out), scale_out, s),
+                                                       static_cast<int8_t*>(packed_out), scale_out,
+                                                       dtype == LUTNN_TABLE_I4 ? 4 : 8, s),
                           "build_table launch");
     }
     return fail(LUTNN_E_UNSUPPORTED, "unknown table dtype %d", dtype);
@@ -267,8 +275,8 @@ lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, int64_t N, i
         if (!lutnn::fused_supported(L->C, L->K, L->V, L->M, L->table_dtype))
             return fail(LUTNN_E_UNSUPPORTED, "no fused kernel for C=%d K=%d V=%d M=%d dtype=%d", L->C, L->K,
                         L->V, L->M, L->table_dtype);
-        if (L->table_dtype == LUTNN_TABLE_I8) {
-            if (!L->scale) return fail(LUTNN_E_NULL, "INT8 table needs layer->scale");
+        if (is_int_table(L->table_dtype)) {
+            if (!L->scale) return fail(LUTNN_E_NULL, "an integer table needs layer->scale");
             if (!L->table_packed) return fail(LUTNN_E_NULL, "the fused INT8 kernel needs layer->table_packed");
             if (!aligned(L->table_packed, 16))
                 return fail(LUTNN_E_ALIGN, "table_packed must be 16-byte aligned");

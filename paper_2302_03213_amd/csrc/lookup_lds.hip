@@ -30,7 +30,9 @@ constexpr int kWaves = 4;
 constexpr int kColsI8 = 256;  // MT: 64 lanes x 4 columns
 constexpr int kRowsPerWaveI8 = 16;
 
-template <bool IDX_DWORD>
+// BITS = 8: T[C][K][M] int8.  BITS = 4: T[C][K][ceil(M/2)] bytes, two 4-bit entries each (even
+// column in the low nibble); they are widened to bytes while being staged, the rest is the same.
+template <bool IDX_DWORD, int BITS = 8>
 __global__ __launch_bounds__(kThreads) void lookup_lds_i8_kernel(
     const int8_t* __restrict__ T, const float* __restrict__ scale, const float* __restrict__ bias,
     int C, int K, int M, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y,
@@ -64,7 +66,19 @@ __global__ __launch_bounds__(kThreads) void lookup_lds_i8_kernel(
             const int c = c0 + cl;
             const int m = n0 + ch * 16;
             uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (c < C) {
+            if (c < C && BITS == 4) {
+                const uint8_t* src =
+                    reinterpret_cast<const uint8_t*>(T) + ((size_t)c * K + k) * ((M + 1) / 2) + m / 2;
+                uint32_t t[4] = {0u, 0u, 0u, 0u};
+                for (int b = 0; b < 16; b += 2) {  // m is even: byte b/2 holds columns m+b, m+b+1
+                    if (m + b >= M) break;
+                    const uint32_t two = src[b >> 1];
+                    const uint32_t lo = ((two & 0xfu) ^ 8u) - 8u, hi = ((two >> 4) ^ 8u) - 8u;  // sign extend
+                    t[b >> 2] |= (lo & 0xffu) << (8 * (b & 3));
+                    if (m + b + 1 < M) t[b >> 2] |= (hi & 0xffu) << (8 * ((b + 1) & 3));
+                }
+                v = make_uint4(t[0], t[1], t[2], t[3]);
+            } else if (c < C) {
                 const int8_t* src = T + ((size_t)c * K + k) * M + m;
                 if (table_vec16 && m + 16 <= M) {
                     v = *reinterpret_cast<const uint4*>(src);
@@ -274,20 +288,32 @@ __global__ __launch_bounds__(kThreads) void lookup_global_kernel(
 // kernels.  Needs M % 4 == 0 and a table aligned for the vector load.
 constexpr int kGatherCols = 256;
 
-template <typename TT, bool IDX_DWORD>
+// UNIFORM: a wavefront works on one row (M >= 256: scalar index loads).  Otherwise rows are
+// narrower than a wavefront: `lpr` lanes per row, 64 / lpr rows per wavefront, per-lane index loads.
+template <typename TT, bool IDX_DWORD, bool UNIFORM>
 __global__ __launch_bounds__(kThreads) void lookup_gather_kernel(
     const TT* __restrict__ T, const float* __restrict__ scale, const float* __restrict__ bias, int C,
     int K, int M, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y, int64_t ldy,
-    int col_chunks) {
+    int col_chunks, int lpr) {
     constexpr bool I8 = sizeof(TT) == 1;
     typedef typename std::conditional<I8, uint32_t, float4>::type Vec;  // four columns
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t gw = (int64_t)blockIdx.x * kWaves + w;
-    const int64_t row = gw / col_chunks;
+    int64_t row;
+    int m;
+    if (UNIFORM) {
+        row = gw / col_chunks;
+        m = (int)(gw % col_chunks) * kGatherCols + lane * 4;
+    } else {
+        const int sub = lane / lpr;
+        if (sub >= 64 / lpr) return;
+        row = gw * (64 / lpr) + sub;
+        m = (lane - sub * lpr) * 4;
+    }
     if (row >= N) return;
-    const int m = (int)(gw % col_chunks) * kGatherCols + lane * 4;
     if (m >= M) return;  // M % 4 == 0: a lane's four columns are all inside or all outside
+    auto uni = [](uint32_t x) { return UNIFORM ? (uint32_t)__builtin_amdgcn_readfirstlane(x) : x; };
     const uint8_t* __restrict__ irow = idx + row * C;
     const TT* __restrict__ tcol = T + m;
 
@@ -311,13 +337,12 @@ __global__ __launch_bounds__(kThreads) void lookup_gather_kernel(
     int c = 0;
     if (IDX_DWORD) {
         for (; c + 4 <= C; c += 4) {
-            const uint32_t word =
-                __builtin_amdgcn_readfirstlane(*reinterpret_cast<const uint32_t*>(irow + c));
+            const uint32_t word = uni(*reinterpret_cast<const uint32_t*>(irow + c));
 #pragma unroll
             for (int b = 0; b < 4; ++b) add(c + b, (int)((word >> (8 * b)) & 0xffu));
         }
     }
-    for (; c < C; ++c) add(c, (int)__builtin_amdgcn_readfirstlane((uint32_t)irow[c]));
+    for (; c < C; ++c) add(c, (int)uni((uint32_t)irow[c]));
 
     float* __restrict__ y = Y + row * ldy + m;
     float4 out;
@@ -349,19 +374,111 @@ bool gather_ok(const TT* T, int M, int64_t staged_blocks) {
            (reinterpret_cast<uintptr_t>(T) & (4 * sizeof(TT) - 1)) == 0;
 }
 
+inline bool gather_i4_ok(const uint8_t* T, int M, int64_t staged_blocks) {
+    return staged_blocks < kMinStagedBlocks && M % 8 == 0 && (reinterpret_cast<uintptr_t>(T) & 3) == 0;
+}
+
 template <typename TT>
 hipError_t launch_gather(const TT* T, const float* scale, const float* bias, int C, int K, int M,
                          const uint8_t* idx, int64_t N, float* Y, int64_t ldy, hipStream_t s) {
-    const int col_chunks = (M + kGatherCols - 1) / kGatherCols;
-    const int64_t blocks = (N * col_chunks + kWaves - 1) / kWaves;
-    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    if ((C % 4 == 0) && ((reinterpret_cast<uintptr_t>(idx) & 3) == 0))
-        hipLaunchKernelGGL((lookup_gather_kernel<TT, true>), dim3((unsigned)blocks), dim3(kThreads), 0, s,
-                           T, scale, bias, C, K, M, idx, N, Y, ldy, col_chunks);
-    else
-        hipLaunchKernelGGL((lookup_gather_kernel<TT, false>), dim3((unsigned)blocks), dim3(kThreads), 0, s,
-                           T, scale, bias, C, K, M, idx, N, Y, ldy, col_chunks);
+    const bool idx_dword = (C % 4 == 0) && ((reinterpret_cast<uintptr_t>(idx) & 3) == 0);
+    const int lpr = M / 4;  // lanes per row when a row is narrower than a wavefront
+    if (lpr >= 64) {
+        const int col_chunks = (M + kGatherCols - 1) / kGatherCols;
+        const int64_t blocks = (N * col_chunks + kWaves - 1) / kWaves;
+        if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        if (idx_dword)
+            hipLaunchKernelGGL((lookup_gather_kernel<TT, true, true>), dim3((unsigned)blocks),
+                               dim3(kThreads), 0, s, T, scale, bias, C, K, M, idx, N, Y, ldy, col_chunks, lpr);
+        else
+            hipLaunchKernelGGL((lookup_gather_kernel<TT, false, true>), dim3((unsigned)blocks),
+                               dim3(kThreads), 0, s, T, scale, bias, C, K, M, idx, N, Y, ldy, col_chunks, lpr);
+    } else {
+        const int64_t rows_per_block = (int64_t)(64 / lpr) * kWaves;
+        const int64_t blocks = (N + rows_per_block - 1) / rows_per_block;
+        if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        if (idx_dword)
+            hipLaunchKernelGGL((lookup_gather_kernel<TT, true, false>), dim3((unsigned)blocks),
+                               dim3(kThreads), 0, s, T, scale, bias, C, K, M, idx, N, Y, ldy, 1, lpr);
+        else
+            hipLaunchKernelGGL((lookup_gather_kernel<TT, false, false>), dim3((unsigned)blocks),
+                               dim3(kThreads), 0, s, T, scale, bias, C, K, M, idx, N, Y, ldy, 1, lpr);
+    }
     return hipGetLastError();
+}
+
+// 4-bit table, any K, any M: one thread per (row, column), nibbles read from global memory.
+__global__ __launch_bounds__(kThreads) void lookup_global_i4_kernel(
+    const uint8_t* __restrict__ T, const float* __restrict__ scale, const float* __restrict__ bias,
+    int C, int K, int M, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y,
+    int64_t ldy) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= N * (int64_t)M) return;
+    const int64_t n = i / M;
+    const int m = (int)(i % M);
+    const int Mb = (M + 1) / 2;
+    int32_t acc = 0;
+    for (int c = 0; c < C; ++c) {
+        int k = idx[n * C + c];
+        k = k < K ? k : K - 1;
+        const uint32_t two = T[((size_t)c * K + k) * Mb + (m >> 1)];
+        const uint32_t nib = (m & 1) ? two >> 4 : two & 0xfu;
+        acc += (int32_t)((nib ^ 8u) - 8u);
+    }
+    const float s = *scale;
+    Y[n * ldy + m] = bias ? __fmaf_rn((float)acc, s, bias[m]) : __fmul_rn((float)acc, s);
+}
+
+// 4-bit table, few rows: as lookup_gather_kernel, a lane takes eight columns (one dword of the
+// table row), a wavefront 512.  Needs M % 8 == 0 and a 4-byte aligned table.
+constexpr int kGatherColsI4 = 512;
+
+template <bool IDX_DWORD, bool UNIFORM>
+__global__ __launch_bounds__(kThreads) void lookup_gather_i4_kernel(
+    const uint8_t* __restrict__ T, const float* __restrict__ scale, const float* __restrict__ bias,
+    int C, int K, int M, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y,
+    int64_t ldy, int col_chunks, int lpr) {
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t gw = (int64_t)blockIdx.x * kWaves + w;
+    int64_t row;
+    int m;
+    if (UNIFORM) {
+        row = gw / col_chunks;
+        m = (int)(gw % col_chunks) * kGatherColsI4 + lane * 8;
+    } else {  // rows narrower than a wavefront: lpr lanes per row
+        const int sub = lane / lpr;
+        if (sub >= 64 / lpr) return;
+        row = gw * (64 / lpr) + sub;
+        m = (lane - sub * lpr) * 8;
+    }
+    if (row >= N) return;
+    if (m >= M) return;  // M % 8 == 0: a lane's eight columns are all inside or all outside
+    auto uni = [](uint32_t x) { return UNIFORM ? (uint32_t)__builtin_amdgcn_readfirstlane(x) : x; };
+    const uint8_t* __restrict__ irow = idx + row * C;
+    const uint8_t* __restrict__ tcol = T + m / 2;
+    const size_t Mb = (size_t)M / 2;
+    int32_t a[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    auto add = [&](int c, int k) {
+        k = k < K ? k : K - 1;
+        const uint32_t v = *reinterpret_cast<const uint32_t*>(tcol + ((size_t)c * K + k) * Mb);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a[j] += (int32_t)(v << (28 - 4 * j)) >> 28;  // nibble j, sign extended
+    };
+    int c = 0;
+    if (IDX_DWORD) {
+        for (; c + 4 <= C; c += 4) {
+            const uint32_t word = uni(*reinterpret_cast<const uint32_t*>(irow + c));
+#pragma unroll
+            for (int b = 0; b < 4; ++b) add(c + b, (int)((word >> (8 * b)) & 0xffu));
+        }
+    }
+    for (; c < C; ++c) add(c, (int)uni((uint32_t)irow[c]));
+    const float s = *scale;
+    float* __restrict__ y = Y + row * ldy + m;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        y[j] = bias ? __fmaf_rn((float)a[j], s, bias[m + j]) : __fmul_rn((float)a[j], s);
 }
 
 constexpr int kLdsBudget = 64 * 1024;
@@ -375,14 +492,16 @@ inline bool idx_dword_ok(const uint8_t* idx, int C) {
 // True when the gather variant would read the table straight from L2 (no staging) and the whole
 // problem is small enough for that to beat the matrix-core kernels, whose 256/512-row tiles and
 // pipeline fill are wasted on it (measured cross-over: about 3e7 table entries).
-bool gather_preferred(const void* T, int table_is_i8, int C, int M, int64_t N) {
+bool gather_preferred(const void* T, int table_kind, int C, int M, int64_t N) {
     if (!T) return false;
-    const int64_t rows_per_block = table_is_i8 ? kRowsPerWaveI8 * kWaves : kRowsPerWaveF32 * kWaves;
-    const int cols_per_block = table_is_i8 ? kColsI8 : kColsF32;
+    const bool f32 = table_kind == 0;
+    const int64_t rows_per_block = f32 ? kRowsPerWaveF32 * kWaves : kRowsPerWaveI8 * kWaves;
+    const int cols_per_block = f32 ? kColsF32 : kColsI8;
     const int64_t staged_blocks =
         ((N + rows_per_block - 1) / rows_per_block) * ((M + cols_per_block - 1) / cols_per_block);
-    const bool direct = table_is_i8 ? gather_ok(static_cast<const int8_t*>(T), M, staged_blocks)
-                                    : gather_ok(static_cast<const float*>(T), M, staged_blocks);
+    const bool direct = table_kind == 0   ? gather_ok(static_cast<const float*>(T), M, staged_blocks)
+                        : table_kind == 1 ? gather_ok(static_cast<const int8_t*>(T), M, staged_blocks)
+                                          : gather_i4_ok(static_cast<const uint8_t*>(T), M, staged_blocks);
     return direct && N * (int64_t)C * M <= (int64_t)1 << 25;
 }
 
@@ -413,6 +532,61 @@ hipError_t launch_lookup_lds_i8(const int8_t* T, const float* scale, const float
     else
         hipLaunchKernelGGL((lookup_lds_i8_kernel<false>), dim3((unsigned)blocks), dim3(kThreads), shmem,
                            s, T, scale, bias, C, K, M, idx, N, Y, ldy, CC, col_tiles, vec16);
+    return hipGetLastError();
+}
+
+hipError_t launch_lookup_lds_i4(const uint8_t* T, const float* scale, const float* bias, int C, int K,
+                                int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,
+                                hipStream_t s) {
+    const int per_codebook = K * kColsI8;  // LDS bytes per staged codebook (entries widened to bytes)
+    if (4 * per_codebook > kLdsBudget) {
+        const int64_t blocks = (N * (int64_t)M + kThreads - 1) / kThreads;
+        if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(lookup_global_i4_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, s, T, scale,
+                           bias, C, K, M, idx, N, Y, ldy);
+        return hipGetLastError();
+    }
+    int CC = (kLdsBudget / 2 / per_codebook) & ~3;
+    if (CC < 4) CC = 4;
+    if (CC > 16) CC = 16;
+    const int col_tiles = (M + kColsI8 - 1) / kColsI8;
+    const int64_t row_tiles = (N + kRowsPerWaveI8 * kWaves - 1) / (kRowsPerWaveI8 * kWaves);
+    const int64_t blocks = row_tiles * col_tiles;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const bool idx_dword = idx_dword_ok(idx, C);
+    if (gather_i4_ok(T, M, blocks)) {
+        const int lpr = M / 8;
+        if (lpr >= 64) {
+            const int col_chunks = (M + kGatherColsI4 - 1) / kGatherColsI4;
+            const int64_t gblocks = (N * col_chunks + kWaves - 1) / kWaves;
+            if (gblocks > 0x7fffffffLL) return hipErrorInvalidValue;
+            if (idx_dword)
+                hipLaunchKernelGGL((lookup_gather_i4_kernel<true, true>), dim3((unsigned)gblocks),
+                                   dim3(kThreads), 0, s, T, scale, bias, C, K, M, idx, N, Y, ldy, col_chunks, lpr);
+            else
+                hipLaunchKernelGGL((lookup_gather_i4_kernel<false, true>), dim3((unsigned)gblocks),
+                                   dim3(kThreads), 0, s, T, scale, bias, C, K, M, idx, N, Y, ldy, col_chunks, lpr);
+        } else {
+            const int64_t rows_per_block = (int64_t)(64 / lpr) * kWaves;
+            const int64_t gblocks = (N + rows_per_block - 1) / rows_per_block;
+            if (gblocks > 0x7fffffffLL) return hipErrorInvalidValue;
+            if (idx_dword)
+                hipLaunchKernelGGL((lookup_gather_i4_kernel<true, false>), dim3((unsigned)gblocks),
+                                   dim3(kThreads), 0, s, T, scale, bias, C, K, M, idx, N, Y, ldy, 1, lpr);
+            else
+                hipLaunchKernelGGL((lookup_gather_i4_kernel<false, false>), dim3((unsigned)gblocks),
+                                   dim3(kThreads), 0, s, T, scale, bias, C, K, M, idx, N, Y, ldy, 1, lpr);
+        }
+        return hipGetLastError();
+    }
+    const size_t shmem = (size_t)CC * per_codebook;
+    const int8_t* Tb = reinterpret_cast<const int8_t*>(T);
+    if (idx_dword)
+        hipLaunchKernelGGL((lookup_lds_i8_kernel<true, 4>), dim3((unsigned)blocks), dim3(kThreads), shmem,
+                           s, Tb, scale, bias, C, K, M, idx, N, Y, ldy, CC, col_tiles, 0);
+    else
+        hipLaunchKernelGGL((lookup_lds_i8_kernel<false, 4>), dim3((unsigned)blocks), dim3(kThreads), shmem,
+                           s, Tb, scale, bias, C, K, M, idx, N, Y, ldy, CC, col_tiles, 0);
     return hipGetLastError();
 }
 

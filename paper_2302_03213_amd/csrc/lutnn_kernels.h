@@ -32,8 +32,11 @@ hipError_t launch_encode(const float* P, int C, int K, int V, const float* X, in
 // Eq. 3 + Sec. 3.3.
 hipError_t launch_build_table_f32(const float* P, const float* W, int64_t ldw, int C, int K, int V,
                                   int M, float* T, hipStream_t s);
+// bits = 8: T is [C][K][M] int8; bits = 4: T is [C][K][ceil(M/2)] bytes of two nibbles.  The packed
+// MFMA operand copy holds one int8 per entry in both cases.
 hipError_t launch_build_table_i8(const float* P, const float* W, int64_t ldw, int C, int K, int V,
-                                 int M, int8_t* T, int8_t* packed, float* scale, hipStream_t s);
+                                 int M, int8_t* T, int8_t* packed, float* scale, int bits,
+                                 hipStream_t s);
 
 // Eq. 4, gather variant.
 hipError_t launch_lookup_lds_i8(const int8_t* T, const float* scale, const float* bias, int C, int K,
@@ -42,7 +45,11 @@ hipError_t launch_lookup_lds_i8(const int8_t* T, const float* scale, const float
 hipError_t launch_lookup_lds_f32(const float* T, const float* bias, int C, int K, int M,
                                  const uint8_t* idx, int64_t N, float* Y, int64_t ldy, hipStream_t s);
 
-bool gather_preferred(const void* T, int table_is_i8, int C, int M, int64_t N);
+hipError_t launch_lookup_lds_i4(const uint8_t* T, const float* scale, const float* bias, int C, int K,
+                                int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,
+                                hipStream_t s);
+// table_kind: 0 fp32, 1 int8, 2 int4 (nibble pairs)
+bool gather_preferred(const void* T, int table_kind, int C, int M, int64_t N);
 
 // Eq. 4, one-hot MFMA variant (INT8).
 hipError_t launch_lookup_mfma_i8(const int8_t* packed, const float* scale, const float* bias, int C,

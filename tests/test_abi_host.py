@@ -47,6 +47,8 @@ def test_size_queries(lut):
     assert lut.table_bytes(128, 16, 512, lut.TABLE_F32) == 128 * 16 * 512 * 4
     assert lut.table_bytes(0, 16, 512, lut.TABLE_I8) == 0
     assert lut.table_bytes(4, 16, 8, 7) == 0
+    assert lut.table_bytes(3, 16, 9, lut.TABLE_I4) == 3 * 16 * 5  # two entries per byte, rows padded
+    assert lut.packed_bytes(64, 16, 64, lut.TABLE_I4) == 64 * 256 * 16  # one int8 per entry, as INT8
     assert lut.packed_bytes(64, 16, 64, lut.TABLE_I8) == 64 * 256 * 16  # M padded to 256
     assert lut.packed_bytes(3, 33, 257, lut.TABLE_I8) == 3 * 3 * 512 * 16  # ceil(33/16) k blocks
     assert lut.packed_bytes(64, 16, 64, lut.TABLE_F32) == 0

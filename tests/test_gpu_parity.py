@@ -393,6 +393,41 @@ def test_config5_fc_large_int8(lut):
     print("config 5 near-ties: %d" % flips)
 
 
+# ------------------------------------------------------------------ INT4 tables (Sec. 3.3, n = 4)
+I4_SHAPES = [
+    # N, C, K, V, M
+    (70, 5, 16, 4, 37), (129, 32, 16, 4, 64), (300, 64, 16, 2, 520), (50, 9, 5, 1, 21),
+    (2100, 8, 16, 4, 4096), (600, 96, 16, 4, 264), (40, 6, 40, 2, 70), (33, 4, 100, 2, 30),
+]
+
+
+@pytest.mark.parametrize("N,C,K,V,M", I4_SHAPES)
+def test_int4_table_build_and_every_lookup(lut, N, C, K, V, M):
+    w = wl.make_layer("t", N, C, K, V, M, "i8", seed=N + C + M + 4)
+    Tf = oracle.build_table_f32(w.P, w.W)
+    q, s = oracle.quantize(Tf, 4)
+    layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I4, bias=dev(w.bias))
+    assert host(layer.scale)[0] == s
+    np.testing.assert_array_equal(host(layer.table), oracle.pack_nibbles(q))  # storage format
+    if K <= 16:
+        ref_packed = packed_from_q(q)
+        np.testing.assert_array_equal(host(layer.packed).reshape(ref_packed.shape), ref_packed)
+    idx_ref = oracle.encode(w.P, w.X)
+    ref = oracle.lookup_i8(q, s, idx_ref, w.bias)
+    variants = ["auto", "lds"] + (["mfma"] if K <= 16 else []) + \
+        (["smfmac"] if K <= 16 and C % 32 == 0 else [])
+    for v in variants:
+        np.testing.assert_array_equal(host(lut.lookup(layer, dev(idx_ref), v)), ref, err_msg=v)
+    idx_gpu = host(lut.encode(layer, dev(w.X)))
+    clean = (idx_gpu == idx_ref).all(axis=1)
+    assert clean.mean() > 0.99
+    for v in ["auto"] + (["fused"] if K <= 16 else []):
+        np.testing.assert_array_equal(host(lut.linear(layer, dev(w.X), v))[clean], ref[clean], err_msg=v)
+    # the 4-bit table approximates the fp32 one to within half a (coarser) step per codebook
+    exact = oracle.lookup_f32(Tf, idx_ref, w.bias)
+    assert np.abs(ref - exact).max() <= C * float(s) / 2 * (1 + 1e-4) + 1e-4
+
+
 # ------------------------------------------------------------------ convolutions (Sec. 4: im2col)
 def unfold_rows(inp, kernel, stride, pad):
     """The im2col matrix with torch's own unfold: rows (b, ho, wo), columns (ci, r, s)."""
