@@ -201,6 +201,20 @@ def main():
                     "frac": round(achieved * 1e9 / cost.PEAK_HBM_BYTES_PER_S, 4),
                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "linear_fused")),
                     "kernel_ms": round(fused_ms[0], 4)}
+    # when the encoder of that layer takes longer than its lookup, the encoder is the dominant
+    # kernel: VALU-issue bound (Eq. 2 in the direct form is K*(2V+2) lane-operations per sub-vector)
+    if v0 != "fused" and enc_ms[0] > look_ms[0]:
+        lane_ops = cost.encode_lane_ops(w0.N, w0.C, w0.K, w0.V)
+        achieved = lane_ops / (enc_ms[0] * 1e-3) / 1e12
+        peak = cost.PEAK_VALU_F32_LANE_OPS_PER_S / 1e12
+        roofline = {"kernel": "encode", "bound": "alu", "achieved": round(achieved, 3),
+                    "peak": round(peak, 2), "unit": "T lane-ops/s",
+                    "frac": round(achieved / peak, 4), "traffic": None,
+                    "kernel_ms": round(enc_ms[0], 4), "ops_per_launch": lane_ops,
+                    "note": "arg-min by definition: per sub-vector and centroid V subtract + V fused "
+                            "multiply-add + one compare + one select; peak = 256 CUs x 64 lanes x "
+                            "2.4 GHz (packed-fp32 instructions are compiled out)",
+                    "lookup": roofline}
     kernels = {}
     for (w, *_r), e, l, f in zip(dev_layers, enc_ms, look_ms, fused_ms):
         if variant_used[w.name] == "fused":
