@@ -179,3 +179,20 @@ def random_table_i8(C, K, M, seed=0):
     """Full-range INT8 table in [-127, 127] (the range Sec. 3.3's scale produces)."""
     g = _gen(seed)
     return torch.randint(-127, 128, (C, K, M), generator=g).numpy().astype(np.int8)
+
+
+def random_tree(C, V, levels, seed=0, level_dims=False, thr_std=0.5):
+    """Threshold trees for the hash encoder (Sec. 2): per codebook 2^levels - 1 nodes in heap order,
+    a split index in [0, V) and a threshold ~ N(0, thr_std) each.  level_dims=True gives every node
+    of a level the same split index, the form the hashing work cited there uses.  Random stand-ins
+    for learned trees; returns (split_dim int32 [C][nodes], threshold fp32 [C][nodes])."""
+    g = _gen(seed)
+    nodes = (1 << levels) - 1
+    if level_dims:
+        per_level = torch.randint(0, V, (C, levels), generator=g).numpy()
+        level_of = np.floor(np.log2(np.arange(nodes) + 1)).astype(np.int64)
+        dims = per_level[:, level_of]
+    else:
+        dims = torch.randint(0, V, (C, nodes), generator=g).numpy()
+    thr = _normal(g, (C, nodes), thr_std)
+    return np.ascontiguousarray(dims, dtype=np.int32), thr

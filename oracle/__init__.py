@@ -39,6 +39,8 @@ def _lib():
         lib.lutnn_oracle_quantize.argtypes = [_f32p, ctypes.c_int64, ctypes.c_int, _i8p, _f32p]
         lib.lutnn_oracle_encode.argtypes = [_f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int, _f32p,
                                             ctypes.c_int64, ctypes.c_int64, _u8p]
+        lib.lutnn_oracle_encode_tree.argtypes = [_i32p, _f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                 _f32p, ctypes.c_int64, ctypes.c_int64, _u8p]
         lib.lutnn_oracle_distances_f64.argtypes = [_f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                    _f32p, ctypes.c_int64, ctypes.c_int64,
                                                    ctypes.c_int, _f64p]
@@ -121,6 +123,24 @@ def encode(P, X):
     assert D == C * V and K <= 256
     idx = np.empty((N, C), dtype=np.uint8)
     _lib().lutnn_oracle_encode(_ptr(P, _f32p), C, K, V, _ptr(X, _f32p), N, D, _ptr(idx, _u8p))
+    return idx
+
+
+def encode_tree(split_dim, threshold, X, V):
+    """Hash encoding (Sec. 2, Sec. 7): walk each codebook's balanced threshold tree (heap order,
+    right when x[split] > threshold); idx[n,c] = the leaf reached, counted from the left."""
+    split_dim = _c(split_dim, np.int32)
+    threshold = _c(threshold, np.float32)
+    X = _c(X, np.float32)
+    C, nodes = split_dim.shape
+    levels = (nodes + 1).bit_length() - 1
+    assert threshold.shape == (C, nodes) and nodes == (1 << levels) - 1 and 1 <= levels <= 8
+    N, D = X.shape
+    assert D == C * V
+    assert split_dim.min() >= 0 and split_dim.max() < V
+    idx = np.empty((N, C), dtype=np.uint8)
+    _lib().lutnn_oracle_encode_tree(_ptr(split_dim, _i32p), _ptr(threshold, _f32p), C, levels, V,
+                                    _ptr(X, _f32p), N, D, _ptr(idx, _u8p))
     return idx
 
 

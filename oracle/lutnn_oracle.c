@@ -12,6 +12,7 @@
  *   - table construction h^c(b^c)[k] = P^c_k . b^c    (Eq. 3)
  *   - symmetric scalar quantisation of the table      (Sec. 3.3)
  *   - lookup + aggregation  a.b ~= sum_c T[c][g^c][m] (Eq. 4)
+ *   - hash (threshold tree) encoding as the alternative g^c (Sec. 2, Sec. 7)
  *
  * Readings taken where the paper is silent (each is listed in the design
  * document of this repository):
@@ -135,6 +136,40 @@ ORACLE_API void lutnn_oracle_encode(const float* P, int C, int K, int V, const f
                 }
             }
             idx[(size_t)n * C + c] = (uint8_t)best;
+        }
+    }
+}
+
+/*
+ * Hash encoding (Sec. 2, "Hashing for acceleration"; evaluated in Sec. 7): in place of the
+ * arg-min of Eq. 2 every codebook owns a balanced binary tree with `levels` levels whose
+ * 2^levels leaves are the buckets.  A sub-vector starts at the root; at each node it looks at ONE
+ * of its V values (the node's split index) and moves to the right child when that value lies above
+ * the node's threshold, to the left child otherwise.  The leaf it reaches, counted from the left,
+ * is idx[n][c].
+ *
+ * Readings: nodes are stored in heap order (node i has children 2i+1 and 2i+2, root 0), so a
+ * codebook has 2^levels - 1 (split index, threshold) pairs; "above" is the strict x > t, so a
+ * value equal to the threshold, and a NaN, go left.
+ *   split_dim  [C][2^levels - 1] int32, every value in [0, V)
+ *   threshold  [C][2^levels - 1] fp32
+ */
+ORACLE_API void lutnn_oracle_encode_tree(const int32_t* split_dim, const float* threshold, int C,
+                                         int levels, int V, const float* X, int64_t N,
+                                         int64_t ldx, uint8_t* idx) {
+    const int nodes = (1 << levels) - 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        const float* x = X + (size_t)n * (size_t)ldx;
+        for (int c = 0; c < C; ++c) {
+            const int32_t* dim = split_dim + (size_t)c * nodes;
+            const float* thr = threshold + (size_t)c * nodes;
+            int node = 0;
+            for (int l = 0; l < levels; ++l) {
+                const int right = x[c * V + dim[node]] > thr[node];
+                node = 2 * node + 1 + right;
+            }
+            idx[(size_t)n * C + c] = (uint8_t)(node - nodes);
         }
     }
 }
