@@ -54,12 +54,17 @@ def main():
     ap.add_argument("--variant", default="auto", choices=["auto", "lds", "mfma", "smfmac", "fused"])
     ap.add_argument("--int4", action="store_true",
                     help="quantise the INT8 workloads' tables to 4 bits instead (Sec. 3.3 with n = 4)")
+    ap.add_argument("--encoder", default="distance", choices=["distance", "tree"],
+                    help="tree: the hash encoder of Sec. 2 / Sec. 7 (seeded random threshold trees with "
+                         "log2 K levels) in place of the distance search of Eq. 2")
     ap.add_argument("--cpu-sample-rows", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 256 MiB device-to-device copy (untimed): the known-size kernel "
                          "against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
     args = ap.parse_args()
+    if args.encoder == "tree" and args.variant == "fused":
+        ap.error("--encoder tree has no fused kernel")
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the operator shards by rows with no "
               "communication; multi-GPU runs are not part of it). Use --gpus 1.", file=sys.stderr)
@@ -68,6 +73,7 @@ def main():
     import numpy as np
     import torch
 
+    import lutnn_workloads as wl
     import paper_2302_03213_amd as lut
     from paper_2302_03213_amd import cost
 
@@ -76,7 +82,7 @@ def main():
     layers = workload_by_name(args.workload)
 
     # ---- device-side set-up (untimed): tables, two rotating activation / output buffer sets
-    dev_layers = []
+    dev_layers, trees = [], {}
     for w in layers:
         dt = lut.TABLE_I8 if w.table_dtype == "i8" else lut.TABLE_F32
         if args.int4 and dt == lut.TABLE_I8:
@@ -88,6 +94,12 @@ def main():
         Xs = [X0, X0.flip(0).contiguous()]
         Ys = [torch.empty((w.N, w.M), dtype=torch.float32, device="cuda") for _ in range(2)]
         ws = torch.empty((w.N, w.C), dtype=torch.uint8, device="cuda")
+        if args.encoder == "tree":
+            levels = w.K.bit_length() - 1
+            assert not w.conv and w.K == 1 << levels, "--encoder tree needs K = 2^levels and matrix input"
+            dims, thr = wl.random_tree(w.C, w.V, levels, seed=0)
+            trees[w.name] = (lut.LutTree(torch.from_numpy(dims).cuda(), torch.from_numpy(thr).cuda(), w.V),
+                             dims, thr)
         dev_layers.append((w, layer, Xs, Ys, ws))
         del W
     torch.cuda.synchronize()
@@ -99,14 +111,18 @@ def main():
         del src, dst
 
     def run_layer(w, layer, X, variant, Y, ws):
-        if w.conv:  # the image batch, no im2col matrix
+        if args.encoder == "tree":
+            lut.linear_tree(layer, trees[w.name][0], X, variant, out=Y, idx_workspace=ws)
+        elif w.conv:  # the image batch, no im2col matrix
             lut.conv2d(layer, X, w.conv["kernel"], w.conv["stride"], w.conv["pad"], variant, out=Y,
                        idx_workspace=ws)
         else:
             lut.linear(layer, X, variant, out=Y, idx_workspace=ws)
 
     def run_encode(w, layer, X, ws):
-        if w.conv:
+        if args.encoder == "tree":
+            lut.encode_tree(trees[w.name][0], X, out=ws)
+        elif w.conv:
             lut.encode_conv2d(layer, X, w.conv["kernel"], w.conv["stride"], w.conv["pad"], out=ws)
         else:
             lut.encode(layer, X, out=ws)
@@ -203,7 +219,14 @@ def main():
                     "kernel_ms": round(fused_ms[0], 4)}
     # when the encoder of that layer takes longer than its lookup, the encoder is the dominant
     # kernel: VALU-issue bound (Eq. 2 in the direct form is K*(2V+2) lane-operations per sub-vector)
-    if v0 != "fused" and enc_ms[0] > look_ms[0]:
+    if args.encoder == "tree" and enc_ms[0] > look_ms[0]:
+        byts = cost.encode_bytes(w0.N, w0.C, w0.V)
+        achieved = byts / (enc_ms[0] * 1e-3) / 1e9
+        roofline = {"kernel": "encode_tree", "bound": "hbm", "achieved": round(achieved, 1),
+                    "peak": cost.PEAK_HBM_BYTES_PER_S / 1e9, "unit": "GB/s",
+                    "frac": round(achieved * 1e9 / cost.PEAK_HBM_BYTES_PER_S, 4), "traffic": None,
+                    "kernel_ms": round(enc_ms[0], 4), "lookup": roofline}
+    elif v0 != "fused" and enc_ms[0] > look_ms[0]:
         lane_ops = cost.encode_lane_ops(w0.N, w0.C, w0.K, w0.V)
         achieved = lane_ops / (enc_ms[0] * 1e-3) / 1e12
         peak = cost.PEAK_VALU_F32_LANE_OPS_PER_S / 1e12
@@ -236,7 +259,15 @@ def main():
             n = min(w.N, len(w.X), args.cpu_sample_rows)
             Tf = oracle.build_table_f32(w.P, w.W)  # offline, untimed like on the GPU
             Xs = np.ascontiguousarray(w.X[:n])
-            if w.table_dtype == "i8":
+            if args.encoder == "tree":
+                _t, dims, thr = trees[w.name]
+                if w.table_dtype == "i8":
+                    q, s = oracle.quantize(Tf, 4 if args.int4 else 8)
+                c0 = time.perf_counter()
+                idx = oracle.encode_tree(dims, thr, Xs, w.V)
+                y = (oracle.lookup_i8(q, s, idx, w.bias) if w.table_dtype == "i8"
+                     else oracle.lookup_f32(Tf, idx, w.bias))
+            elif w.table_dtype == "i8":
                 q, s = oracle.quantize(Tf, 4 if args.int4 else 8)
                 c0 = time.perf_counter()
                 y = oracle.linear_i8(w.P, q, s, Xs, w.bias)
@@ -267,8 +298,10 @@ def main():
         "vs_baseline": None, "dtype": "i8" if w0.table_dtype == "i8" else "f32",
         "data": "synthetic",
         "config": {"workload": w_desc, "variant": args.variant, "variant_used": variant_used,
-                   "step": "lutnn_linear (lutnn_conv2d for an image batch) per layer: encode fp32 + "
-                           "lookup, inputs resident in HBM, two rotating X/Y buffer sets"},
+                   "encoder": args.encoder,
+                   "step": ("lutnn_linear_tree per layer: hash encode + lookup" if args.encoder == "tree" else
+                            "lutnn_linear (lutnn_conv2d for an image batch) per layer: encode fp32 + "
+                            "lookup") + ", inputs resident in HBM, two rotating X/Y buffer sets"},
         "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -163,6 +163,50 @@ LUTNN_API lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, in
                                     uint8_t* idx_workspace, void* stream);
 
 /*
+ * Hash encoding (Sec. 2, "Hashing for acceleration"; the alternative to Eq. 2 evaluated in Sec. 7):
+ * each codebook owns a balanced binary tree with `levels` levels whose K = 2^levels leaves are the
+ * buckets.  A sub-vector starts at the root and at every node compares one of its V values, the
+ * node's split index, with the node's threshold:
+ *   node <- 2*node + 1 + (x[split_dim[c][node]] > threshold[c][node])   (root 0; a value equal to
+ *                                                   the threshold, and a NaN, go to the left child)
+ *   idx[n][c] = node - (2^levels - 1) after `levels` steps: the leaf reached, counted from the left.
+ * The descriptor lives in host memory, the arrays it points to in device memory, owned by the
+ * caller.  The trees come from training, like the centroids; the library does not learn them.
+ */
+typedef struct {
+    int32_t C;       /* codebooks                                                             */
+    int32_t V;       /* sub-vector length; D = C*V                                            */
+    int32_t levels;  /* 1..8; K = 2^levels buckets                                            */
+    int32_t reserved; /* must be 0                                                            */
+    const int32_t* split_dim; /* device, [C][2^levels - 1] heap order; values outside [0, V)
+                                 are clamped into it                                          */
+    const float* threshold;   /* device, [C][2^levels - 1] fp32                               */
+} lutnn_tree;
+
+/*
+ *   X    [N][D] fp32, row stride ldx >= D = C*V
+ *   idx  [N][C] uint8, dense; usable by lutnn_lookup with a table of K = 2^levels rows
+ * Errors: E_NULL, E_SHAPE (C, V < 1, levels outside 1..8, reserved != 0, ldx < D), E_HIP.
+ */
+LUTNN_API lutnn_status lutnn_encode_tree(const lutnn_tree* tree, const float* X, int64_t N,
+                                         int64_t ldx, uint8_t* idx, void* stream);
+
+/*
+ * The whole operator with the hash encoder in front: lutnn_encode_tree into idx_workspace, then
+ * lutnn_lookup(layer, idx_workspace, ..., variant).  layer->C and V must equal the tree's and
+ * layer->K must be 2^levels; layer->centroids is not used (the table rows are the buckets'
+ * prototypes times the weights, built by lutnn_build_table from whatever prototypes training
+ * assigned to the buckets).
+ *   idx_workspace  [N][C] uint8 device scratch, required
+ *   variant        a lookup variant: AUTO, LDS, MFMA or SMFMAC
+ * Errors: as lutnn_encode_tree and lutnn_lookup; E_SHAPE when tree and layer disagree.
+ */
+LUTNN_API lutnn_status lutnn_linear_tree(const lutnn_layer* layer, const lutnn_tree* tree,
+                                         const float* X, int64_t N, int64_t ldx, float* Y,
+                                         int64_t ldy, int32_t variant, uint8_t* idx_workspace,
+                                         void* stream);
+
+/*
  * A 2-D convolution as the operator above (Sec. 4: a convolution becomes a matrix product by
  * im2col, with M = output channels, D = input channels x filter size and N = output pixels).
  * Row n = (image b, output pixel ho, wo), b slowest; column j = (input channel ci, filter row r,

@@ -28,7 +28,7 @@ VARIANTS = {"auto": VARIANT_AUTO, "lds": VARIANT_LDS, "mfma": VARIANT_MFMA, "fus
             "smfmac": VARIANT_SMFMAC}
 
 EXPORTS = ["lutnn_table_bytes", "lutnn_packed_bytes", "lutnn_build_table", "lutnn_encode",
-           "lutnn_lookup", "lutnn_linear", "lutnn_conv2d_rows", "lutnn_encode_conv2d", "lutnn_conv2d",
+           "lutnn_lookup", "lutnn_linear", "lutnn_encode_tree", "lutnn_linear_tree", "lutnn_conv2d_rows", "lutnn_encode_conv2d", "lutnn_conv2d",
            "lutnn_auto_variant", "lutnn_status_string", "lutnn_last_error", "lutnn_version"]
 
 
@@ -50,6 +50,12 @@ class _CLayer(ctypes.Structure):
 class _CConvGeom(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("Cin", "H", "W", "kh", "kw", "stride_h", "stride_w",
                                               "pad_h", "pad_w", "reserved")]
+
+
+class _CTree(ctypes.Structure):
+    _fields_ = [("C", ctypes.c_int32), ("V", ctypes.c_int32), ("levels", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("split_dim", ctypes.c_void_p),
+                ("threshold", ctypes.c_void_p)]
 
 
 def _load():
@@ -77,6 +83,11 @@ def _load():
     lib.lutnn_lookup.argtypes = [ctypes.POINTER(_CLayer), vp, i64, vp, i64, i32, vp]
     lib.lutnn_linear.restype = i32
     lib.lutnn_linear.argtypes = [ctypes.POINTER(_CLayer), vp, i64, i64, vp, i64, i32, vp, vp]
+    lib.lutnn_encode_tree.restype = i32
+    lib.lutnn_encode_tree.argtypes = [ctypes.POINTER(_CTree), vp, i64, i64, vp, vp]
+    lib.lutnn_linear_tree.restype = i32
+    lib.lutnn_linear_tree.argtypes = [ctypes.POINTER(_CLayer), ctypes.POINTER(_CTree), vp, i64, i64, vp,
+                                      i64, i32, vp, vp]
     lib.lutnn_conv2d_rows.restype = i64
     lib.lutnn_conv2d_rows.argtypes = [ctypes.POINTER(_CConvGeom), i64]
     lib.lutnn_encode_conv2d.restype = i32
@@ -190,6 +201,49 @@ def lookup(layer, idx, variant="auto", out=None):
     assert out.dtype == torch.float32 and out.stride(1) == 1 and out.shape == (N, layer.M)
     _check(LIB.lutnn_lookup(ctypes.byref(layer.c), _ptr(idx), N, _ptr(out), out.stride(0),
                             _variant(variant), _stream()))
+    return out
+
+
+class LutTree:
+    """Device buffers of the hash encoder's threshold trees (Sec. 2) plus their C descriptor.
+    split_dim [C, 2^levels - 1] int32 and threshold (same shape) fp32, heap order."""
+
+    def __init__(self, split_dim, threshold, V):
+        assert split_dim.is_cuda and threshold.is_cuda
+        assert split_dim.dtype == torch.int32 and threshold.dtype == torch.float32
+        assert split_dim.shape == threshold.shape and split_dim.dim() == 2
+        C, nodes = split_dim.shape
+        levels = (nodes + 1).bit_length() - 1
+        assert nodes == (1 << levels) - 1, "a tree has 2^levels - 1 nodes"
+        self.C, self.V, self.levels, self.K = int(C), int(V), levels, 1 << levels
+        self.split_dim = split_dim.contiguous()
+        self.threshold = threshold.contiguous()
+        self.c = _CTree(self.C, self.V, levels, 0, self.split_dim.data_ptr(), self.threshold.data_ptr())
+
+
+def encode_tree(tree, X, out=None):
+    """lutnn_encode_tree: hash encoding.  X [N, D] fp32 (row stride free) -> idx [N, C] uint8."""
+    assert X.is_cuda and X.dtype == torch.float32 and X.stride(1) == 1
+    N = X.shape[0]
+    if out is None:
+        out = torch.empty((N, tree.C), dtype=torch.uint8, device=X.device)
+    assert out.is_contiguous() and out.shape == (N, tree.C) and out.dtype == torch.uint8
+    _check(LIB.lutnn_encode_tree(ctypes.byref(tree.c), _ptr(X), N, X.stride(0), _ptr(out), _stream()))
+    return out
+
+
+def linear_tree(layer, tree, X, variant="auto", out=None, idx_workspace=None):
+    """lutnn_linear_tree: hash encoding, then the table lookup of Eq. 4."""
+    assert X.is_cuda and X.dtype == torch.float32 and X.stride(1) == 1
+    N = X.shape[0]
+    if out is None:
+        out = torch.empty((N, layer.M), dtype=torch.float32, device=X.device)
+    assert out.dtype == torch.float32 and out.stride(1) == 1 and out.shape == (N, layer.M)
+    if idx_workspace is None:
+        idx_workspace = torch.empty((N, layer.C), dtype=torch.uint8, device=X.device)
+    _check(LIB.lutnn_linear_tree(ctypes.byref(layer.c), ctypes.byref(tree.c), _ptr(X), N, X.stride(0),
+                                 _ptr(out), out.stride(0), _variant(variant), _ptr(idx_workspace),
+                                 _stream()))
     return out
 
 

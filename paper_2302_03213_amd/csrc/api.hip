@@ -135,6 +135,24 @@ lutnn_status check_encode(const lutnn_layer* L, const float* X, int64_t N, int64
     return LUTNN_OK;
 }
 
+lutnn_status check_tree(const lutnn_tree* T, const float* X, int64_t N, int64_t ldx) {
+    if (!T) return fail(LUTNN_E_NULL, "tree is NULL");
+    if (T->reserved != 0) return fail(LUTNN_E_SHAPE, "tree->reserved must be 0");
+    if (T->levels < 1 || T->levels > 8)
+        return fail(LUTNN_E_SHAPE, "tree->levels=%d outside 1..8 (indices are uint8)", T->levels);
+    if (lutnn_status st = check_dims(T->C, 1 << T->levels, T->V, 1)) return st;
+    if (N == 0) return LUTNN_OK;
+    if (!T->split_dim || !T->threshold) return fail(LUTNN_E_NULL, "tree->split_dim or tree->threshold is NULL");
+    if (!X) return fail(LUTNN_E_NULL, "X is NULL");
+    if (N < 0 || N >= kMaxRows) return fail(LUTNN_E_SHAPE, "N=%lld out of range", (long long)N);
+    if (ldx < (int64_t)T->C * T->V)
+        return fail(LUTNN_E_SHAPE, "ldx=%lld is smaller than D=C*V=%lld", (long long)ldx,
+                    (long long)T->C * T->V);
+    if (!aligned(X, 4) || !aligned(T->split_dim, 4) || !aligned(T->threshold, 4))
+        return fail(LUTNN_E_ALIGN, "X, split_dim and threshold must be 4-byte aligned");
+    return LUTNN_OK;
+}
+
 // Validates a convolution geometry against the layer and derives the output size.
 lutnn_status check_conv(const lutnn_layer* L, const lutnn_conv2d_geom* g, int64_t B, lutnn::ConvGeom* out,
                         int64_t* rows) {
@@ -231,6 +249,39 @@ lutnn_status lutnn_encode(const lutnn_layer* layer, const float* X, int64_t N, i
     return hip_result(lutnn::launch_encode(layer->centroids, layer->C, layer->K, layer->V, X, N, ldx, idx,
                                            static_cast<hipStream_t>(stream)),
                       "encode launch");
+}
+
+lutnn_status lutnn_encode_tree(const lutnn_tree* tree, const float* X, int64_t N, int64_t ldx,
+                               uint8_t* idx, void* stream) {
+    if (lutnn_status st = check_tree(tree, X, N, ldx)) return st;
+    if (N == 0) return LUTNN_OK;
+    if (!idx) return fail(LUTNN_E_NULL, "idx is NULL");
+    return hip_result(lutnn::launch_encode_tree(tree->split_dim, tree->threshold, tree->C, tree->levels,
+                                                tree->V, X, N, ldx, idx, static_cast<hipStream_t>(stream)),
+                      "tree encode launch");
+}
+
+lutnn_status lutnn_linear_tree(const lutnn_layer* layer, const lutnn_tree* tree, const float* X,
+                               int64_t N, int64_t ldx, float* Y, int64_t ldy, int32_t variant,
+                               uint8_t* idx_workspace, void* stream) {
+    if (lutnn_status st = check_layer(layer)) return st;
+    if (lutnn_status st = check_tree(tree, X, N, ldx)) return st;
+    if (tree->C != layer->C || tree->V != layer->V || (1 << tree->levels) != layer->K)
+        return fail(LUTNN_E_SHAPE, "tree (C=%d V=%d levels=%d) does not match layer (C=%d V=%d K=%d)", tree->C,
+                    tree->V, tree->levels, layer->C, layer->V, layer->K);
+    if (N == 0) return LUTNN_OK;
+    if (!idx_workspace) return fail(LUTNN_E_NULL, "idx_workspace is NULL");
+    if (variant == LUTNN_VARIANT_FUSED)
+        return fail(LUTNN_E_UNSUPPORTED, "there is no fused kernel for the hash encoder");
+    const int v = resolve_lookup_variant(layer, variant, idx_workspace, N);
+    if (lutnn_status st = check_lookup(layer, v, idx_workspace, Y, N, ldy)) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (lutnn_status st = hip_result(lutnn::launch_encode_tree(tree->split_dim, tree->threshold, tree->C,
+                                                               tree->levels, tree->V, X, N, ldx,
+                                                               idx_workspace, s),
+                                     "tree encode launch"))
+        return st;
+    return do_lookup(layer, v, idx_workspace, N, Y, ldy, s);
 }
 
 lutnn_status lutnn_lookup(const lutnn_layer* layer, const uint8_t* idx, int64_t N, float* Y,

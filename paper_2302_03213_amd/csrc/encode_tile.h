@@ -46,27 +46,50 @@ __device__ __forceinline__ void stage_x(const float* __restrict__ X, int64_t ldx
                                         int64_t row0, int c0, float* __restrict__ xs, int vec4,
                                         int tid) {
     using E = EncTile<V, CT>;
+    // All of a thread's loads are issued before the first LDS write, so that their latencies
+    // overlap instead of adding up (a workgroup has nothing else to do until the tile is staged).
     if (vec4) {
         constexpr int Q = E::TW / 4;
-        for (int i = tid; i < kEncRows * Q; i += kEncThreads) {
+        constexpr int ITER = (kEncRows * Q + kEncThreads - 1) / kEncThreads;
+        float4 val[ITER];
+#pragma unroll
+        for (int it = 0; it < ITER; ++it) {
+            const int i = tid + it * kEncThreads;
             const int r = i / Q, col = (i % Q) * 4;
             const int gcol = c0 * V + col;
-            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row0 + r < N && gcol < D)
-                val = *reinterpret_cast<const float4*>(X + (row0 + r) * ldx + gcol);
-            float* dst = xs + r * E::LS + col;
-            dst[0] = val.x;
-            dst[1] = val.y;
-            dst[2] = val.z;
-            dst[3] = val.w;
+            val[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i < kEncRows * Q && row0 + r < N && gcol < D)
+                val[it] = *reinterpret_cast<const float4*>(X + (row0 + r) * ldx + gcol);
+        }
+#pragma unroll
+        for (int it = 0; it < ITER; ++it) {
+            const int i = tid + it * kEncThreads;
+            if (i < kEncRows * Q) {
+                float* dst = xs + (i / Q) * E::LS + (i % Q) * 4;
+                dst[0] = val[it].x;
+                dst[1] = val[it].y;
+                dst[2] = val[it].z;
+                dst[3] = val[it].w;
+            }
         }
     } else {
-        for (int i = tid; i < kEncRows * E::TW; i += kEncThreads) {
-            const int r = i / E::TW, col = i % E::TW;
-            const int gcol = c0 * V + col;
-            float val = 0.f;
-            if (row0 + r < N && gcol < D) val = X[(row0 + r) * ldx + gcol];
-            xs[r * E::LS + col] = val;
+        constexpr int TOTAL = kEncRows * E::TW;
+        constexpr int BATCH = 8;
+        for (int i0 = tid; i0 < TOTAL; i0 += BATCH * kEncThreads) {
+            float val[BATCH];
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) {
+                const int i = i0 + b * kEncThreads;
+                const int r = i / E::TW, col = i % E::TW;
+                const int gcol = c0 * V + col;
+                val[b] = 0.f;
+                if (i < TOTAL && row0 + r < N && gcol < D) val[b] = X[(row0 + r) * ldx + gcol];
+            }
+#pragma unroll
+            for (int b = 0; b < BATCH; ++b) {
+                const int i = i0 + b * kEncThreads;
+                if (i < TOTAL) xs[(i / E::TW) * E::LS + i % E::TW] = val[b];
+            }
         }
     }
 }

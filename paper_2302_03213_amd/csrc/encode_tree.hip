@@ -1,0 +1,195 @@
+// Hash encoding (arXiv 2302.03213, Sec. 2 "Hashing for acceleration", evaluated in Sec. 7) for gfx950.
+//
+// In place of the arg-min over K distances, every codebook owns a balanced binary tree with
+// `levels` levels; its 2^levels leaves are the buckets.  A sub-vector starts at the root, and at
+// each node compares ONE of its V values (the node's split index) with the node's threshold:
+//
+//   node <- 2*node + 1 + (x[split[node]] > threshold[node])        heap order, root 0
+//   idx[n][c] = node - (2^levels - 1) after `levels` steps          leaves counted from the left
+//
+// The paper found this slower than the distance search on SIMD CPUs because the walk is a chain of
+// dependent, data-dependent steps.  With lane = row a wavefront walks 64 trees at once and the
+// steps of different codebooks are independent, so the cost per sub-vector is `levels` pairs of
+// LDS reads and a handful of VALU operations against ~11*K operations for Eq. 2 with V = 4: the
+// kernel is bound by reading X from HBM.
+//
+// Mapping: the tile machinery of the distance encoder (64 rows x CT codebooks of X staged through
+// LDS with coalesced row segments, indices leaving through LDS as contiguous row segments).  The
+// tile's nodes are staged as (threshold, split index) pairs so that a step is one 8-byte LDS read
+// for the node and one 4-byte LDS read for the value it points at; within a wavefront the node
+// reads hit at most 2^level distinct addresses.
+#include <algorithm>
+
+#include "encode_tile.h"
+#include "lutnn_kernels.h"
+
+namespace lutnn {
+namespace {
+
+// L_T: levels when known at compile time (0 = run-time value).
+template <int V, int CT, int L_T>
+__global__ __launch_bounds__(kEncThreads) void encode_tree_tile_kernel(
+    const float* __restrict__ X, int64_t ldx, const int32_t* __restrict__ split_dim,
+    const float* __restrict__ threshold, uint8_t* __restrict__ idx, int64_t N, int C, int levels_rt,
+    int vec4, int idx_dword_ok) {
+    using E = EncTile<V, CT>;
+    __shared__ float xs[E::kLdsFloats];
+    __shared__ uint32_t is[kEncRows * (CT / 4)];
+    extern __shared__ uint2 tp[];  // [CT][nodes]: .x = threshold bits, .y = split index
+
+    const int levels = L_T ? L_T : levels_rt;
+    const int nodes = (1 << levels) - 1;
+    const int col_tiles = (C + CT - 1) / CT;
+    const int64_t row0 = (int64_t)(blockIdx.x / col_tiles) * kEncRows;
+    const int c0 = (int)(blockIdx.x % col_tiles) * CT;
+    const int tid = threadIdx.x;
+
+    // the tile's codebooks are contiguous in both node arrays; a split index outside [0, V) is
+    // clamped so that no value outside the sub-vector is ever read.  Codebooks past C get
+    // (threshold 0, index 0) nodes: their walk is harmless and its result is dropped.
+    const int staged = std::min(CT, C - c0) * nodes;
+    for (int i = tid; i < CT * nodes; i += kEncThreads) {
+        uint2 node = make_uint2(0u, 0u);
+        if (i < staged) {
+            const size_t g = (size_t)c0 * nodes + i;
+            const int d = split_dim[g];
+            node = make_uint2(__float_as_uint(threshold[g]), (uint32_t)(d < 0 ? 0 : d >= V ? V - 1 : d));
+        }
+        tp[i] = node;
+    }
+    stage_x<V, CT>(X, ldx, N, C * V, row0, c0, xs, vec4, tid);
+    __syncthreads();
+
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    // The wavefront's CPW codebooks advance one level at a time: their walks are independent, so
+    // the LDS latency of one overlaps the others.
+    int node[E::CPW];
+#pragma unroll
+    for (int j = 0; j < E::CPW; ++j) node[j] = 0;
+    const float* __restrict__ xrow = xs + lane * E::LS + w * E::CPW * V;
+    const uint2* __restrict__ tw = tp + (size_t)w * E::CPW * nodes;
+    auto step = [&]() {
+        uint2 p[E::CPW];
+        float x[E::CPW];
+#pragma unroll
+        for (int j = 0; j < E::CPW; ++j) p[j] = tw[j * nodes + node[j]];
+#pragma unroll
+        for (int j = 0; j < E::CPW; ++j) x[j] = xrow[j * V + p[j].y];
+#pragma unroll
+        for (int j = 0; j < E::CPW; ++j) node[j] = 2 * node[j] + 1 + (x[j] > __uint_as_float(p[j].x) ? 1 : 0);
+    };
+    if constexpr (L_T != 0) {
+#pragma unroll
+        for (int l = 0; l < L_T; ++l) step();
+    } else {
+        for (int l = 0; l < levels; ++l) step();
+    }
+    uint32_t packed[E::PW];
+#pragma unroll
+    for (int j = 0; j < E::PW; ++j) packed[j] = 0;
+#pragma unroll
+    for (int j = 0; j < E::CPW; ++j) {
+        const uint32_t leaf = (c0 + w * E::CPW + j < C) ? (uint32_t)(node[j] - nodes) : 0u;
+        packed[j / 4] |= leaf << (8 * (j % 4));
+    }
+    store_index_bytes<V, CT>(is + lane * (CT / 4), w * E::CPW, packed);
+    __syncthreads();
+
+    for (int i = tid; i < kEncRows * (CT / 4); i += kEncThreads) {
+        const int r = i / (CT / 4), j = i % (CT / 4);
+        const int c = c0 + 4 * j;
+        if (row0 + r >= N || c >= C) continue;
+        const uint32_t wv = is[i];
+        uint8_t* dst = idx + (row0 + r) * (int64_t)C + c;
+        if (idx_dword_ok) {  // C % 4 == 0 and idx 4-byte aligned -> the whole dword is in range
+            *reinterpret_cast<uint32_t*>(dst) = wv;
+        } else {
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                if (c + b < C) dst[b] = (uint8_t)(wv >> (8 * b));
+        }
+    }
+}
+
+// Any V: one thread per sub-vector, everything from global memory.
+__global__ __launch_bounds__(kEncThreads) void encode_tree_generic_kernel(
+    const float* __restrict__ X, int64_t ldx, const int32_t* __restrict__ split_dim,
+    const float* __restrict__ threshold, uint8_t* __restrict__ idx, int64_t N, int C, int levels,
+    int V) {
+    const int64_t i = (int64_t)blockIdx.x * kEncThreads + threadIdx.x;
+    if (i >= N * (int64_t)C) return;
+    const int64_t n = i / C;
+    const int c = (int)(i % C);
+    const int nodes = (1 << levels) - 1;
+    const float* x = X + n * ldx + (int64_t)c * V;
+    const int32_t* dim = split_dim + (size_t)c * nodes;
+    const float* thr = threshold + (size_t)c * nodes;
+    int node = 0;
+    for (int l = 0; l < levels; ++l) {
+        const int d = dim[node];
+        node = 2 * node + 1 + (x[d < 0 ? 0 : d >= V ? V - 1 : d] > thr[node] ? 1 : 0);
+    }
+    idx[i] = (uint8_t)(node - nodes);
+}
+
+template <int V, int CT>
+hipError_t launch_tree_ct(const int32_t* split_dim, const float* threshold, int C, int levels,
+                          const float* X, int64_t N, int64_t ldx, uint8_t* idx, hipStream_t s) {
+    const int64_t row_tiles = (N + kEncRows - 1) / kEncRows;
+    const int64_t col_tiles = (C + CT - 1) / CT;
+    const int64_t blocks = row_tiles * col_tiles;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int vec4 = ((CT * V) % 4 == 0) && (((int64_t)C * V) % 4 == 0) && (ldx % 4 == 0) &&
+                     ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
+    const int idx_dword_ok = (C % 4 == 0) && ((reinterpret_cast<uintptr_t>(idx) & 3) == 0);
+    const size_t node_bytes = (size_t)CT * ((1u << levels) - 1) * sizeof(uint2);
+    dim3 grid((unsigned)blocks), block(kEncThreads);
+    if (levels == 4)
+        hipLaunchKernelGGL((encode_tree_tile_kernel<V, CT, 4>), grid, block, node_bytes, s, X, ldx,
+                           split_dim, threshold, idx, N, C, levels, vec4, idx_dword_ok);
+    else
+        hipLaunchKernelGGL((encode_tree_tile_kernel<V, CT, 0>), grid, block, node_bytes, s, X, ldx,
+                           split_dim, threshold, idx, N, C, levels, vec4, idx_dword_ok);
+    return hipGetLastError();
+}
+
+// Tile width: the full tile unless the grid would be small (as for the distance encoder) or the
+// tile's nodes would take more than 24 KiB of LDS (deep trees); then a quarter of it.
+template <int V>
+hipError_t launch_tree(const int32_t* split_dim, const float* threshold, int C, int levels,
+                       const float* X, int64_t N, int64_t ldx, uint8_t* idx, hipStream_t s) {
+    constexpr int CT = enc_tile_codebooks(V);
+    constexpr int CT_SMALL = CT / 4 >= 4 ? CT / 4 : 4;
+    const int64_t full_blocks = ((N + kEncRows - 1) / kEncRows) * ((C + CT - 1) / CT);
+    const size_t full_node_bytes = (size_t)CT * ((1u << levels) - 1) * sizeof(uint2);
+    if (CT_SMALL < CT && (full_blocks < 1024 || full_node_bytes > 24 * 1024))
+        return launch_tree_ct<V, CT_SMALL>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+    return launch_tree_ct<V, CT>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+}
+
+}  // namespace
+
+hipError_t launch_encode_tree(const int32_t* split_dim, const float* threshold, int C, int levels,
+                              int V, const float* X, int64_t N, int64_t ldx, uint8_t* idx,
+                              hipStream_t s) {
+    switch (V) {
+        case 1: return launch_tree<1>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        case 2: return launch_tree<2>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        case 3: return launch_tree<3>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        case 4: return launch_tree<4>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        case 8: return launch_tree<8>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        case 9: return launch_tree<9>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        case 16: return launch_tree<16>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        case 32: return launch_tree<32>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        default: break;
+    }
+    const int64_t total = N * (int64_t)C;
+    const int64_t blocks = (total + kEncThreads - 1) / kEncThreads;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(encode_tree_generic_kernel, dim3((unsigned)blocks), dim3(kEncThreads), 0, s, X, ldx,
+                       split_dim, threshold, idx, N, C, levels, V);
+    return hipGetLastError();
+}
+
+}  // namespace lutnn

@@ -29,6 +29,11 @@ hipError_t launch_encode_conv(const float* P, int C, int K, int V, const float* 
 hipError_t launch_encode(const float* P, int C, int K, int V, const float* X, int64_t N, int64_t ldx,
                          uint8_t* idx, hipStream_t s);
 
+// Hash encoding (Sec. 2, Sec. 7): per codebook a heap-ordered threshold tree with `levels` levels.
+hipError_t launch_encode_tree(const int32_t* split_dim, const float* threshold, int C, int levels,
+                              int V, const float* X, int64_t N, int64_t ldx, uint8_t* idx,
+                              hipStream_t s);
+
 // Eq. 3 + Sec. 3.3.
 hipError_t launch_build_table_f32(const float* P, const float* W, int64_t ldw, int C, int K, int V,
                                   int M, float* T, hipStream_t s);
