@@ -207,6 +207,41 @@ LUTNN_API lutnn_status lutnn_linear_tree(const lutnn_layer* layer, const lutnn_t
                                          void* stream);
 
 /*
+ * Soft-PQ backward pass (Sec. 3.1 "Backpropagation through soft-PQ", Eq. 5-6; Sec. 3.2 "Learned
+ * temperature").  In training the layer's VALUE is the hard output that lutnn_linear computes, and
+ * its GRADIENT is that of the soft output
+ *   Ysoft[n][m] = sum_c sum_k s[n][c][k] * T[c][k][m],   s[n][c][:] = softmax_k(-||x_n^c - P^c_k||^2 / t),
+ * with the real-valued table T = P . W of Eq. 3 (Sec. 3.3: the backward pass does not quantise).
+ * The weights W stay fixed (the tables are rebuilt from the updated centroids), so everything
+ * follows from  Z = dL/dY . W^T, the input gradient of the ordinary linear layer with the same
+ * weights, which the caller computes with any GEMM:
+ *   dP[c][k][v] = dL/dP       gradient for the centroids
+ *   dX[n][cV+v] = dL/dX       gradient for the layer input (earlier layers need it)
+ *   dt          = dL/dt       gradient for the layer's temperature
+ * All arithmetic is fp32; sums over rows are taken in a fixed order (reproducible run to run).
+ *
+ *   temperature  t > 0
+ *   X   [N][D] fp32, row stride ldx >= D = C*V            (the forward pass's input)
+ *   Z   [N][D] fp32, row stride ldz >= D
+ *   dP  [C][K][V] fp32, overwritten
+ *   dX  [N][D] fp32, row stride lddx >= D, overwritten; NULL to skip it
+ *   dt  one fp32, overwritten; NULL to skip it
+ *   workspace  device scratch of at least lutnn_softpq_workspace_bytes(C, K, V, N) bytes, 4-byte
+ *              aligned; contents unspecified afterwards
+ * Uses layer->centroids, C, K, V.  Supported: K = 8 or 16 with V in {1,2,3,4,8,9,16,32} (the
+ * paper's settings); anything else is E_UNSUPPORTED.
+ * Errors: E_NULL, E_SHAPE (also t <= 0, workspace too small), E_UNSUPPORTED, E_ALIGN, E_HIP.
+ */
+LUTNN_API lutnn_status lutnn_softpq_backward(const lutnn_layer* layer, float temperature,
+                                             const float* X, int64_t N, int64_t ldx, const float* Z,
+                                             int64_t ldz, float* dP, float* dX, int64_t lddx,
+                                             float* dt, void* workspace, size_t workspace_bytes,
+                                             void* stream);
+
+/* Host: bytes of workspace lutnn_softpq_backward needs; 0 for unsupported (K, V) or empty shapes. */
+LUTNN_API size_t lutnn_softpq_workspace_bytes(int32_t C, int32_t K, int32_t V, int64_t N);
+
+/*
  * A 2-D convolution as the operator above (Sec. 4: a convolution becomes a matrix product by
  * im2col, with M = output channels, D = input channels x filter size and N = output pixels).
  * Row n = (image b, output pixel ho, wo), b slowest; column j = (input channel ci, filter row r,

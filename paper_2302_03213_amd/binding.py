@@ -28,7 +28,8 @@ VARIANTS = {"auto": VARIANT_AUTO, "lds": VARIANT_LDS, "mfma": VARIANT_MFMA, "fus
             "smfmac": VARIANT_SMFMAC}
 
 EXPORTS = ["lutnn_table_bytes", "lutnn_packed_bytes", "lutnn_build_table", "lutnn_encode",
-           "lutnn_lookup", "lutnn_linear", "lutnn_encode_tree", "lutnn_linear_tree", "lutnn_conv2d_rows", "lutnn_encode_conv2d", "lutnn_conv2d",
+           "lutnn_lookup", "lutnn_linear", "lutnn_encode_tree", "lutnn_linear_tree",
+           "lutnn_softpq_backward", "lutnn_softpq_workspace_bytes", "lutnn_conv2d_rows", "lutnn_encode_conv2d", "lutnn_conv2d",
            "lutnn_auto_variant", "lutnn_status_string", "lutnn_last_error", "lutnn_version"]
 
 
@@ -88,6 +89,11 @@ def _load():
     lib.lutnn_linear_tree.restype = i32
     lib.lutnn_linear_tree.argtypes = [ctypes.POINTER(_CLayer), ctypes.POINTER(_CTree), vp, i64, i64, vp,
                                       i64, i32, vp, vp]
+    lib.lutnn_softpq_workspace_bytes.restype = ctypes.c_size_t
+    lib.lutnn_softpq_workspace_bytes.argtypes = [i32, i32, i32, i64]
+    lib.lutnn_softpq_backward.restype = i32
+    lib.lutnn_softpq_backward.argtypes = [ctypes.POINTER(_CLayer), ctypes.c_float, vp, i64, i64, vp, i64, vp,
+                                          vp, i64, vp, vp, ctypes.c_size_t, vp]
     lib.lutnn_conv2d_rows.restype = i64
     lib.lutnn_conv2d_rows.argtypes = [ctypes.POINTER(_CConvGeom), i64]
     lib.lutnn_encode_conv2d.restype = i32
@@ -245,6 +251,30 @@ def linear_tree(layer, tree, X, variant="auto", out=None, idx_workspace=None):
                                  _ptr(out), out.stride(0), _variant(variant), _ptr(idx_workspace),
                                  _stream()))
     return out
+
+
+def softpq_workspace_bytes(C, K, V, N):
+    return int(LIB.lutnn_softpq_workspace_bytes(C, K, V, N))
+
+
+def softpq_backward(layer, temperature, X, Z, need_dx=True, workspace=None):
+    """lutnn_softpq_backward: gradients of the soft output (Eq. 5-6) from Z = dL/dY @ W^T.
+    Returns (dP [C, K, V], dX [N, D] or None, dt [1])."""
+    assert X.is_cuda and X.dtype == torch.float32 and X.stride(1) == 1
+    assert Z.is_cuda and Z.dtype == torch.float32 and Z.stride(1) == 1 and Z.shape == X.shape
+    N = X.shape[0]
+    dP = torch.empty((layer.C, layer.K, layer.V), dtype=torch.float32, device=X.device)
+    dX = torch.empty((N, layer.C * layer.V), dtype=torch.float32, device=X.device) if need_dx else None
+    dt = torch.empty(1, dtype=torch.float32, device=X.device)
+    need = softpq_workspace_bytes(layer.C, layer.K, layer.V, N)
+    if workspace is None:
+        workspace = torch.empty(max(need, 4), dtype=torch.uint8, device=X.device)
+    assert workspace.is_cuda and workspace.is_contiguous()
+    _check(LIB.lutnn_softpq_backward(ctypes.byref(layer.c), float(temperature), _ptr(X), N, X.stride(0),
+                                     _ptr(Z), Z.stride(0), _ptr(dP), _ptr(dX),
+                                     dX.stride(0) if need_dx else 0, _ptr(dt), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream()))
+    return dP, dX, dt
 
 
 def _pair(v):

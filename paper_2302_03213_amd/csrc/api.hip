@@ -2,6 +2,7 @@
 // include/lutnn.h.  Nothing here allocates device memory or synchronises.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -282,6 +283,45 @@ lutnn_status lutnn_linear_tree(const lutnn_layer* layer, const lutnn_tree* tree,
                                      "tree encode launch"))
         return st;
     return do_lookup(layer, v, idx_workspace, N, Y, ldy, s);
+}
+
+size_t lutnn_softpq_workspace_bytes(int32_t C, int32_t K, int32_t V, int64_t N) {
+    if (C <= 0 || K <= 0 || V <= 0 || N <= 0) return 0;
+    return lutnn::softpq_workspace_bytes(C, K, V, N);
+}
+
+lutnn_status lutnn_softpq_backward(const lutnn_layer* layer, float temperature, const float* X, int64_t N,
+                                   int64_t ldx, const float* Z, int64_t ldz, float* dP, float* dX,
+                                   int64_t lddx, float* dt, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+    if (lutnn_status st = check_layer(layer)) return st;
+    if (!(temperature > 0.0f) || !std::isfinite(temperature))
+        return fail(LUTNN_E_SHAPE, "temperature must be positive and finite (got %g)", (double)temperature);
+    if (!lutnn::softpq_supported(layer->K, layer->V))
+        return fail(LUTNN_E_UNSUPPORTED, "soft-PQ backward supports K in {8,16} and V in {1,2,3,4,8,9,16,32} "
+                    "(got K=%d V=%d)", layer->K, layer->V);
+    if (!dP) return fail(LUTNN_E_NULL, "dP is NULL");
+    if (N < 0 || N >= kMaxRows) return fail(LUTNN_E_SHAPE, "N=%lld out of range", (long long)N);
+    const int64_t D = (int64_t)layer->C * layer->V;
+    if (N > 0) {  // an empty batch may come with NULL data pointers
+        if (lutnn_status st = check_encode(layer, X, N, ldx)) return st;
+        if (!Z) return fail(LUTNN_E_NULL, "Z is NULL");
+        if (ldz < D) return fail(LUTNN_E_SHAPE, "ldz=%lld is smaller than D=%lld", (long long)ldz, (long long)D);
+        if (dX && lddx < D)
+            return fail(LUTNN_E_SHAPE, "lddx=%lld is smaller than D=%lld", (long long)lddx, (long long)D);
+        if (!workspace) return fail(LUTNN_E_NULL, "workspace is NULL");
+        const size_t need = lutnn::softpq_workspace_bytes(layer->C, layer->K, layer->V, N);
+        if (workspace_bytes < need)
+            return fail(LUTNN_E_SHAPE, "workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, need);
+    }
+    if (!aligned(Z, 4) || !aligned(dP, 4) || !aligned(dX, 4) || !aligned(dt, 4) || !aligned(workspace, 4))
+        return fail(LUTNN_E_ALIGN, "Z, dP, dX, dt and workspace must be 4-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // N == 0: the launcher only writes the zeros of the empty sums
+    return hip_result(lutnn::launch_softpq_backward(layer->centroids, layer->C, layer->K, layer->V, temperature,
+                                                    X, N, ldx, Z, ldz, dP, dX, lddx, dt,
+                                                    static_cast<float*>(workspace), s),
+                      "soft-PQ backward launch");
 }
 
 lutnn_status lutnn_lookup(const lutnn_layer* layer, const uint8_t* idx, int64_t N, float* Y,

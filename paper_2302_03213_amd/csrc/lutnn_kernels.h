@@ -34,6 +34,14 @@ hipError_t launch_encode_tree(const int32_t* split_dim, const float* threshold, 
                               int V, const float* X, int64_t N, int64_t ldx, uint8_t* idx,
                               hipStream_t s);
 
+// Soft-PQ backward (Sec. 3.1-3.2, Eq. 5-6): gradients with respect to the centroids, the layer
+// input and the temperature, from Z = dL/dY . W^T.  workspace: softpq_workspace_bytes() bytes.
+bool softpq_supported(int K, int V);
+size_t softpq_workspace_bytes(int C, int K, int V, int64_t N);
+hipError_t launch_softpq_backward(const float* P, int C, int K, int V, float t, const float* X, int64_t N,
+                                  int64_t ldx, const float* Z, int64_t ldz, float* dP, float* dX,
+                                  int64_t lddx, float* dt, float* workspace, hipStream_t s);
+
 // Eq. 3 + Sec. 3.3.
 hipError_t launch_build_table_f32(const float* P, const float* W, int64_t ldw, int C, int K, int V,
                                   int M, float* T, hipStream_t s);

@@ -1,0 +1,170 @@
+"""GPU parity of the soft-PQ backward pass (Sec. 3.1-3.2, Eq. 5-6 of arXiv 2302.03213) against the
+fp64 oracle.  The kernel works in fp32 from Z = G . W^T (formed here in fp64 and rounded once); the
+oracle applies the chain rule through the table T = P . W without that factoring.
+
+Bar (the paper fixes no precision for training): every gradient within 5e-5 of the largest
+magnitude of its tensor.  The softmax weights carry a relative error of about (d/t) * 2^-23 plus the
+2 ulp of the hardware exponential, i.e. up to 1e-5 for exponents of a few tens; a sum of N such
+terms in fp32 adds at most N * 2^-24 relative to the sum of magnitudes (1e-3 for N = 16384 in the
+worst case, ~sqrt(N) * 2^-24 = 8e-6 typically).  dt is one sum over all N * C * K terms with
+cancellation, so it is held to 2e-3 of the sum of the terms' magnitudes instead.  Observed: 2e-7 to 8e-7
+for dP and dX."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import lutnn_workloads as wl
+from gpu_util import dev, host
+from oracle import softpq as osp
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lut():
+    import paper_2302_03213_amd as lut_mod
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return lut_mod
+
+
+@pytest.fixture(autouse=True)
+def announce(request):
+    print("\n[case] %s" % request.node.nodeid, file=sys.stderr, flush=True)
+    yield
+
+
+def close(got, ref, frac=5e-5):
+    scale = max(np.abs(ref).max(), 1e-30)
+    err = np.abs(got - ref).max() / scale
+    assert err <= frac, "normalised error %.3e" % err
+    return err
+
+
+def dt_bar(w, t, G):
+    """2e-3 of the sum of |dz_k d_k| / t^2: the magnitude the temperature gradient is summed from."""
+    s, d, _ = osp.soft_encoding(w.P, w.X, t)
+    P64, Wc = w.P.astype(np.float64), w.W.astype(np.float64).reshape(w.C, w.V, -1)
+    ds = np.einsum("nm,ckm->nck", G, np.einsum("ckv,cvm->ckm", P64, Wc))
+    dz = s * (ds - (s * ds).sum(-1, keepdims=True))
+    return 2e-3 * np.abs(dz * d).sum() / (t * t)
+
+
+def run_case(lut, N, C, K, V, M, t, seed, strided=False):
+    w = wl.make_layer("t", N, C, K, V, M, "f32", seed=seed)
+    G = np.random.default_rng(seed).standard_normal((N, M))
+    Z = (G @ w.W.astype(np.float64).T).astype(np.float32)
+    dP_ref, dX_ref, dt_ref = osp.backward(w.P, w.W, w.X, t, G)
+    layer = lut.LutLayer(dev(w.P), None, lut.TABLE_F32, M)
+    if strided:
+        Xb = torch.zeros((N, C * V + 5), dtype=torch.float32, device="cuda")
+        Zb = torch.zeros((N, C * V + 3), dtype=torch.float32, device="cuda")
+        Xb[:, 1:1 + C * V] = dev(w.X)
+        Zb[:, 3:3 + C * V] = dev(Z)
+        Xd, Zd = Xb[:, 1:1 + C * V], Zb[:, 3:3 + C * V]
+    else:
+        Xd, Zd = dev(w.X), dev(Z)
+    dP, dX, dt = lut.softpq_backward(layer, t, Xd, Zd)
+    e1 = close(host(dP), dP_ref)
+    e2 = close(host(dX), dX_ref)
+    assert abs(host(dt)[0] - dt_ref) <= dt_bar(w, t, G), (host(dt)[0], dt_ref)
+    # without the input gradient the other two are unchanged, bit for bit (fixed summation order)
+    dP2, none, dt2 = lut.softpq_backward(layer, t, Xd, Zd, need_dx=False)
+    assert none is None
+    np.testing.assert_array_equal(host(dP2), host(dP))
+    np.testing.assert_array_equal(host(dt2), host(dt))
+    return e1, e2
+
+
+SOFTPQ_SHAPES = [
+    # N, C, K, V, M, t
+    (1, 1, 16, 4, 3, 1.0), (63, 5, 16, 4, 7, 1.0), (64, 16, 16, 4, 20, 0.5), (200, 33, 16, 4, 16, 2.0),
+    (130, 17, 16, 9, 12, 1.0), (130, 8, 8, 9, 12, 3.0), (150, 40, 16, 2, 9, 1.0), (100, 9, 16, 1, 5, 0.3),
+    (100, 35, 16, 3, 6, 1.0), (100, 20, 16, 8, 6, 4.0), (70, 6, 16, 16, 8, 8.0), (70, 5, 16, 32, 8, 16.0),
+    (90, 12, 8, 4, 10, 1.0), (90, 7, 8, 16, 10, 6.0), (66, 3, 8, 32, 4, 20.0), (120, 70, 8, 2, 5, 1.0),
+    # several row tiles per chunk, several chunks, ragged tail
+    (4200, 64, 16, 4, 24, 1.0), (9000, 8, 16, 9, 16, 2.0),
+]
+
+
+@pytest.mark.parametrize("N,C,K,V,M,t", SOFTPQ_SHAPES)
+def test_softpq_backward_matches_oracle(lut, N, C, K, V, M, t):
+    e = run_case(lut, N, C, K, V, M, t, seed=N + C + K + V)
+    print("normalised errors dP %.2e dX %.2e" % e)
+
+
+def test_softpq_backward_strided_and_misaligned_operands(lut):
+    run_case(lut, 130, 9, 16, 4, 11, 1.0, seed=3, strided=True)
+    run_case(lut, 77, 5, 16, 9, 6, 1.5, seed=4, strided=True)
+
+
+def test_softpq_backward_small_temperature_is_finite_and_matches(lut):
+    # t = 0.05: exponents of several hundred; the max-subtracted softmax must not overflow
+    run_case(lut, 128, 8, 16, 4, 8, 0.05, seed=6)
+
+
+def test_softpq_backward_is_reproducible_and_handles_an_empty_batch(lut):
+    w = wl.make_layer("t", 3000, 32, 16, 4, 8, "f32", seed=1)
+    Z = dev(np.random.default_rng(1).standard_normal((3000, 128)).astype(np.float32))
+    layer = lut.LutLayer(dev(w.P), None, lut.TABLE_F32, 8)
+    a = lut.softpq_backward(layer, 1.0, dev(w.X), Z)
+    b = lut.softpq_backward(layer, 1.0, dev(w.X), Z)
+    for x, y in zip(a, b):
+        np.testing.assert_array_equal(host(x), host(y))
+    dP, dX, dt = lut.softpq_backward(layer, 1.0, dev(w.X)[:0], Z[:0])
+    assert not host(dP).any() and dX.shape == (0, 128) and host(dt)[0] == 0.0
+
+
+def test_softpq_backward_unsupported_and_bad_arguments(lut):
+    w = wl.make_layer("t", 8, 4, 5, 4, 8, "f32", seed=1)  # K = 5
+    layer = lut.LutLayer(dev(w.P), None, lut.TABLE_F32, 8)
+    Z = dev(np.zeros((8, 16), np.float32))
+    with pytest.raises(lut.LutnnError) as e:
+        lut.softpq_backward(layer, 1.0, dev(w.X), Z)
+    assert e.value.status == 3
+    w = wl.make_layer("t", 8, 4, 16, 4, 8, "f32", seed=1)
+    layer = lut.LutLayer(dev(w.P), None, lut.TABLE_F32, 8)
+    for bad_t in (0.0, -1.0, float("nan"), float("inf")):
+        with pytest.raises(lut.LutnnError) as e:
+            lut.softpq_backward(layer, bad_t, dev(w.X), Z)
+        assert e.value.status == 2
+    with pytest.raises(lut.LutnnError) as e:
+        lut.softpq_backward(layer, 1.0, dev(w.X), Z, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == 2
+
+
+def test_autograd_wrapper_trains_centroids_and_temperature(lut):
+    """The module form: hard forward (INT8 table), soft backward.  Gradients match the oracle, and
+    a few steps of gradient descent on the centroids lower the soft loss the gradients belong to."""
+    from paper_2302_03213_amd.softpq import SoftPQLinear
+    N, C, K, V, M, t = 512, 16, 16, 4, 24, 1.0
+    w = wl.make_layer("t", N, C, K, V, M, "i8", seed=12)
+    target = w.X.astype(np.float64) @ w.W.astype(np.float64) + w.bias
+    layer = SoftPQLinear(dev(w.P), dev(w.W), dev(w.bias), temperature=t, table_dtype=lut.TABLE_I8)
+    X = dev(w.X).requires_grad_(True)
+    Y = layer(X)
+    # value of the forward pass = the hard INT8 operator
+    ref_layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8, bias=dev(w.bias))
+    np.testing.assert_array_equal(host(Y.detach()), host(lut.linear(ref_layer, dev(w.X))))
+    G = (Y.detach().double() - dev(target.astype(np.float32)).double()).float() / N  # dL/dY of 0.5*MSE
+    Y.backward(G)
+    dP_ref, dX_ref, dt_ref = osp.backward(w.P, w.W, w.X, t, host(G).astype(np.float64))
+    close(host(layer.centroids.grad), dP_ref, 5e-4)  # Z comes from torch's fp32 GEMM here
+    close(host(X.grad), dX_ref, 5e-4)
+    assert abs(layer.temperature.grad.item() - dt_ref) <= dt_bar(w, t, host(G).astype(np.float64)) * 2
+    np.testing.assert_allclose(host(layer.bias.grad), host(G).sum(axis=0), rtol=1e-4, atol=1e-6)
+
+    def soft_loss(P):
+        return 0.5 * ((osp.soft_forward(P, w.W, w.X, t, w.bias) - target) ** 2).sum() / N
+
+    before = soft_loss(w.P)
+    opt = torch.optim.SGD([layer.centroids], lr=0.5)
+    for _ in range(5):
+        opt.zero_grad()
+        Y = layer(dev(w.X))
+        Ysoft = osp.soft_forward(host(layer.centroids.detach()), w.W, w.X, t, w.bias)
+        Y.backward(dev(((Ysoft - target) / N).astype(np.float32)))  # gradient of the soft loss
+        opt.step()
+    after = soft_loss(host(layer.centroids.detach()))
+    assert after < before, (before, after)
