@@ -43,6 +43,80 @@ def workload_by_name(name):
     return [table[name](0)]
 
 
+def bench_softpq_backward(args, w, lut, cost, np, torch):
+    """One step = one lutnn_softpq_backward call (both kernels) on the layer's activations and a
+    seeded Z = dL/dY . W^T, everything resident in HBM."""
+    assert not w.conv, "softpq_backward is benchmarked on matrix workloads"
+    g = torch.Generator(device="cpu")
+    g.manual_seed(1)
+    layer = lut.LutLayer(torch.from_numpy(w.P).cuda(), None, lut.TABLE_F32, w.M)
+    X0 = torch.from_numpy(w.X).cuda()
+    Z0 = (torch.randn((w.N, w.D), generator=g, dtype=torch.float32) * 0.1).cuda()
+    Xs, Zs = [X0, X0.flip(0).contiguous()], [Z0, Z0.flip(0).contiguous()]
+    ws = torch.empty(max(lut.softpq_workspace_bytes(w.C, w.K, w.V, w.N), 4), dtype=torch.uint8, device="cuda")
+    temperature = 1.0
+
+    def step(i):
+        return lut.softpq_backward(layer, temperature, Xs[i & 1], Zs[i & 1], workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    acc = 0.0
+    for i in range(args.steps):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        out = step(i)
+        ev[1].record()
+        ev[1].synchronize()
+        acc += ev[0].elapsed_time(ev[1])
+    k_ms = acc / args.steps
+    lane_ops = cost.softpq_backward_lane_ops(w.N, w.C, w.K, w.V)
+    byts = cost.softpq_backward_bytes(w.N, w.C, w.V)
+    peak = cost.PEAK_VALU_F32_LANE_OPS_PER_S / 1e12
+    achieved = lane_ops / (k_ms * 1e-3) / 1e12
+    roofline = {"kernel": "softpq_backward (+ reduce)", "bound": "alu", "achieved": round(achieved, 3),
+                "peak": round(peak, 2), "unit": "T lane-ops/s", "frac": round(achieved / peak, 4),
+                "traffic": None, "kernel_ms": round(k_ms, 4), "ops_per_launch": lane_ops,
+                "hbm_GBps": round(byts / (k_ms * 1e-3) / 1e9, 1),
+                "hbm_frac": round(byts / (k_ms * 1e-3) / cost.PEAK_HBM_BYTES_PER_S, 4),
+                "note": "lane-ops of the backward formulas themselves (sums over rows not counted); peak = "
+                        "256 CUs x 64 lanes x 2.4 GHz"}
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        from oracle import softpq as osp
+        n = min(w.N, 128)
+        G = np.random.default_rng(0).standard_normal((n, w.M))
+        c0 = time.perf_counter()
+        dP, dX, dt = osp.backward(w.P, w.W, w.X[:n], temperature, G)
+        t_cpu = time.perf_counter() - c0
+        # cheap sanity link on the same rows (not a parity test): feed the GPU the Z of this G
+        Zs_ = torch.from_numpy((G @ w.W.astype(np.float64).T).astype(np.float32)).cuda()
+        got = lut.softpq_backward(layer, temperature, X0[:n].contiguous(), Zs_)
+        err = np.abs(got[0].cpu().numpy() - dP).max() / max(np.abs(dP).max(), 1e-30)
+        assert err < 1e-4, "GPU soft-PQ backward disagrees with the oracle (%.2e)" % err
+        cpu = {"value": round(n / t_cpu, 1), "unit": "rows/s", "cores": oracle.threads(), "kind": "oracle",
+               "sample": "first %d rows of %s, fp64 chain rule through the full table (numpy); %.2f s wall"
+                         % (n, w.name, t_cpu)}
+    out = {
+        "metric": "softpq_backward_rows_per_s", "value": round(w.N / sec, 1), "unit": "rows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s N=%d D=%d V=%d C=%d K=%d" % (w.name, w.N, w.D, w.V, w.C, w.K),
+                   "step": "lutnn_softpq_backward (dP, dX, dt from X and Z = dL/dY . W^T), inputs resident in "
+                           "HBM, two rotating X/Z buffer sets; the GEMM that forms Z is not part of it"},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,6 +131,9 @@ def main():
     ap.add_argument("--encoder", default="distance", choices=["distance", "tree"],
                     help="tree: the hash encoder of Sec. 2 / Sec. 7 (seeded random threshold trees with "
                          "log2 K levels) in place of the distance search of Eq. 2")
+    ap.add_argument("--op", default="linear", choices=["linear", "softpq_backward"],
+                    help="softpq_backward: time lutnn_softpq_backward (the training operator of Sec. 3) on "
+                         "the workload's first layer instead of the inference step")
     ap.add_argument("--cpu-sample-rows", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -80,6 +157,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     layers = workload_by_name(args.workload)
+    if args.op == "softpq_backward":
+        return bench_softpq_backward(args, layers[0], lut, cost, np, torch)
 
     # ---- device-side set-up (untimed): tables, two rotating activation / output buffer sets
     dev_layers, trees = [], {}

@@ -48,6 +48,20 @@ def encode_lane_ops(N, C, K, V):
     return N * C * K * (2 * V + 2)
 
 
+def softpq_backward_lane_ops(N, C, K, V):
+    """VALU lane-ops of the soft-PQ backward formulas (Eq. 5-6) per (row, codebook): per centroid
+    3V for the distance and dL/ds (subtract, two fused multiply-adds per element), 4V for the input
+    gradient and the centroid contribution (subtract, multiply, add, fused multiply-add), and about 10
+    for the softmax and its derivative (min, scale, exponential, sum, normalise, mean, difference,
+    product, temperature term, sign/scale).  The sums over rows are not counted."""
+    return N * C * K * (7 * V + 10)
+
+
+def softpq_backward_bytes(N, C, V, with_dx=True):
+    """Algorithmic HBM bytes: read X and Z once, write dX once (4 bytes each per element)."""
+    return N * C * V * 4 * (3 if with_dx else 2)
+
+
 def lookup_entries(N, C, M):
     """Table entries read and added by Eq. 4."""
     return N * C * M

@@ -25,7 +25,7 @@ def test_header_declares_the_documented_entry_points():
     names = declared_symbols()
     for must in ("lutnn_build_table", "lutnn_encode", "lutnn_lookup", "lutnn_linear"):
         assert must in names
-    assert len(names) >= 15
+    assert len(names) >= 17
 
 
 def test_library_exports_every_declared_symbol(lut):
@@ -226,6 +226,53 @@ def test_tree_descriptor_validation(lut):
     assert L.lutnn_encode_tree(ctypes.byref(ok), None, 0, 16, None, None) == 0  # empty batch
     assert L.lutnn_linear_tree(ctypes.byref(layer), ctypes.byref(ok), None, 0, 16, None, 8,
                                lut.VARIANT_AUTO, None, None) == 0
+
+
+def test_softpq_backward_validation_and_workspace_query(lut):
+    L, vp = lut.LIB, ctypes.c_void_p
+    X, Z, DP, DX, DT, WS = (vp(0x10000 * i) for i in range(1, 7))
+    # config 5: 64 column tiles of 16 codebooks, 32 chunks of 8 row tiles; one 64-float group per
+    # codebook and chunk, one temperature partial per workgroup
+    assert lut.softpq_workspace_bytes(1024, 16, 4, 16384) == (32 * 1024 * 64 + 32 * 64) * 4
+    assert lut.softpq_workspace_bytes(1024, 5, 4, 16384) == 0      # K not supported
+    assert lut.softpq_workspace_bytes(1024, 16, 5, 16384) == 0     # V not supported
+    assert lut.softpq_workspace_bytes(1024, 16, 4, 0) == 0
+    assert lut.softpq_workspace_bytes(4, 16, 9, 64) == (1 * 4 * 3 * 64 + 1) * 4  # ceil(9/4) = 3 groups
+    ok = _layer(lut)
+    f = ctypes.c_float
+    big = 1 << 20
+    cases = [
+        (L.lutnn_softpq_backward(None, f(1.0), X, 8, 16, Z, 16, DP, DX, 16, DT, WS, big, None), "LUTNN_E_NULL"),
+        (L.lutnn_softpq_backward(ctypes.byref(ok), f(0.0), X, 8, 16, Z, 16, DP, DX, 16, DT, WS, big, None),
+         "LUTNN_E_SHAPE"),
+        (L.lutnn_softpq_backward(ctypes.byref(ok), f(float("nan")), X, 8, 16, Z, 16, DP, DX, 16, DT, WS, big,
+                                 None), "LUTNN_E_SHAPE"),
+        (L.lutnn_softpq_backward(ctypes.byref(_layer(lut, K=5)), f(1.0), X, 8, 16, Z, 16, DP, DX, 16, DT, WS,
+                                 big, None), "LUTNN_E_UNSUPPORTED"),
+        (L.lutnn_softpq_backward(ctypes.byref(_layer(lut, V=5)), f(1.0), X, 8, 20, Z, 20, DP, DX, 20, DT, WS,
+                                 big, None), "LUTNN_E_UNSUPPORTED"),
+        (L.lutnn_softpq_backward(ctypes.byref(ok), f(1.0), X, 8, 16, Z, 16, None, DX, 16, DT, WS, big, None),
+         "LUTNN_E_NULL"),
+        (L.lutnn_softpq_backward(ctypes.byref(ok), f(1.0), None, 8, 16, Z, 16, DP, DX, 16, DT, WS, big, None),
+         "LUTNN_E_NULL"),
+        (L.lutnn_softpq_backward(ctypes.byref(ok), f(1.0), X, 8, 16, None, 16, DP, DX, 16, DT, WS, big, None),
+         "LUTNN_E_NULL"),
+        (L.lutnn_softpq_backward(ctypes.byref(ok), f(1.0), X, 8, 15, Z, 16, DP, DX, 16, DT, WS, big, None),
+         "LUTNN_E_SHAPE"),
+        (L.lutnn_softpq_backward(ctypes.byref(ok), f(1.0), X, 8, 16, Z, 15, DP, DX, 16, DT, WS, big, None),
+         "LUTNN_E_SHAPE"),
+        (L.lutnn_softpq_backward(ctypes.byref(ok), f(1.0), X, 8, 16, Z, 16, DP, DX, 15, DT, WS, big, None),
+         "LUTNN_E_SHAPE"),
+        (L.lutnn_softpq_backward(ctypes.byref(ok), f(1.0), X, 8, 16, Z, 16, DP, DX, 16, DT, None, big, None),
+         "LUTNN_E_NULL"),
+        (L.lutnn_softpq_backward(ctypes.byref(ok), f(1.0), X, 8, 16, Z, 16, DP, DX, 16, DT, WS, 16, None),
+         "LUTNN_E_SHAPE"),  # workspace too small
+        (L.lutnn_softpq_backward(ctypes.byref(ok), f(1.0), X, 8, 16, vp(0x20002), 16, DP, DX, 16, DT, WS, big,
+                                 None), "LUTNN_E_ALIGN"),
+    ]
+    for i, (code, want) in enumerate(cases):
+        name, detail = _status(lut, code)
+        assert name == want, "case %d: got %s (%s), wanted %s" % (i, name, detail, want)
 
 
 def test_auto_variant_rule(lut):
