@@ -40,20 +40,54 @@ constexpr int softpq_tile_codebooks(int V) {
     return enc_tile_codebooks(V) == 0 ? 0 : (enc_tile_codebooks(V) / 2 >= 4 ? enc_tile_codebooks(V) / 2 : 4);
 }
 
-// Sum over the 64 lanes of a wavefront of a 64-element vector per lane; lane l returns element l.
+typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+
+// lo + (lo of the partner lane) where this lane keeps the lower half, hi + (hi of the partner)
+// where it keeps the upper half; the partner is lane ^ 32 / lane ^ 16.  The row-swap instructions
+// exchange exactly the halves the two lanes have no use for, so no select is needed.
+__device__ __forceinline__ float exchange_add_32(float lo, float hi) {
+    const uint2v r = __builtin_amdgcn_permlane32_swap(__float_as_uint(lo), __float_as_uint(hi), false, false);
+    return __uint_as_float(r.x) + __uint_as_float(r.y);
+}
+__device__ __forceinline__ float exchange_add_16(float lo, float hi) {
+    const uint2v r = __builtin_amdgcn_permlane16_swap(__float_as_uint(lo), __float_as_uint(hi), false, false);
+    return __uint_as_float(r.x) + __uint_as_float(r.y);
+}
+// x + (x of lane ^ 8 | ^ 2 | ^ 1) as one DPP add; lane ^ 4 has no DPP form and goes through the
+// LDS crossbar (no memory access).
+template <int CTRL>
+__device__ __forceinline__ float add_dpp(float x) {
+    return x + __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(x), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float add_xor4(float x) {
+    return x + __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(x), 0x101f));  // swap, mask 4
+}
+
+// Sum over the 64 lanes of a wavefront of a 64-element vector per lane; lane l returns element l
+// (every step halves the vector: the lane whose bit m is clear keeps the lower half).
 __device__ __forceinline__ float reduce_scatter_64(float (&v)[64], int lane) {
 #pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
-        const bool upper = (lane & m) != 0;
+    for (int i = 0; i < 32; ++i) v[i] = exchange_add_32(v[i], v[i + 32]);
 #pragma unroll
-        for (int i = 0; i < m; ++i) {
-            const float lo = v[i], hi = v[i + m];
-            const float send = upper ? lo : hi;
-            const float keep = upper ? hi : lo;
-            v[i] = keep + __shfl_xor(send, m, 64);
-        }
+    for (int i = 0; i < 16; ++i) v[i] = exchange_add_16(v[i], v[i + 16]);
+    const bool up8 = (lane & 8) != 0, up4 = (lane & 4) != 0, up2 = (lane & 2) != 0, up1 = (lane & 1) != 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {  // row_ror:8 pairs lane with lane ^ 8 inside its row of 16
+        const float lo = add_dpp<0x128>(v[i]), hi = add_dpp<0x128>(v[i + 8]);
+        v[i] = up8 ? hi : lo;
     }
-    return v[0];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float lo = add_xor4(v[i]), hi = add_xor4(v[i + 4]);
+        v[i] = up4 ? hi : lo;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {  // quad_perm [2,3,0,1]
+        const float lo = add_dpp<0x4E>(v[i]), hi = add_dpp<0x4E>(v[i + 2]);
+        v[i] = up2 ? hi : lo;
+    }
+    const float lo = add_dpp<0xB1>(v[0]), hi = add_dpp<0xB1>(v[1]);  // quad_perm [1,0,3,2]
+    return up1 ? hi : lo;
 }
 
 template <int V, int K_T>
@@ -103,7 +137,8 @@ __global__ __launch_bounds__(kEncThreads) void softpq_backward_kernel(
         stage_x<V, CT>(Z, ldz, N, C * V, row0, c0, zs, vec4_z, tid);
         __syncthreads();
 
-#pragma unroll
+        // one codebook at a time (rolled: a codebook's K*V centroid values fill the scalar registers)
+#pragma unroll 1
         for (int j = 0; j < E::CPW; ++j) {
             const int cl = w * E::CPW + j;
             const int c = c0 + cl;  // wave-uniform
@@ -170,7 +205,10 @@ __global__ __launch_bounds__(kEncThreads) void softpq_backward_kernel(
                         for (int k = 0; k < K_T; ++k) contrib[k * S::VG + vv] = 0.f;
                     }
                 }
-                acc[j][g] += reduce_scatter_64(contrib, lane);
+                const float r = reduce_scatter_64(contrib, lane);
+#pragma unroll
+                for (int jj = 0; jj < E::CPW; ++jj)  // j is wave-uniform; acc keeps static indices
+                    if (jj == j) acc[jj][g] += r;
             }
         }
         __syncthreads();
@@ -230,8 +268,18 @@ __global__ __launch_bounds__(256) void softpq_reduce_kernel(const float* __restr
         const int k = (int)(i / V) % K_T;
         const int v = (int)(i % V);
         const size_t e = (size_t)c * S::GROUP_FLOATS + (v / S::VG) * 64 + k * S::VG + (v % S::VG);
+        // loads eight at a time (independent), added in ascending chunk order
         float sum = 0.f;
-        for (int ch = 0; ch < chunks; ++ch) sum += partial[(size_t)ch * C * S::GROUP_FLOATS + e];
+        const size_t stride = (size_t)C * S::GROUP_FLOATS;
+        int ch = 0;
+        for (; ch + 8 <= chunks; ch += 8) {
+            float t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = partial[(size_t)(ch + u) * stride + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) sum += t[u];
+        }
+        for (; ch < chunks; ++ch) sum += partial[(size_t)ch * stride + e];
         dP[i] = sum;
     }
     if (dt && blockIdx.x == 0 && threadIdx.x < 64) {
