@@ -41,6 +41,48 @@ inline bool enc_vec4_ok(const float* X, int64_t ldx, int C, int V) {
            ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
 }
 
+// The two halves of staging a tile with 16-byte loads (X 16-byte aligned, ldx and C*V multiples of
+// 4): a thread's ITER loads into registers, and those registers into LDS.  Kept apart so that a
+// kernel can issue the loads of its next tile before it works on the current one.
+template <int V, int CT>
+struct XTileRegs {
+    static constexpr int Q = EncTile<V, CT>::TW / 4;
+    static constexpr int ITER = (kEncRows * Q + kEncThreads - 1) / kEncThreads;
+    float4 val[ITER];
+};
+
+template <int V, int CT>
+__device__ __forceinline__ void load_x_tile(const float* __restrict__ X, int64_t ldx, int64_t N, int D,
+                                            int64_t row0, int c0, int tid, XTileRegs<V, CT>& t) {
+    using R = XTileRegs<V, CT>;
+#pragma unroll
+    for (int it = 0; it < R::ITER; ++it) {
+        const int i = tid + it * kEncThreads;
+        const int r = i / R::Q, col = (i % R::Q) * 4;
+        const int gcol = c0 * V + col;
+        t.val[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (i < kEncRows * R::Q && row0 + r < N && gcol < D)
+            t.val[it] = *reinterpret_cast<const float4*>(X + (row0 + r) * ldx + gcol);
+    }
+}
+
+template <int V, int CT>
+__device__ __forceinline__ void store_x_tile(float* __restrict__ xs, int tid, const XTileRegs<V, CT>& t) {
+    using E = EncTile<V, CT>;
+    using R = XTileRegs<V, CT>;
+#pragma unroll
+    for (int it = 0; it < R::ITER; ++it) {
+        const int i = tid + it * kEncThreads;
+        if (i < kEncRows * R::Q) {
+            float* dst = xs + (i / R::Q) * E::LS + (i % R::Q) * 4;
+            dst[0] = t.val[it].x;
+            dst[1] = t.val[it].y;
+            dst[2] = t.val[it].z;
+            dst[3] = t.val[it].w;
+        }
+    }
+}
+
 template <int V, int CT>
 __device__ __forceinline__ void stage_x(const float* __restrict__ X, int64_t ldx, int64_t N, int D,
                                         int64_t row0, int c0, float* __restrict__ xs, int vec4,
@@ -49,29 +91,9 @@ __device__ __forceinline__ void stage_x(const float* __restrict__ X, int64_t ldx
     // All of a thread's loads are issued before the first LDS write, so that their latencies
     // overlap instead of adding up (a workgroup has nothing else to do until the tile is staged).
     if (vec4) {
-        constexpr int Q = E::TW / 4;
-        constexpr int ITER = (kEncRows * Q + kEncThreads - 1) / kEncThreads;
-        float4 val[ITER];
-#pragma unroll
-        for (int it = 0; it < ITER; ++it) {
-            const int i = tid + it * kEncThreads;
-            const int r = i / Q, col = (i % Q) * 4;
-            const int gcol = c0 * V + col;
-            val[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (i < kEncRows * Q && row0 + r < N && gcol < D)
-                val[it] = *reinterpret_cast<const float4*>(X + (row0 + r) * ldx + gcol);
-        }
-#pragma unroll
-        for (int it = 0; it < ITER; ++it) {
-            const int i = tid + it * kEncThreads;
-            if (i < kEncRows * Q) {
-                float* dst = xs + (i / Q) * E::LS + (i % Q) * 4;
-                dst[0] = val[it].x;
-                dst[1] = val[it].y;
-                dst[2] = val[it].z;
-                dst[3] = val[it].w;
-            }
-        }
+        XTileRegs<V, CT> t;
+        load_x_tile<V, CT>(X, ldx, N, D, row0, c0, tid, t);
+        store_x_tile<V, CT>(xs, tid, t);
     } else {
         constexpr int TOTAL = kEncRows * E::TW;
         constexpr int BATCH = 8;

@@ -26,27 +26,14 @@
 namespace lutnn {
 namespace {
 
-// L_T: levels when known at compile time (0 = run-time value).
-template <int V, int CT, int L_T>
-__global__ __launch_bounds__(kEncThreads) void encode_tree_tile_kernel(
-    const float* __restrict__ X, int64_t ldx, const int32_t* __restrict__ split_dim,
-    const float* __restrict__ threshold, uint8_t* __restrict__ idx, int64_t N, int C, int levels_rt,
-    int vec4, int idx_dword_ok) {
-    using E = EncTile<V, CT>;
-    __shared__ float xs[E::kLdsFloats];
-    __shared__ uint32_t is[kEncRows * (CT / 4)];
-    extern __shared__ uint2 tp[];  // [CT][nodes]: .x = threshold bits, .y = split index
-
-    const int levels = L_T ? L_T : levels_rt;
-    const int nodes = (1 << levels) - 1;
-    const int col_tiles = (C + CT - 1) / CT;
-    const int64_t row0 = (int64_t)(blockIdx.x / col_tiles) * kEncRows;
-    const int c0 = (int)(blockIdx.x % col_tiles) * CT;
-    const int tid = threadIdx.x;
-
-    // the tile's codebooks are contiguous in both node arrays; a split index outside [0, V) is
-    // clamped so that no value outside the sub-vector is ever read.  Codebooks past C get
-    // (threshold 0, index 0) nodes: their walk is harmless and its result is dropped.
+// Stages the (threshold, split index) pairs of the tile's codebooks; they are contiguous in both
+// node arrays.  A split index outside [0, V) is clamped so that no value outside the sub-vector is
+// ever read.  Codebooks past C get (threshold 0, index 0) nodes: their walk is harmless and its
+// result is dropped.
+template <int V, int CT>
+__device__ __forceinline__ void stage_nodes(const int32_t* __restrict__ split_dim,
+                                            const float* __restrict__ threshold, int C, int c0, int nodes,
+                                            uint2* __restrict__ tp, int tid) {
     const int staged = std::min(CT, C - c0) * nodes;
     for (int i = tid; i < CT * nodes; i += kEncThreads) {
         uint2 node = make_uint2(0u, 0u);
@@ -57,13 +44,16 @@ __global__ __launch_bounds__(kEncThreads) void encode_tree_tile_kernel(
         }
         tp[i] = node;
     }
-    stage_x<V, CT>(X, ldx, N, C * V, row0, c0, xs, vec4, tid);
-    __syncthreads();
+}
 
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lane = tid & 63;
-    // The wavefront's CPW codebooks advance one level at a time: their walks are independent, so
-    // the LDS latency of one overlaps the others.
+// Wave `w` walks the trees of its CPW codebooks for row `lane` and leaves the row's index bytes in
+// `is`.  The codebooks advance one level at a time: their walks are independent, so the LDS
+// latency of one overlaps the others.  L_T: levels when known at compile time (0 = run-time).
+template <int V, int CT, int L_T>
+__device__ __forceinline__ void walk_trees(const float* __restrict__ xs, const uint2* __restrict__ tp,
+                                           int levels, int nodes, int C, int c0, int w, int lane,
+                                           uint32_t* __restrict__ is) {
+    using E = EncTile<V, CT>;
     int node[E::CPW];
 #pragma unroll
     for (int j = 0; j < E::CPW; ++j) node[j] = 0;
@@ -94,8 +84,13 @@ __global__ __launch_bounds__(kEncThreads) void encode_tree_tile_kernel(
         packed[j / 4] |= leaf << (8 * (j % 4));
     }
     store_index_bytes<V, CT>(is + lane * (CT / 4), w * E::CPW, packed);
-    __syncthreads();
+}
 
+// Each row's CT index bytes are contiguous in idx[N][C]: out as row segments.
+template <int CT>
+__device__ __forceinline__ void write_index_rows(const uint32_t* __restrict__ is, uint8_t* __restrict__ idx,
+                                                 int64_t N, int C, int64_t row0, int c0, int idx_dword_ok,
+                                                 int tid) {
     for (int i = tid; i < kEncRows * (CT / 4); i += kEncThreads) {
         const int r = i / (CT / 4), j = i % (CT / 4);
         const int c = c0 + 4 * j;
@@ -110,6 +105,31 @@ __global__ __launch_bounds__(kEncThreads) void encode_tree_tile_kernel(
                 if (c + b < C) dst[b] = (uint8_t)(wv >> (8 * b));
         }
     }
+}
+
+template <int V, int CT, int L_T>
+__global__ __launch_bounds__(kEncThreads) void encode_tree_tile_kernel(
+    const float* __restrict__ X, int64_t ldx, const int32_t* __restrict__ split_dim,
+    const float* __restrict__ threshold, uint8_t* __restrict__ idx, int64_t N, int C, int levels_rt,
+    int vec4, int idx_dword_ok) {
+    using E = EncTile<V, CT>;
+    __shared__ float xs[E::kLdsFloats];
+    __shared__ uint32_t is[kEncRows * (CT / 4)];
+    extern __shared__ uint2 tp[];  // [CT][nodes]: .x = threshold bits, .y = split index
+
+    const int levels = L_T ? L_T : levels_rt;
+    const int nodes = (1 << levels) - 1;
+    const int col_tiles = (C + CT - 1) / CT;
+    const int64_t row0 = (int64_t)(blockIdx.x / col_tiles) * kEncRows;
+    const int c0 = (int)(blockIdx.x % col_tiles) * CT;
+    const int tid = threadIdx.x;
+
+    stage_nodes<V, CT>(split_dim, threshold, C, c0, nodes, tp, tid);
+    stage_x<V, CT>(X, ldx, N, C * V, row0, c0, xs, vec4, tid);
+    __syncthreads();
+    walk_trees<V, CT, L_T>(xs, tp, levels, nodes, C, c0, __builtin_amdgcn_readfirstlane(tid >> 6), tid & 63, is);
+    __syncthreads();
+    write_index_rows<CT>(is, idx, N, C, row0, c0, idx_dword_ok, tid);
 }
 
 // Any V: one thread per sub-vector, everything from global memory.
@@ -144,7 +164,8 @@ hipError_t launch_tree_ct(const int32_t* split_dim, const float* threshold, int 
                      ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
     const int idx_dword_ok = (C % 4 == 0) && ((reinterpret_cast<uintptr_t>(idx) & 3) == 0);
     const size_t node_bytes = (size_t)CT * ((1u << levels) - 1) * sizeof(uint2);
-    dim3 grid((unsigned)blocks), block(kEncThreads);
+    dim3 block(kEncThreads);
+    dim3 grid((unsigned)blocks);
     if (levels == 4)
         hipLaunchKernelGGL((encode_tree_tile_kernel<V, CT, 4>), grid, block, node_bytes, s, X, ldx,
                            split_dim, threshold, idx, N, C, levels, vec4, idx_dword_ok);

@@ -42,6 +42,9 @@ TREE_SHAPES = [
     (90, 7, 5, 4), (33, 4, 7, 8), (41, 3, 12, 3),
     # grids of 1024 workgroups and more take the full tile width
     (4160, 600, 4, 4), (4100, 512, 4, 8), (2100, 320, 9, 4),
+    # thousands of tiles: ragged rows and codebooks, byte-wise index stores, deep trees on narrow
+    # tiles, V = 9
+    (8250, 1030, 4, 4), (8250, 1030, 4, 8), (16500, 300, 9, 4), (5000, 2048, 2, 5),
 ]
 
 
