@@ -1,0 +1,139 @@
+"""GPU parity of combinations of the library's options that the per-feature tests do not pair up
+(convolution input with fp32 / INT4 tables, hash encoder with INT4 tables), and of the entry points
+under HIP graph capture.  Same bars as tests/test_gpu_parity.py."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import lutnn_workloads as wl
+import oracle
+from gpu_util import dev, host, near_tie_report
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lut():
+    import paper_2302_03213_amd as lut_mod
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return lut_mod
+
+
+@pytest.fixture(autouse=True)
+def announce(request):
+    print("\n[case] %s" % request.node.nodeid, file=sys.stderr, flush=True)
+    yield
+
+
+def unfold_rows(inp, kernel, stride, pad):
+    cols = torch.nn.functional.unfold(torch.from_numpy(inp), kernel, padding=pad, stride=stride)
+    return cols.permute(0, 2, 1).reshape(-1, cols.shape[1]).contiguous().numpy()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "i4"])
+def test_conv2d_with_fp32_and_int4_tables(lut, dtype):
+    B, Cin, H, W, M = 2, 16, 14, 12, 40
+    g = np.random.default_rng(3)
+    inp = g.standard_normal((B, Cin, H, W)).astype(np.float32)
+    w = wl.make_layer("t", 1, Cin, 16, 9, M, "f32", seed=9)
+    X = unfold_rows(inp, (3, 3), (1, 1), (1, 1))
+    idx_ref = oracle.encode(w.P, X)
+    Tf = oracle.build_table_f32(w.P, w.W)
+    if dtype == "f32":
+        ref = oracle.lookup_f32(Tf, idx_ref, w.bias)
+        layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_F32, bias=dev(w.bias))
+    else:
+        q, s = oracle.quantize(Tf, 4)
+        ref = oracle.lookup_i8(q, s, idx_ref, w.bias)
+        layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I4, bias=dev(w.bias))
+    idx = host(lut.encode_conv2d(layer, dev(inp), 3, 1, 1))
+    w.X = X
+    assert near_tie_report(w, idx, idx_ref) <= 1
+    clean = (idx == idx_ref).all(axis=1)
+    variants = ["auto", "lds"] if dtype == "f32" else ["auto", "lds", "mfma"]
+    for v in variants:
+        got = host(lut.conv2d(layer, dev(inp), 3, 1, 1, v))
+        if dtype == "f32":
+            np.testing.assert_allclose(got[clean], ref[clean], rtol=1e-5, atol=1e-4, err_msg=v)
+        else:
+            np.testing.assert_array_equal(got[clean], ref[clean], err_msg=v)
+
+
+def test_linear_tree_with_an_int4_table(lut):
+    N, C, V, levels, M = 700, 64, 4, 4, 264
+    w = wl.make_layer("t", N, C, 16, V, M, "i8", seed=31)
+    dims, thr = wl.random_tree(C, V, levels, seed=31)
+    q, s = oracle.quantize(oracle.build_table_f32(w.P, w.W), 4)
+    ref = oracle.lookup_i8(q, s, oracle.encode_tree(dims, thr, w.X, V), w.bias)
+    layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I4, bias=dev(w.bias))
+    tree = lut.LutTree(dev(dims), dev(thr), V)
+    for v in ("auto", "lds", "mfma", "smfmac"):
+        np.testing.assert_array_equal(host(lut.linear_tree(layer, tree, dev(w.X), v)), ref, err_msg=v)
+
+
+@pytest.mark.parametrize("variant", ["auto", "smfmac", "mfma", "lds", "fused"])
+def test_linear_replayed_from_a_hip_graph(lut, variant):
+    """The entry points allocate nothing, clear nothing with memset nodes and never synchronise, so a
+    captured lutnn_linear can be replayed; every replay, with fresh inputs written into the captured
+    buffers and eager work in between, must equal the eager result."""
+    N, C, K, V, M = 700, 64, 16, 4, 320
+    w = wl.make_layer("t", N, C, K, V, M, "i8", seed=17)
+    layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8, bias=dev(w.bias))
+    X = dev(w.X).clone()
+    Y = torch.empty((N, M), dtype=torch.float32, device="cuda")
+    ws = torch.empty((N, C), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):  # warm-up on the capture stream, as torch asks
+        lut.linear(layer, X, variant, out=Y, idx_workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lut.linear(layer, X, variant, out=Y, idx_workspace=ws)
+    rng = np.random.default_rng(5)
+    for rep in range(4):
+        Xn = rng.standard_normal((N, C * V)).astype(np.float32)
+        X.copy_(dev(Xn))
+        Y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = host(Y)
+        eager = host(lut.linear(layer, dev(Xn), variant))
+        np.testing.assert_array_equal(got, eager, err_msg="replay %d" % rep)
+        float((dev(Xn) * 2).sum())  # unrelated eager work and a synchronisation between replays
+
+
+def test_softpq_backward_and_tree_encode_replayed_from_a_hip_graph(lut):
+    N, C, K, V = 1500, 32, 16, 4
+    w = wl.make_layer("t", N, C, K, V, 8, "f32", seed=23)
+    dims, thr = wl.random_tree(C, V, 4, seed=23)
+    tree = lut.LutTree(dev(dims), dev(thr), V)
+    layer = lut.LutLayer(dev(w.P), None, lut.TABLE_F32, 8)
+    X = dev(w.X).clone()
+    Z = dev(np.random.default_rng(2).standard_normal((N, C * V)).astype(np.float32))
+    ws = torch.empty(lut.softpq_workspace_bytes(C, K, V, N), dtype=torch.uint8, device="cuda")
+    idx = torch.empty((N, C), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        lut.softpq_backward(layer, 1.0, X, Z, workspace=ws)
+        lut.encode_tree(tree, X, out=idx)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        dP, dX, dt = lut.softpq_backward(layer, 1.0, X, Z, workspace=ws)
+        lut.encode_tree(tree, X, out=idx)
+    rng = np.random.default_rng(6)
+    for rep in range(3):
+        Xn = rng.standard_normal((N, C * V)).astype(np.float32)
+        X.copy_(dev(Xn))
+        graph.replay()
+        torch.cuda.synchronize()
+        e = lut.softpq_backward(layer, 1.0, dev(Xn), Z)
+        for a, b in zip((dP, dX, dt), e):
+            np.testing.assert_array_equal(host(a), host(b), err_msg="replay %d" % rep)
+        np.testing.assert_array_equal(host(idx), oracle.encode_tree(dims, thr, Xn, V))
