@@ -61,7 +61,10 @@ typedef enum {
     LUTNN_VARIANT_FUSED = 3, /* lutnn_linear only: one kernel, indices never leave the chip          */
     LUTNN_VARIANT_SMFMAC = 4 /* as MFMA, on the 2:4 structured-sparse matrix instructions: a one-hot
                                 slice is 2:4 sparse by construction, so the result is identical at
-                                twice the matrix rate.  Needs C % 32 == 0, 16-byte aligned idx      */
+                                twice the matrix rate.  Needs C % 32 == 0, 16-byte aligned idx.
+                                The environment variable LUTNN_SMFMAC_TILE_ROWS (128, 256, 384 or
+                                512), read at every call, pins the rows per workgroup tile that the
+                                library otherwise prices itself: a tuning knob, results are the same */
 } lutnn_variant;
 
 /*

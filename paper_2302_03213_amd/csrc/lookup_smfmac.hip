@@ -48,6 +48,7 @@
 // one, so there is no pipeline fill per tile.
 //
 // Needs C % 32 == 0 and a 16-byte aligned idx.
+#include <cstdlib>
 #include <type_traits>
 
 #include "lutnn_kernels.h"
@@ -79,7 +80,7 @@ __device__ __forceinline__ void dma16_at(uint32_t lds_base, const void* sbase, u
 }
 
 // TM = 32-row blocks per wavefront: the workgroup tile is 128*TM rows x 128 columns.  TM = 4 is
-// the efficient shape; 2 and 1 exist so that problems with few rows still spread over the chip.
+// the efficient shape; 3, 2 and 1 exist so that problems with few rows still spread over the chip.
 template <int TM>
 __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const uint4* __restrict__ packed, const float* __restrict__ scale, const float* __restrict__ bias,
@@ -249,10 +250,8 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     auto load_idx_all = [&]() {
         load_idx(I0{});
         if constexpr (TM > 1) load_idx(I1{});
-        if constexpr (TM > 2) {
-            load_idx(I2{});
-            load_idx(I3{});
-        }
+        if constexpr (TM > 2) load_idx(I2{});
+        if constexpr (TM > 3) load_idx(I3{});
         ip += 32;
     };
     load_idx_all();
@@ -329,6 +328,8 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
                 if (j + 1 < KSTEPS) {
                     if constexpr (S == 16) {
                         if ((q & 1) == 0) load_b_operand((j + 1) & 1, SB, j + 1, q >> 1);
+                    } else if constexpr (S == 12) {
+                        if (q % 3 != 2) load_b_operand((j + 1) & 1, SB, j + 1, q - q / 3);
                     } else if constexpr (S == 8) {
                         load_b_operand((j + 1) & 1, SB, j + 1, q);
                     } else {
@@ -392,7 +393,10 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
                         if (q == 4) load_idx(I0{});
                         if (q == 6) load_idx(I1{});
                     }
-                    if constexpr (TM > 2) {
+                    if constexpr (TM == 3) {
+                        if (q == 8) load_idx(I2{});
+                    }
+                    if constexpr (TM == 4) {
                         if (q == 12) load_idx(I2{});
                         if (q == 14) load_idx(I3{});
                     }
@@ -487,15 +491,29 @@ hipError_t launch_lookup_smfmac_i8(const int8_t* packed, const float* scale, con
     if (!smfmac_supported(C, K, idx)) return hipErrorInvalidValue;
     // Tile height.  512 rows amortise the table slab best, but the tiles have to cover the chip:
     // price each height as (rounds of 256 workgroups) x (measured time of one tile relative to
-    // the 512-row tile: 0.56 for 256 rows, 0.42 for 128 - the slab traffic does not shrink).
+    // the 512-row tile: 0.8 for 384 rows, 0.56 for 256, 0.42 for 128 - the slab traffic does not
+    // shrink).
     const int64_t col_tiles = (M + BN - 1) / BN;
     auto cost = [&](int64_t bm, double rel) {
         const int64_t tiles = ((N + bm - 1) / bm) * col_tiles;
         return (double)((tiles + kComputeUnits - 1) / kComputeUnits) * rel;
     };
-    const double c4 = cost(512, 1.0), c2 = cost(256, 0.56), c1 = cost(128, 0.42);
-    if (c4 <= c2 && c4 <= c1) return launch_tm<4>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
-    if (c2 <= c1) return launch_tm<2>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
+    // LUTNN_SMFMAC_TILE_ROWS = 128 | 256 | 384 | 512 pins the height (tuning sweeps, and tests that
+    // must reach every instance whatever the prices below say); anything else is ignored.
+    if (const char* e = std::getenv("LUTNN_SMFMAC_TILE_ROWS")) {
+        switch (std::atoi(e)) {
+            case 512: return launch_tm<4>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
+            case 384: return launch_tm<3>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
+            case 256: return launch_tm<2>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
+            case 128: return launch_tm<1>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
+            default: break;
+        }
+    }
+    const double c4 = cost(512, 1.0), c3 = cost(384, 0.8), c2 = cost(256, 0.56), c1 = cost(128, 0.42);
+    const double best = std::min(std::min(c4, c3), std::min(c2, c1));
+    if (c4 == best) return launch_tm<4>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
+    if (c3 == best) return launch_tm<3>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
+    if (c2 == best) return launch_tm<2>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
     return launch_tm<1>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
 }
 

@@ -155,11 +155,22 @@ SMFMAC_SHAPES = [
     # N, C, K, M   (C % 32 == 0)
     (1, 32, 16, 1), (130, 64, 16, 64), (513, 96, 16, 250), (1025, 384, 16, 513), (700, 32, 7, 100),
     (512, 160, 16, 128), (300, 128, 1, 40), (2000, 224, 16, 130),
-    # tile heights: the shapes above take 128-row tiles; 512 rows here ...
-    (2100, 64, 16, 3968),
-    # ... and 256 rows, several tiles per workgroup, here
-    (4700, 64, 16, 4096),
+    # larger grids, where the launcher prices taller tiles (every height is also pinned below)
+    (2100, 64, 16, 3968), (4700, 64, 16, 4096), (2100, 64, 16, 6400), (1000, 64, 16, 8192),
 ]
+
+
+@pytest.mark.parametrize("rows", [128, 256, 384, 512])
+@pytest.mark.parametrize("N,C,K,M", [(1500, 96, 16, 300), (2100, 64, 16, 3968), (4700, 64, 16, 4096)])
+def test_lookup_smfmac_every_tile_height(lut, monkeypatch, rows, N, C, K, M):
+    """Each tile height on ragged rows / columns, one tile per workgroup (C % 64 != 0 or few tiles)
+    and several (the last shape), pinned through the library's tuning variable."""
+    monkeypatch.setenv("LUTNN_SMFMAC_TILE_ROWS", str(rows))
+    w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=N + rows)
+    ol = OracleLayer(w)
+    idx = wl.random_indices(N, C, K, seed=N + rows)
+    layer = device_layer_from_oracle(lut, ol)
+    np.testing.assert_array_equal(host(lut.lookup(layer, dev(idx), "smfmac")), ol.lookup(idx))
 
 
 @pytest.mark.parametrize("N,C,K,M", SMFMAC_SHAPES)
