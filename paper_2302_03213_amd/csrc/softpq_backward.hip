@@ -124,6 +124,7 @@ __global__ __launch_bounds__(kEncThreads) void softpq_backward_kernel(
     const int64_t tile_begin = (int64_t)chunk * tiles_per_chunk;
     const int64_t tile_end = std::min<int64_t>(tile_begin + tiles_per_chunk, row_tiles);
 
+    const float inv_t_log2e = inv_t * 1.44269504f;
     float acc[E::CPW][S::NG];
 #pragma unroll
     for (int j = 0; j < E::CPW; ++j)
@@ -167,7 +168,7 @@ __global__ __launch_bounds__(kEncThreads) void softpq_backward_kernel(
             float s[K_T], ssum = 0.f;
 #pragma unroll
             for (int k = 0; k < K_T; ++k) {
-                s[k] = __expf((dmin - d[k]) * inv_t);
+                s[k] = __builtin_amdgcn_exp2f((dmin - d[k]) * inv_t_log2e);  // exp((dmin - d_k) / t)
                 ssum += s[k];
             }
             const float rs = 1.0f / ssum;
