@@ -137,3 +137,49 @@ def test_softpq_backward_and_tree_encode_replayed_from_a_hip_graph(lut):
         for a, b in zip((dP, dX, dt), e):
             np.testing.assert_array_equal(host(a), host(b), err_msg="replay %d" % rep)
         np.testing.assert_array_equal(host(idx), oracle.encode_tree(dims, thr, Xn, V))
+
+
+def test_four_million_rows_cross_the_32_bit_byte_offsets(lut):
+    """N = 2^22 + 77: X, Y and dX are larger than 2 GiB each, so every row offset the kernels form
+    must be 64-bit.  The oracle checks the first and the last rows and a sample in between."""
+    N, C, K, V, M = (1 << 22) + 77, 32, 16, 4, 128
+    w = wl.make_layer("t", 1, C, K, V, M, "i8", seed=41)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(41)
+    X = torch.randn((N, C * V), generator=g, dtype=torch.float32)
+    Xd = X.cuda()
+    layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8, bias=dev(w.bias))
+    rows = np.unique(np.concatenate([np.arange(64), np.arange(N - 600, N),
+                                     np.random.default_rng(1).integers(0, N, 2000),
+                                     np.arange((1 << 21) - 32, (1 << 21) + 32)]))
+    Xs = X.numpy()[rows]
+    idx_ref = oracle.encode(w.P, Xs)
+    Tf = oracle.build_table_f32(w.P, w.W)
+    q, s = oracle.quantize_i8(Tf)
+    ref = oracle.lookup_i8(q, s, idx_ref, w.bias)
+    idx = lut.encode(layer, Xd)
+    w.X = Xs
+    got_idx = host(idx[torch.from_numpy(rows).cuda()])
+    assert near_tie_report(w, got_idx, idx_ref) <= 1
+    clean = (got_idx == idx_ref).all(axis=1)
+    rows_d = torch.from_numpy(rows).cuda()
+    for v in ("smfmac", "mfma", "lds"):
+        Y = lut.lookup(layer, idx, v)
+        np.testing.assert_array_equal(host(Y[rows_d])[clean], ref[clean], err_msg=v)
+        del Y
+    dims, thr = wl.random_tree(C, V, 4, seed=41)
+    tidx = lut.encode_tree(lut.LutTree(dev(dims), dev(thr), V), Xd)
+    np.testing.assert_array_equal(host(tidx[rows_d]), oracle.encode_tree(dims, thr, Xs, V))
+    del tidx, idx
+    # soft-PQ: dX rows are per-row quantities; compare the sampled ones with the fp64 oracle
+    from oracle import softpq as osp
+    G = np.random.default_rng(2).standard_normal((len(rows), M))
+    Zs = (G @ w.W.astype(np.float64).T).astype(np.float32)
+    Zd = torch.zeros((N, C * V), dtype=torch.float32, device="cuda")
+    Zd[rows_d] = dev(Zs)
+    flayer = lut.LutLayer(dev(w.P), None, lut.TABLE_F32, M)
+    dP, dX, dt = lut.softpq_backward(flayer, 1.0, Xd, Zd)
+    dP_ref, dX_ref, dt_ref = osp.backward(w.P, w.W, Xs, 1.0, G)  # rows with Z = 0 contribute nothing
+    got = host(dX[rows_d])
+    assert np.abs(got - dX_ref).max() <= 5e-5 * np.abs(dX_ref).max()
+    assert np.abs(host(dP) - dP_ref).max() <= 5e-5 * np.abs(dP_ref).max()
