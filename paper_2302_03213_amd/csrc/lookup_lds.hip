@@ -508,6 +508,8 @@ bool gather_preferred(const void* T, int table_kind, int C, int M, int64_t N) {
 hipError_t launch_lookup_lds_i8(const int8_t* T, const float* scale, const float* bias, int C, int K,
                                 int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,
                                 hipStream_t s) {
+    if (rows_kernel_preferred(N, M, K, false))
+        return launch_lookup_rows_i8(T, 8, scale, bias, C, K, M, idx, N, Y, ldy, s);
     const int per_codebook = K * kColsI8;  // LDS bytes per staged codebook
     if (4 * per_codebook > kLdsBudget) {
         const int64_t blocks = (N * (int64_t)M + kThreads - 1) / kThreads;
@@ -538,6 +540,8 @@ hipError_t launch_lookup_lds_i8(const int8_t* T, const float* scale, const float
 hipError_t launch_lookup_lds_i4(const uint8_t* T, const float* scale, const float* bias, int C, int K,
                                 int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,
                                 hipStream_t s) {
+    if (rows_kernel_preferred(N, M, K, false))
+        return launch_lookup_rows_i8(T, 4, scale, bias, C, K, M, idx, N, Y, ldy, s);
     const int per_codebook = K * kColsI8;  // LDS bytes per staged codebook (entries widened to bytes)
     if (4 * per_codebook > kLdsBudget) {
         const int64_t blocks = (N * (int64_t)M + kThreads - 1) / kThreads;
@@ -592,6 +596,7 @@ hipError_t launch_lookup_lds_i4(const uint8_t* T, const float* scale, const floa
 
 hipError_t launch_lookup_lds_f32(const float* T, const float* bias, int C, int K, int M,
                                  const uint8_t* idx, int64_t N, float* Y, int64_t ldy, hipStream_t s) {
+    if (rows_kernel_preferred(N, M, K, true)) return launch_lookup_rows_f32(T, bias, C, K, M, idx, N, Y, ldy, s);
     const int per_codebook = K * kColsF32 * 4;
     if (4 * per_codebook > kLdsBudget) {
         const int64_t blocks = (N * (int64_t)M + kThreads - 1) / kThreads;

@@ -61,6 +61,15 @@ hipError_t launch_lookup_lds_f32(const float* T, const float* bias, int C, int K
 hipError_t launch_lookup_lds_i4(const uint8_t* T, const float* scale, const float* bias, int C, int K,
                                 int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,
                                 hipStream_t s);
+// Eq. 4, gather variant with lane = row (256 rows per workgroup share the staged slabs): the shape
+// for many rows.  bits = 8: T is [C][K][M] int8; bits = 4: [C][K][ceil(M/2)] nibble pairs.
+bool rows_kernel_preferred(int64_t N, int M, int K, bool f32);
+hipError_t launch_lookup_rows_i8(const void* T, int bits, const float* scale, const float* bias, int C,
+                                 int K, int M, const uint8_t* idx, int64_t N, float* Y, int64_t ldy,
+                                 hipStream_t s);
+hipError_t launch_lookup_rows_f32(const float* T, const float* bias, int C, int K, int M,
+                                  const uint8_t* idx, int64_t N, float* Y, int64_t ldy, hipStream_t s);
+
 // table_kind: 0 fp32, 1 int8, 2 int4 (nibble pairs)
 bool gather_preferred(const void* T, int table_kind, int C, int M, int64_t N);
 

@@ -226,6 +226,44 @@ def test_lookup_f32_within_tolerance(lut, N, C, K, M):
         assert_f32_close(got, oracle.lookup_f32(ol.Tf, idx, w.bias if with_bias else None))
 
 
+MANY_ROWS_SHAPES = [
+    # N, C, K, M: enough rows and tiles for the lane = row gather kernels (256 rows per workgroup)
+    (2100, 33, 16, 8200), (4200, 64, 16, 4096), (2100, 12, 40, 8200), (1100, 5, 200, 16400),
+    (2500, 7, 1, 8192), (2100, 18, 16, 8195),
+]
+
+
+@pytest.mark.parametrize("N,C,K,M", MANY_ROWS_SHAPES)
+def test_lookup_many_rows_gather_i8_i4_f32(lut, N, C, K, M):
+    idx = wl.random_indices(N, C, K, seed=N + C)
+    # INT8, full-range table, strided output with a guard band
+    w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=N + M)
+    ol = OracleLayer(w)
+    ol.q = wl.random_table_i8(C, K, M, seed=C + K)
+    ol.s = np.float32(0.031)
+    layer = device_layer_from_oracle(lut, ol)
+    ref = ol.lookup(idx)
+    Ybig = torch.full((N, M + 4), -7.0, dtype=torch.float32, device="cuda")
+    lut.lookup(layer, dev(idx), "lds", out=Ybig[:, :M])
+    np.testing.assert_array_equal(host(Ybig[:, :M]), ref)
+    assert (host(Ybig[:, M:]) == -7.0).all()
+    # index matrix at an odd address
+    raw = torch.zeros(N * C + 1, dtype=torch.uint8, device="cuda")
+    raw[1:] = dev(idx).flatten()
+    np.testing.assert_array_equal(host(lut.lookup(layer, raw[1:].view(N, C), "lds")), ref)
+    # INT4 (same codes, clamped to the 4-bit range, nibble storage)
+    q4 = np.clip(ol.q, -7, 7).astype(np.int8)
+    l4 = lut.LutLayer(dev(w.P), dev(oracle.pack_nibbles(q4)), lut.TABLE_I4, M,
+                      scale=dev(np.array([ol.s], np.float32)), bias=dev(w.bias))
+    np.testing.assert_array_equal(host(lut.lookup(l4, dev(idx), "lds")),
+                                  oracle.lookup_i8(q4, ol.s, idx, w.bias))
+    # fp32
+    wf = wl.make_layer("t", 1, C, K, 2, M, "f32", seed=N + M + 1)
+    olf = OracleLayer(wf)
+    lf = device_layer_from_oracle(lut, olf)
+    assert_f32_close(host(lut.lookup(lf, dev(idx), "lds")), oracle.lookup_f32(olf.Tf, idx, wf.bias))
+
+
 def test_lookup_index_matrix_at_odd_address(lut):
     # idx only byte aligned: the dword / 16-byte index fetches must not be used
     w = wl.make_layer("t", 1, 32, 16, 2, 128, "i8", seed=35)
