@@ -194,3 +194,37 @@ def test_autograd_wrapper_trains_centroids_and_temperature(lut):
         opt.step()
     after = soft_loss(host(layer.centroids.detach()))
     assert after < before, (before, after)
+
+
+def test_autograd_conv2d_module_matches_oracle_on_unfolded_rows(lut):
+    """SoftPQConv2d: value = the hard convolution read from NCHW; gradients = the oracle's on the
+    im2col rows, the input gradient folded back onto the image (fold is unfold's adjoint)."""
+    from paper_2302_03213_amd.softpq import SoftPQConv2d
+    B, Cin, H, W, M, K, t = 2, 8, 11, 9, 12, 16, 1.3
+    kernel, stride, pad = (3, 3), (2, 1), (1, 1)
+    rng = np.random.default_rng(31)
+    inp = rng.standard_normal((B, Cin, H, W)).astype(np.float32)
+    w = wl.make_layer("t", 1, Cin, K, 9, M, "i8", seed=31)  # V = 9: one channel's patch per sub-vector
+    cols = torch.nn.functional.unfold(torch.from_numpy(inp), kernel, padding=pad, stride=stride)
+    X = cols.permute(0, 2, 1).reshape(-1, cols.shape[1]).contiguous().numpy()
+    Ho = (H + 2 * pad[0] - kernel[0]) // stride[0] + 1
+    Wo = (W + 2 * pad[1] - kernel[1]) // stride[1] + 1
+    mod = SoftPQConv2d(dev(w.P), dev(w.W), kernel, stride, pad, bias=dev(w.bias), temperature=t,
+                       table_dtype=lut.TABLE_I8)
+    x = dev(inp).requires_grad_(True)
+    Y = mod(x)
+    assert Y.shape == (B, M, Ho, Wo)
+    ref_layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8, bias=dev(w.bias))
+    hard = lut.conv2d(ref_layer, dev(inp), kernel, stride, pad).view(B, Ho, Wo, M).permute(0, 3, 1, 2)
+    np.testing.assert_array_equal(host(Y.detach()), host(hard))
+    G = rng.standard_normal((B, M, Ho, Wo)).astype(np.float32)
+    Y.backward(dev(G))
+    G2 = np.ascontiguousarray(G.transpose(0, 2, 3, 1).reshape(-1, M)).astype(np.float64)
+    dP_ref, dX_ref, dt_ref = osp.backward(w.P, w.W, X, t, G2)
+    dcols = torch.from_numpy(dX_ref).view(B, Ho * Wo, -1).permute(0, 2, 1)
+    dinp_ref = torch.nn.functional.fold(dcols, (H, W), kernel, padding=pad, stride=stride).numpy()
+    close(host(mod.centroids.grad), dP_ref, 5e-4)  # Z comes from torch's fp32 GEMM here
+    close(host(x.grad), dinp_ref, 5e-4)
+    w.X = X
+    assert abs(mod.temperature.grad.item() - dt_ref) <= 2 * dt_bar(w, t, G2)
+    np.testing.assert_allclose(host(mod.bias.grad), G2.sum(axis=0), rtol=1e-4, atol=1e-5)
