@@ -84,7 +84,23 @@ __global__ __launch_bounds__(kRowsThreads) void lookup_rows_i8_kernel(
             const int c = c0 + cl;
             const int m = n0 + ch * 16;
             uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (c < C && BITS == 4) {
+            if (c < C && BITS == 4 && table_vec16 && m + 16 <= M) {
+                // eight bytes = sixteen entries: split the nibbles, interleave them back into column
+                // order, and sign-extend each 4-bit value in its byte
+                const uint2 w2 = *reinterpret_cast<const uint2*>(
+                    reinterpret_cast<const uint8_t*>(T) + ((size_t)c * K + k) * (size_t)(M / 2) + m / 2);
+                const uint32_t ws[2] = {w2.x, w2.y};
+                uint32_t t[4];
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const uint32_t lo = ws[q] & 0x0f0f0f0fu, hi = (ws[q] >> 4) & 0x0f0f0f0fu;
+                    const uint32_t a = __builtin_amdgcn_perm(hi, lo, 0x05010400u);  // lo0 hi0 lo1 hi1
+                    const uint32_t b = __builtin_amdgcn_perm(hi, lo, 0x07030602u);  // lo2 hi2 lo3 hi3
+                    t[2 * q + 0] = a | (((a >> 3) & 0x01010101u) * 0xf0u);
+                    t[2 * q + 1] = b | (((b >> 3) & 0x01010101u) * 0xf0u);
+                }
+                v = make_uint4(t[0], t[1], t[2], t[3]);
+            } else if (c < C && BITS == 4) {
                 const uint8_t* src =
                     reinterpret_cast<const uint8_t*>(T) + ((size_t)c * K + k) * ((M + 1) / 2) + m / 2;
                 uint32_t t[4] = {0u, 0u, 0u, 0u};
@@ -273,7 +289,9 @@ hipError_t launch_lookup_rows_i8(const void* T, int bits, const float* scale, co
     const int col_tiles = (M + kRowsColsI8 - 1) / kRowsColsI8;
     const int64_t blocks = ((N + kRowsThreads - 1) / kRowsThreads) * col_tiles;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    const int vec16 = bits == 8 && (M % 16 == 0) && ((reinterpret_cast<uintptr_t>(T) & 15) == 0);
+    // 16-entry chunks as one vector load: 16 bytes of an INT8 row, 8 bytes of an INT4 row
+    const int vec16 = bits == 8 ? (M % 16 == 0) && ((reinterpret_cast<uintptr_t>(T) & 15) == 0)
+                                : (M % 16 == 0) && ((reinterpret_cast<uintptr_t>(T) & 7) == 0);
     const size_t shmem = (size_t)CC * per_codebook;
     const int8_t* Tb = static_cast<const int8_t*>(T);
     const dim3 grid((unsigned)blocks), block(kRowsThreads);
