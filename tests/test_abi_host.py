@@ -28,6 +28,18 @@ def test_header_declares_the_documented_entry_points():
     assert len(names) >= 17
 
 
+def test_header_is_plain_c99(tmp_path):
+    """The boundary is a C ABI: the header must compile as C, without torch or HIP types."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "lutnn.h"\n'
+                   'int main(void) { lutnn_layer l; lutnn_tree t; lutnn_conv2d_geom g;\n'
+                   '  (void)l; (void)t; (void)g; return LUTNN_OK; }\n')
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                        "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_library_exports_every_declared_symbol(lut):
     for name in declared_symbols():
         assert hasattr(lut.LIB, name), "liblutnn.so does not export %s" % name
