@@ -35,7 +35,8 @@ lutnn_status check_dims(int32_t C, int32_t K, int32_t V, int32_t M) {
     if (C <= 0 || K <= 0 || V <= 0 || M <= 0)
         return fail(LUTNN_E_SHAPE, "C, K, V, M must be positive (got C=%d K=%d V=%d M=%d)", C, K, V, M);
     if (K > 256) return fail(LUTNN_E_SHAPE, "K=%d exceeds 256 (indices are uint8)", K);
-    if ((int64_t)C * V > (1 << 24) || M > (1 << 24) || C > (1 << 22))
+    // M: a grid dimension of the table kernels counts blocks of 256 padded columns and stops at 65535
+    if ((int64_t)C * V > (1 << 24) || M > (1 << 24) - 512 || C > (1 << 22))
         return fail(LUTNN_E_SHAPE, "dimension too large (C=%d V=%d M=%d)", C, V, M);
     return LUTNN_OK;
 }
