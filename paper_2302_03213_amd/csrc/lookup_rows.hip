@@ -8,8 +8,8 @@
 // 256 rows share them.  For one codebook a lane reads the table row its own index selects, 16
 // bytes at a time.  Rows of the slab are padded by 16 bytes, so that the K (<= 16) rows start in
 // different banks: lanes with different indices hit different banks, lanes with the same index
-// the same address (a broadcast) - the gather is conflict free although every lane goes its own
-// way.  This is the closest CDNA form of the paper's table read: there the index vector shuffles
+// the same address - the gather is nearly conflict free although every lane goes its own way
+// (measured: a quarter of the LDS-active cycles are conflicts, while the VALU sets the pace).  This is the closest CDNA form of the paper's table read: there the index vector shuffles
 // a 16-entry register table (pshufb / tbl), here it picks one of 16 LDS rows per lane.
 //
 // INT8 / INT4 entries are added into 32-bit accumulators one byte lane at a time (the compiler
