@@ -7,7 +7,10 @@
  *      each sub-vector is replaced by the index of its nearest of K centroids (Eq. 2);
  *   2. lookup + aggregation: Y[n][m] = sum_c T[c][idx[n][c]][m] (Eq. 4), where the table
  *      T[c][k][m] = P[c][k] . B[cV:(c+1)V][m] is precomputed (Eq. 3) and optionally
- *      quantised to INT8 with one symmetric scale (Sec. 3.3).
+ *      quantised to INT8 or INT4 with one symmetric scale (Sec. 3.3).
+ * Around it: the same two steps for a convolution read from its NCHW batch (lutnn_conv2d), the
+ * hash (threshold tree) encoder the paper discusses as the alternative to step 1 (lutnn_encode_tree,
+ * Sec. 2 and Sec. 7), and the backward pass of soft-PQ training (lutnn_softpq_backward, Sec. 3).
  *
  * Conventions common to every call
  *   - Pointers are DEVICE pointers unless a parameter is marked "host".  The caller owns
@@ -20,7 +23,8 @@
  *     returns a lutnn_status; on failure nothing has been enqueued and
  *     lutnn_last_error() describes the reason.  No exception crosses this boundary.
  *   - N == 0 is valid: once the layer descriptor has been validated the call returns LUTNN_OK
- *     without looking at the data pointers (an empty batch may have none) or enqueuing anything.
+ *     without looking at the data pointers (an empty batch may have none) or enqueuing anything
+ *     (lutnn_softpq_backward still writes its zero sums).
  *   - Inputs are assumed finite.  Non-finite activations never cause an out-of-range
  *     index or an out-of-bounds access; the index chosen for them is unspecified.
  *   - Outputs must not alias inputs.
