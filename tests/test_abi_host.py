@@ -318,3 +318,15 @@ def test_cost_model_formulas(lut):
     assert c.mm_size_bytes(D, M) == 4 * D * M
     assert c.equivalent_flops(16384, 4096, 4096) == 2 * 16384 * 4096 * 4096
     assert c.lookup_mfma_ops(16384, 1024, 4096) == 2 * 16384 * 16384 * 4096
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asking for more exits with a message before touching a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr
+    env = dict(os.environ, WORLD_SIZE="4")
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True, env=env)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr
