@@ -57,11 +57,12 @@ constexpr int64_t kMaxRows = (int64_t)1 << 31;
 int resolve_lookup_variant(const lutnn_layer* L, int variant, const uint8_t* idx, int64_t N) {
     if (variant != LUTNN_VARIANT_AUTO) return variant;
     if (is_int_table(L->table_dtype) && L->table_packed && L->K <= 16) {
-        // small problems: rows gathered straight from L2 beat a matrix-core launch
+        // small problems with few codebooks: rows gathered straight from L2 beat a matrix-core launch
         if (lutnn::gather_preferred(L->table, L->table_dtype == LUTNN_TABLE_I4 ? 2 : 1, L->C, L->M, N))
             return LUTNN_VARIANT_LDS;
-        // the sparse kernel works on 512-row tiles; below that the dense 256-row tile wastes less
-        if (N > 256 && lutnn::smfmac_supported(L->C, L->K, idx)) return LUTNN_VARIANT_SMFMAC;
+        // the sparse kernel at any N (its 128-row tiles spread even a single row's columns over the
+        // chip and stream the table in parallel); the dense one where the sparse one cannot run
+        if (lutnn::smfmac_supported(L->C, L->K, idx)) return LUTNN_VARIANT_SMFMAC;
         return LUTNN_VARIANT_MFMA;
     }
     return LUTNN_VARIANT_LDS;

@@ -490,8 +490,8 @@ inline bool idx_dword_ok(const uint8_t* idx, int C) {
 }  // namespace
 
 // True when the gather variant would read the table straight from L2 (no staging) and the whole
-// problem is small enough for that to beat the matrix-core kernels, whose 256/512-row tiles and
-// pipeline fill are wasted on it (measured cross-over: about 3e7 table entries).
+// problem is small enough for that to beat the matrix-core kernels, whose tiles and pipeline fill
+// are wasted on it (measured cross-over: about 3e7 table entries) ...
 bool gather_preferred(const void* T, int table_kind, int C, int M, int64_t N) {
     if (!T) return false;
     const bool f32 = table_kind == 0;
@@ -502,7 +502,9 @@ bool gather_preferred(const void* T, int table_kind, int C, int M, int64_t N) {
     const bool direct = table_kind == 0   ? gather_ok(static_cast<const float*>(T), M, staged_blocks)
                         : table_kind == 1 ? gather_ok(static_cast<const int8_t*>(T), M, staged_blocks)
                                           : gather_i4_ok(static_cast<const uint8_t*>(T), M, staged_blocks);
-    return direct && N * (int64_t)C * M <= (int64_t)1 << 25;
+    // ... and the per-row chain of C dependent additions (about 65 ns each) is short: with a
+    // thousand codebooks a single row takes 67 us this way and 34 us on the matrix cores
+    return direct && C <= 256 && N * (int64_t)C * M <= (int64_t)1 << 25;
 }
 
 hipError_t launch_lookup_lds_i8(const int8_t* T, const float* scale, const float* bias, int C, int K,

@@ -293,7 +293,8 @@ def test_auto_variant_rule(lut):
     big = _layer(lut, C=1024, M=4096)
     assert L.lutnn_auto_variant(ctypes.byref(big), vp(0x30000), 16384) == lut.VARIANT_SMFMAC
     assert L.lutnn_auto_variant(ctypes.byref(big), vp(0x30004), 16384) == lut.VARIANT_MFMA  # idx alignment
-    assert L.lutnn_auto_variant(ctypes.byref(big), vp(0x30000), 200) == lut.VARIANT_MFMA
+    assert L.lutnn_auto_variant(ctypes.byref(big), vp(0x30000), 200) == lut.VARIANT_SMFMAC
+    assert L.lutnn_auto_variant(ctypes.byref(big), vp(0x30000), 1) == lut.VARIANT_SMFMAC  # long chains: no gather
     odd = _layer(lut, C=1000, M=4096)
     assert L.lutnn_auto_variant(ctypes.byref(odd), vp(0x30000), 16384) == lut.VARIANT_MFMA  # C % 32 != 0
     small = _layer(lut, C=64, M=64)  # few table entries: rows gathered straight from L2
