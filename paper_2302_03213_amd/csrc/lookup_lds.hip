@@ -365,6 +365,83 @@ __global__ __launch_bounds__(kThreads) void lookup_gather_kernel(
     y[3] = out.w;
 }
 
+// The same gather for a handful of rows (batch-1 inference, the paper's own setting): with so few
+// wavefronts the per-row chain of C loads and additions is pure latency, so the SPLIT wavefronts of
+// a workgroup share one (row, 256 columns) and take a contiguous range of codebooks each; the
+// partial sums meet in LDS and wavefront 0 adds them in range order (exact for integer tables, a
+// fixed order for fp32 ones).  M % 4 == 0, table aligned for the vector load, M >= 256.
+template <typename TT, bool IDX_DWORD, int SPLIT>
+__global__ __launch_bounds__(64 * SPLIT) void lookup_gather_split_kernel(
+    const TT* __restrict__ T, const float* __restrict__ scale, const float* __restrict__ bias, int C,
+    int K, int M, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y, int64_t ldy,
+    int col_chunks, int per_wave) {
+    constexpr bool I8 = sizeof(TT) == 1;
+    typedef typename std::conditional<I8, uint32_t, float4>::type Vec;  // four columns
+    typedef typename std::conditional<I8, int32_t, float>::type Acc;
+    __shared__ Acc part[SPLIT][4][64];
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t row = blockIdx.x / col_chunks;  // < N by construction of the grid
+    const int m = (int)(blockIdx.x % col_chunks) * kGatherCols + lane * 4;
+    const bool col_ok = m < M;  // M % 4 == 0: a lane's four columns are all inside or all outside
+    const uint8_t* __restrict__ irow = idx + row * C;
+    const TT* __restrict__ tcol = T + (col_ok ? m : 0);
+
+    Acc a[4] = {0, 0, 0, 0};
+    auto add = [&](int c, int k) {
+        k = k < K ? k : K - 1;
+        const Vec v = *reinterpret_cast<const Vec*>(tcol + ((size_t)c * K + k) * M);
+        if constexpr (I8) {
+            a[0] += (int32_t)(int8_t)(v & 0xffu);
+            a[1] += (int32_t)(int8_t)((v >> 8) & 0xffu);
+            a[2] += (int32_t)(int8_t)((v >> 16) & 0xffu);
+            a[3] += (int32_t)v >> 24;
+        } else {
+            a[0] += v.x;
+            a[1] += v.y;
+            a[2] += v.z;
+            a[3] += v.w;
+        }
+    };
+    // codebooks [c, c_end) of this wavefront; per_wave is a multiple of 4, so dword index loads stay aligned
+    int c = w * per_wave;
+    const int c_end = min(C, c + per_wave);
+    if (IDX_DWORD) {
+        for (; c + 4 <= c_end; c += 4) {
+            const uint32_t word =
+                (uint32_t)__builtin_amdgcn_readfirstlane(*reinterpret_cast<const uint32_t*>(irow + c));
+#pragma unroll
+            for (int b = 0; b < 4; ++b) add(c + b, (int)((word >> (8 * b)) & 0xffu));
+        }
+    }
+    for (; c < c_end; ++c) add(c, (int)__builtin_amdgcn_readfirstlane((uint32_t)irow[c]));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) part[w][j][lane] = a[j];
+    __syncthreads();
+    if (w != 0 || !col_ok) return;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        Acc sum = part[0][j][lane];
+        for (int ww = 1; ww < SPLIT; ++ww) sum += part[ww][j][lane];
+        a[j] = sum;
+    }
+    float* __restrict__ y = Y + row * ldy + m;
+    if constexpr (I8) {
+        const float s = *scale;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            y[j] = bias ? __fmaf_rn((float)a[j], s, bias[m + j]) : __fmul_rn((float)a[j], s);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) y[j] = bias ? a[j] + bias[m + j] : a[j];
+    }
+}
+
+// Fewer (row, 256-column chunk) pairs than this and at least this many codebooks: the split form
+// (measured at C = 1024, M = 4096: faster than one wavefront per pair up to about 160 rows).
+constexpr int64_t kSplitMaxWaves = 2049;
+constexpr int kSplitMinCodebooks = 64;
+
 // The staged kernels need at least this many workgroups to be worth their staging.
 constexpr int64_t kMinStagedBlocks = 512;
 
@@ -385,6 +462,19 @@ hipError_t launch_gather(const TT* T, const float* scale, const float* bias, int
     const int lpr = M / 4;  // lanes per row when a row is narrower than a wavefront
     if (lpr >= 64) {
         const int col_chunks = (M + kGatherCols - 1) / kGatherCols;
+        if (N * col_chunks < kSplitMaxWaves && C >= kSplitMinCodebooks) {
+            const dim3 grid((unsigned)(N * col_chunks));
+#define LUTNN_LAUNCH_SPLIT(DW, SPLIT)                                                                        \
+    hipLaunchKernelGGL((lookup_gather_split_kernel<TT, DW, SPLIT>), grid, dim3(64 * SPLIT), 0, s, T, scale,  \
+                       bias, C, K, M, idx, N, Y, ldy, col_chunks, ((C + SPLIT - 1) / SPLIT + 3) & ~3)
+            if (C >= 512) {
+                if (idx_dword) LUTNN_LAUNCH_SPLIT(true, 16); else LUTNN_LAUNCH_SPLIT(false, 16);
+            } else {
+                if (idx_dword) LUTNN_LAUNCH_SPLIT(true, 4); else LUTNN_LAUNCH_SPLIT(false, 4);
+            }
+#undef LUTNN_LAUNCH_SPLIT
+            return hipGetLastError();
+        }
         const int64_t blocks = (N * col_chunks + kWaves - 1) / kWaves;
         if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
         if (idx_dword)
@@ -502,9 +592,15 @@ bool gather_preferred(const void* T, int table_kind, int C, int M, int64_t N) {
     const bool direct = table_kind == 0   ? gather_ok(static_cast<const float*>(T), M, staged_blocks)
                         : table_kind == 1 ? gather_ok(static_cast<const int8_t*>(T), M, staged_blocks)
                                           : gather_i4_ok(static_cast<const uint8_t*>(T), M, staged_blocks);
-    // ... and the per-row chain of C dependent additions (about 65 ns each) is short: with a
-    // thousand codebooks a single row takes 67 us this way and 34 us on the matrix cores
-    return direct && C <= 256 && N * (int64_t)C * M <= (int64_t)1 << 25;
+    if (!direct) return false;
+    // a few rows: the split gather reads N rows' worth of table entries, the matrix cores the whole
+    // table; measured cross-over at config 5's width between 32 and 48 rows (K = 16)
+    const int64_t col_chunks = (M + kGatherCols - 1) / kGatherCols;
+    if (table_kind != 2 && M >= 256 && C >= kSplitMinCodebooks && N <= 32 && N * col_chunks < kSplitMaxWaves)
+        return true;
+    // ... or the per-row chain of C dependent additions (about 65 ns each) is short: with a
+    // thousand codebooks a row takes 67 us on the unsplit gather and 34 us on the matrix cores
+    return C <= 256 && N * (int64_t)C * M <= (int64_t)1 << 25;
 }
 
 hipError_t launch_lookup_lds_i8(const int8_t* T, const float* scale, const float* bias, int C, int K,

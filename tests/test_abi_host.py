@@ -294,7 +294,9 @@ def test_auto_variant_rule(lut):
     assert L.lutnn_auto_variant(ctypes.byref(big), vp(0x30000), 16384) == lut.VARIANT_SMFMAC
     assert L.lutnn_auto_variant(ctypes.byref(big), vp(0x30004), 16384) == lut.VARIANT_MFMA  # idx alignment
     assert L.lutnn_auto_variant(ctypes.byref(big), vp(0x30000), 200) == lut.VARIANT_SMFMAC
-    assert L.lutnn_auto_variant(ctypes.byref(big), vp(0x30000), 1) == lut.VARIANT_SMFMAC  # long chains: no gather
+    assert L.lutnn_auto_variant(ctypes.byref(big), vp(0x30000), 1) == lut.VARIANT_LDS   # split gather: a few rows
+    assert L.lutnn_auto_variant(ctypes.byref(big), vp(0x30000), 32) == lut.VARIANT_LDS
+    assert L.lutnn_auto_variant(ctypes.byref(big), vp(0x30000), 33) == lut.VARIANT_SMFMAC
     odd = _layer(lut, C=1000, M=4096)
     assert L.lutnn_auto_variant(ctypes.byref(odd), vp(0x30000), 16384) == lut.VARIANT_MFMA  # C % 32 != 0
     small = _layer(lut, C=64, M=64)  # few table entries: rows gathered straight from L2

@@ -264,6 +264,32 @@ def test_lookup_many_rows_gather_i8_i4_f32(lut, N, C, K, M):
     assert_f32_close(host(lut.lookup(lf, dev(idx), "lds")), oracle.lookup_f32(olf.Tf, idx, wf.bias))
 
 
+@pytest.mark.parametrize("N,C,K,M", [(1, 1024, 16, 4096), (1, 64, 16, 256), (3, 513, 16, 260), (7, 100, 40, 1028),
+                                     (2, 2048, 5, 512), (5, 70, 16, 4100)])
+def test_lookup_few_rows_split_gather(lut, N, C, K, M):
+    """A handful of rows: the workgroup's wavefronts split the codebooks and meet in LDS (int8 exact,
+    fp32 in a fixed order within the usual tolerance); index matrix also at an odd address."""
+    idx = wl.random_indices(N, C, K, seed=N + C + M)
+    w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=N + M)
+    ol = OracleLayer(w)
+    ol.q = wl.random_table_i8(C, K, M, seed=C + K)
+    ol.s = np.float32(0.017)
+    ref = ol.lookup(idx)
+    for with_bias in (True, False):
+        layer = device_layer_from_oracle(lut, ol, with_bias)
+        np.testing.assert_array_equal(host(lut.lookup(layer, dev(idx), "lds")),
+                                      ref if with_bias else ol.lookup(idx, bias=None))
+    raw = torch.zeros(N * C + 1, dtype=torch.uint8, device="cuda")
+    raw[1:] = dev(idx).flatten()
+    np.testing.assert_array_equal(host(lut.lookup(device_layer_from_oracle(lut, ol), raw[1:].view(N, C), "lds")), ref)
+    wf = wl.make_layer("t", 1, C, K, 2, M, "f32", seed=N + M + 1)
+    olf = OracleLayer(wf)
+    got = host(lut.lookup(device_layer_from_oracle(lut, olf), dev(idx), "lds"))
+    assert_f32_close(got, oracle.lookup_f32(olf.Tf, idx, wf.bias))
+    again = host(lut.lookup(device_layer_from_oracle(lut, olf), dev(idx), "lds"))
+    np.testing.assert_array_equal(got, again)  # fixed summation order
+
+
 def test_lookup_index_matrix_at_odd_address(lut):
     # idx only byte aligned: the dword / 16-byte index fetches must not be used
     w = wl.make_layer("t", 1, 32, 16, 2, 128, "i8", seed=35)
