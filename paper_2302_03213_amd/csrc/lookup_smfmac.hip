@@ -48,6 +48,7 @@
 // one, so there is no pipeline fill per tile.
 //
 // Needs C % 32 == 0 and a 16-byte aligned idx.
+#include <algorithm>
 #include <cstdlib>
 #include <type_traits>
 
@@ -81,11 +82,15 @@ __device__ __forceinline__ void dma16_at(uint32_t lds_base, const void* sbase, u
 
 // TM = 32-row blocks per wavefront: the workgroup tile is 128*TM rows x 128 columns.  TM = 4 is
 // the efficient shape; 3, 2 and 1 exist so that problems with few rows still spread over the chip.
-template <int TM>
+// SPLITS > 1 (run-time `splits`, template flag SPLIT): `splits` workgroups share an output tile, each
+// contracts C / splits consecutive codebooks and adds its int32 partial sums into Y with atomics; Y
+// then holds integers (zeroed beforehand, turned into the final floats by a separate pass).  For
+// problems with fewer tiles than compute units: more workgroups stream the table in parallel.
+template <int TM, bool SPLIT = false>
 __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const uint4* __restrict__ packed, const float* __restrict__ scale, const float* __restrict__ bias,
     int C, int M, int Mp, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y,
-    int64_t ldy, int row_tiles, int64_t tiles) {
+    int64_t ldy, int row_tiles, int64_t tiles, int splits) {
     constexpr int WAVE_ROWS = TM * 32;
     constexpr int BM = 4 * WAVE_ROWS;  // rows per workgroup
     constexpr int I_LOADS = TM;        // index loads per wave per super-stage
@@ -115,7 +120,10 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     if (t >= xcd_end) return;
     bool has_next = t + wg_per_xcd < xcd_end;
 
-    const int supers = C / 32;  // C % 32 == 0
+    // codebooks of this workgroup: all C, or share `t % splits` of them (C / splits % 32 == 0)
+    const int c_count = SPLIT ? C / splits : C;
+    const int c_begin = SPLIT ? (int)(t % splits) * c_count : 0;
+    const int supers = c_count / 32;  // C % 32 == 0
     const int stages = 2 * supers;
 
     // ---- the two streams.  Compute works on tile (ct_n0, ct_m0); the loads run three stages
@@ -133,10 +141,11 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const uint32_t rs1 = (uint32_t)Mp * 16u;  // bytes from one codebook's row to the next
     const int row0 = 16 * (w >> 1) + 4 * (w & 1);
     auto aim_loads_at = [&](int64_t tt) {
-        ft_n0 = (int)(tt / row_tiles) * BN;
-        ft_m0 = (tt % row_tiles) * BM;
-        bp = reinterpret_cast<const char*>(packed + ft_n0) + (size_t)row0 * rs1;
-        ip = idx + ft_m0 * C;
+        const int64_t tile = SPLIT ? tt / splits : tt;
+        ft_n0 = (int)(tile / row_tiles) * BN;
+        ft_m0 = (tile % row_tiles) * BM;
+        bp = reinterpret_cast<const char*>(packed + ft_n0) + (size_t)(row0 + c_begin) * rs1;
+        ip = idx + ft_m0 * C + c_begin;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             int64_t row = w * WAVE_ROWS + i * 32 + l32;
@@ -443,7 +452,10 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
                 run_stage(s + 3, B3{}, std::false_type{});
             }
         }
-        mfma_store_tile<TM>(acc, sc, bias, M, N, ct_m0 + w * WAVE_ROWS, ct_n0, Y, ldy);
+        if constexpr (SPLIT)
+            mfma_atomic_add_tile<TM>(acc, M, N, ct_m0 + w * WAVE_ROWS, ct_n0, reinterpret_cast<int32_t*>(Y), ldy);
+        else
+            mfma_store_tile<TM>(acc, sc, bias, M, N, ct_m0 + w * WAVE_ROWS, ct_n0, Y, ldy);
         if (!has_next) break;
         // next tile: its first stages and index words are already in LDS / registers
 #pragma unroll
@@ -459,6 +471,23 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     }
 }
 
+// Y[n][m] = 0 as int32 / Y[n][m] = fma((float)int32, s, bias[m]) in place, over the N x M region of a
+// matrix with row stride ldy: the two passes around a codebook-split contraction.
+// grid: (blocks of 256 columns, rows).
+__global__ __launch_bounds__(256) void zero_rows_kernel(float* __restrict__ Y, int M, int64_t ldy) {
+    const int m = blockIdx.x * 256 + threadIdx.x;
+    if (m < M) Y[(int64_t)blockIdx.y * ldy + m] = 0.f;
+}
+__global__ __launch_bounds__(256) void dequant_rows_kernel(float* __restrict__ Y, int M, int64_t ldy,
+                                                           const float* __restrict__ scale,
+                                                           const float* __restrict__ bias) {
+    const int m = blockIdx.x * 256 + threadIdx.x;
+    if (m >= M) return;
+    float* y = Y + (int64_t)blockIdx.y * ldy + m;
+    const float a = (float)__float_as_int(*y);
+    *y = bias ? __fmaf_rn(a, *scale, bias[m]) : __fmul_rn(a, *scale);
+}
+
 template <int TM>
 hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias, int C, int M,
                      const uint8_t* idx, int64_t N, float* Y, int64_t ldy, hipStream_t s) {
@@ -470,12 +499,38 @@ hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias
     int64_t blocks = (tiles + 7) / 8 * 8;
     if (blocks > 0x7fffffffLL || row_tiles > 0x7fffffffLL) return hipErrorInvalidValue;
     if ((int64_t)Mp * 16 * 21 > 0xffffffffLL) return hipErrorInvalidValue;  // row strides are 32-bit
+    // Few tiles and many codebooks (a small batch on a wide layer): every workgroup would stream
+    // 2 KiB x C of table alone while most of the chip idles.  Split the codebooks over `splits`
+    // workgroups per tile instead; their int32 partial sums meet in Y through atomics, between a
+    // pass that zeroes Y and one that dequantises it.  Worth its two extra launches and its atomics
+    // from 512 codebooks on and up to 128 rows (measured at C = 1024, M = 4096: 0.025 against
+    // 0.035 ms per call at 33 rows, equal at 256, slower beyond); each share keeps at least 64
+    // codebooks.
+    if (tiles <= kComputeUnits / 2 && C >= 512 && N <= 128) {
+        const int supers = C / 32;
+        int splits = 1;
+        for (int cand = (int)std::min<int64_t>(16, kComputeUnits / tiles); cand > 1; --cand)
+            if (supers % cand == 0 && supers / cand >= 2) {
+                splits = cand;
+                break;
+            }
+        if (splits > 1) {
+            const dim3 cells((unsigned)((M + 255) / 256), (unsigned)N);
+            hipLaunchKernelGGL(zero_rows_kernel, cells, dim3(256), 0, s, Y, M, ldy);
+            const int64_t units = tiles * splits;
+            hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, true>), dim3((unsigned)((units + 7) / 8 * 8)),
+                               dim3(kMfmaThreads), 0, s, reinterpret_cast<const uint4*>(packed), scale, bias, C, M,
+                               Mp, idx, N, Y, ldy, (int)row_tiles, units, splits);
+            hipLaunchKernelGGL(dequant_rows_kernel, cells, dim3(256), 0, s, Y, M, ldy, scale, bias);
+            return hipGetLastError();
+        }
+    }
     // Stream several tiles per workgroup when the ring phase carries over from tile to tile:
     // one workgroup per compute unit (the kernel's LDS footprint allows only one anyway).
     if (C % 64 == 0 && blocks > kComputeUnits) blocks = kComputeUnits;
-    hipLaunchKernelGGL(lookup_smfmac_i8_kernel<TM>, dim3((unsigned)blocks), dim3(kMfmaThreads), 0, s,
+    hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, false>), dim3((unsigned)blocks), dim3(kMfmaThreads), 0, s,
                        reinterpret_cast<const uint4*>(packed), scale, bias, C, M, Mp, idx, N, Y, ldy,
-                       (int)row_tiles, tiles);
+                       (int)row_tiles, tiles, 1);
     return hipGetLastError();
 }
 

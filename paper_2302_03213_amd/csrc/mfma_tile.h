@@ -236,6 +236,31 @@ __device__ __forceinline__ void mfma_store_tile_impl(const v16i (&acc)[TM][4], f
     }
 }
 
+// The same tile added into an int32 image of Y (row stride ldy elements) with integer atomics:
+// the partial sums of workgroups that share an output tile but split the codebooks.  Integer
+// addition is associative, so the result does not depend on the order of arrival.
+template <int TM>
+__device__ __forceinline__ void mfma_atomic_add_tile(const v16i (&acc)[TM][4], int M, int64_t N,
+                                                     int64_t row_base, int col_base, int32_t* __restrict__ Yi,
+                                                     int64_t ldy) {
+    const int lane = threadIdx.x & 63;
+    const int l32 = lane & 31, h = lane >> 5;
+    int32_t* __restrict__ p = Yi + (row_base + 4 * h) * ldy + col_base + l32;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int rr = i * 32 + 8 * (r >> 2) + (r & 3);
+            if (row_base + 4 * h + rr < N) {
+                int32_t* __restrict__ q = p + (int64_t)rr * ldy;
+#pragma unroll
+                for (int tn = 0; tn < 4; ++tn)
+                    if (col_base + tn * 32 + l32 < M) atomicAdd(q + tn * 32, acc[i][tn][r]);
+            }
+        }
+    }
+}
+
 template <int TM>
 __device__ __forceinline__ void mfma_store_tile(const v16i (&acc)[TM][4], float s,
                                                 const float* __restrict__ bias, int M, int64_t N,

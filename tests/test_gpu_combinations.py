@@ -73,6 +73,41 @@ def test_linear_tree_with_an_int4_table(lut):
         np.testing.assert_array_equal(host(lut.linear_tree(layer, tree, dev(w.X), v)), ref, err_msg=v)
 
 
+def test_small_batch_paths_replayed_from_a_hip_graph(lut):
+    """The small-batch paths under capture: 64 rows on a wide layer (codebooks split over workgroups:
+    a zeroing pass, integer atomics into Y, a dequantising pass - every replay must start from
+    zero again) and 4 rows (split gather)."""
+    C, K, V, M = 1024, 16, 4, 512
+    w = wl.make_layer("t", 64, C, K, V, M, "i8", seed=19)
+    layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8, bias=dev(w.bias))
+    for N in (64, 4):
+        X = dev(w.X[:N]).clone()
+        Y = torch.empty((N, M), dtype=torch.float32, device="cuda")
+        ws = torch.empty((N, C), dtype=torch.uint8, device="cuda")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            lut.linear(layer, X, "auto", out=Y, idx_workspace=ws)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            lut.linear(layer, X, "auto", out=Y, idx_workspace=ws)
+        rng = np.random.default_rng(N)
+        for rep in range(4):
+            Xn = rng.standard_normal((N, C * V)).astype(np.float32)
+            X.copy_(dev(Xn))
+            graph.replay()
+            torch.cuda.synchronize()
+            got = host(Y)
+            idx_ref = oracle.encode(w.P, Xn)
+            q, s = oracle.quantize_i8(oracle.build_table_f32(w.P, w.W))
+            ref = oracle.lookup_i8(q, s, idx_ref, w.bias)
+            clean = (host(ws) == idx_ref).all(axis=1)
+            assert clean.mean() > 0.9
+            np.testing.assert_array_equal(got[clean], ref[clean], err_msg="N=%d replay %d" % (N, rep))
+
+
 @pytest.mark.parametrize("variant", ["auto", "smfmac", "mfma", "lds", "fused"])
 def test_linear_replayed_from_a_hip_graph(lut, variant):
     """The entry points allocate nothing, clear nothing with memset nodes and never synchronise, so a

@@ -173,6 +173,26 @@ def test_lookup_smfmac_every_tile_height(lut, monkeypatch, rows, N, C, K, M):
     np.testing.assert_array_equal(host(lut.lookup(layer, dev(idx), "smfmac")), ol.lookup(idx))
 
 
+@pytest.mark.parametrize("N,C,K,M", [(33, 1024, 16, 4096), (100, 512, 16, 300), (128, 544, 16, 1000),
+                                     (64, 576, 7, 130), (1, 2048, 16, 256), (77, 1536, 16, 768)])
+def test_lookup_smfmac_codebooks_split_over_workgroups(lut, N, C, K, M):
+    """Few tiles, many codebooks: several workgroups share an output tile, each with a range of the
+    codebooks, and add int32 partial sums into Y (zeroed before, dequantised after).  Bit-exact, with
+    and without bias, into a strided Y whose guard band must stay untouched.  (544 codebooks = 17
+    groups of 32 cannot be split evenly: that shape takes the unsplit kernel.)"""
+    w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=N + C + M)
+    ol = OracleLayer(w)
+    ol.q = wl.random_table_i8(C, K, M, seed=C + M)
+    ol.s = np.float32(0.0213)
+    idx = wl.random_indices(N, C, K, seed=N + 5)
+    for with_bias in (True, False):
+        layer = device_layer_from_oracle(lut, ol, with_bias)
+        Ybig = torch.full((N, M + 8), 3.5, dtype=torch.float32, device="cuda")
+        lut.lookup(layer, dev(idx), "smfmac", out=Ybig[:, :M])
+        np.testing.assert_array_equal(host(Ybig[:, :M]), ol.lookup(idx, bias="layer" if with_bias else None))
+        assert (host(Ybig[:, M:]) == 3.5).all()
+
+
 @pytest.mark.parametrize("N,C,K,M", SMFMAC_SHAPES)
 def test_lookup_smfmac_bit_exact(lut, N, C, K, M):
     w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=71 + N + C + M)
