@@ -134,6 +134,8 @@ def main():
     ap.add_argument("--op", default="linear", choices=["linear", "softpq_backward"],
                     help="softpq_backward: time lutnn_softpq_backward (the training operator of Sec. 3) on "
                          "the workload's first layer instead of the inference step")
+    ap.add_argument("--rows", type=int, default=0,
+                    help="use only the first ROWS rows of the workload (small-batch latency of the same layer)")
     ap.add_argument("--cpu-sample-rows", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -157,6 +159,11 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     layers = workload_by_name(args.workload)
+    if args.rows:  # a smaller batch of the same layer(s): per-call latency at N = --rows
+        for w in layers:
+            assert not w.conv, "--rows applies to matrix workloads"
+            w.N = min(w.N, args.rows)
+            w.X = np.ascontiguousarray(w.X[:w.N])
     if args.op == "softpq_backward":
         return bench_softpq_backward(args, layers[0], lut, cost, np, torch)
 
