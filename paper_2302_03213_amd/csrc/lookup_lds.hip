@@ -571,6 +571,54 @@ __global__ __launch_bounds__(kThreads) void lookup_gather_i4_kernel(
         y[j] = bias ? __fmaf_rn((float)a[j], s, bias[m + j]) : __fmul_rn((float)a[j], s);
 }
 
+// The split form of the 4-bit gather for a handful of rows (see lookup_gather_split_kernel): one
+// (row, 512 columns) per workgroup, its wavefronts each a range of the codebooks.  M % 8 == 0, M >= 512.
+template <bool IDX_DWORD, int SPLIT>
+__global__ __launch_bounds__(64 * SPLIT) void lookup_gather_i4_split_kernel(
+    const uint8_t* __restrict__ T, const float* __restrict__ scale, const float* __restrict__ bias,
+    int C, int K, int M, const uint8_t* __restrict__ idx, float* __restrict__ Y, int64_t ldy,
+    int col_chunks, int per_wave) {
+    __shared__ int32_t part[SPLIT][8][64];
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t row = blockIdx.x / col_chunks;  // < N by construction of the grid
+    const int m = (int)(blockIdx.x % col_chunks) * kGatherColsI4 + lane * 8;
+    const bool col_ok = m < M;  // M % 8 == 0: a lane's eight columns are all inside or all outside
+    const uint8_t* __restrict__ irow = idx + row * C;
+    const uint8_t* __restrict__ tcol = T + (col_ok ? m / 2 : 0);
+    const size_t Mb = (size_t)M / 2;
+    int32_t a[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    auto add = [&](int c, int k) {
+        k = k < K ? k : K - 1;
+        const uint32_t v = *reinterpret_cast<const uint32_t*>(tcol + ((size_t)c * K + k) * Mb);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a[j] += (int32_t)(v << (28 - 4 * j)) >> 28;  // nibble j, sign extended
+    };
+    int c = w * per_wave;  // per_wave is a multiple of 4: dword index loads stay aligned
+    const int c_end = min(C, c + per_wave);
+    if (IDX_DWORD) {
+        for (; c + 4 <= c_end; c += 4) {
+            const uint32_t word =
+                (uint32_t)__builtin_amdgcn_readfirstlane(*reinterpret_cast<const uint32_t*>(irow + c));
+#pragma unroll
+            for (int b = 0; b < 4; ++b) add(c + b, (int)((word >> (8 * b)) & 0xffu));
+        }
+    }
+    for (; c < c_end; ++c) add(c, (int)__builtin_amdgcn_readfirstlane((uint32_t)irow[c]));
+#pragma unroll
+    for (int j = 0; j < 8; ++j) part[w][j][lane] = a[j];
+    __syncthreads();
+    if (w != 0 || !col_ok) return;
+    const float s = *scale;
+    float* __restrict__ y = Y + row * ldy + m;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        int32_t sum = part[0][j][lane];
+        for (int ww = 1; ww < SPLIT; ++ww) sum += part[ww][j][lane];
+        y[j] = bias ? __fmaf_rn((float)sum, s, bias[m + j]) : __fmul_rn((float)sum, s);
+    }
+}
+
 constexpr int kLdsBudget = 64 * 1024;
 
 inline bool idx_dword_ok(const uint8_t* idx, int C) {
@@ -595,9 +643,9 @@ bool gather_preferred(const void* T, int table_kind, int C, int M, int64_t N) {
     if (!direct) return false;
     // a few rows: the split gather reads N rows' worth of table entries, the matrix cores the whole
     // table; measured cross-over at config 5's width between 32 and 48 rows (K = 16)
-    const int64_t col_chunks = (M + kGatherCols - 1) / kGatherCols;
-    if (table_kind != 2 && M >= 256 && C >= kSplitMinCodebooks && N <= 32 && N * col_chunks < kSplitMaxWaves)
-        return true;
+    const int chunk = table_kind == 2 ? kGatherColsI4 : kGatherCols;  // columns per wavefront
+    const int64_t col_chunks = (M + chunk - 1) / chunk;
+    if (M >= chunk && C >= kSplitMinCodebooks && N <= 32 && N * col_chunks < kSplitMaxWaves) return true;
     // ... or the per-row chain of C dependent additions (about 65 ns each) is short: with a
     // thousand codebooks a row takes 67 us on the unsplit gather and 34 us on the matrix cores
     return C <= 256 && N * (int64_t)C * M <= (int64_t)1 << 25;
@@ -660,6 +708,19 @@ hipError_t launch_lookup_lds_i4(const uint8_t* T, const float* scale, const floa
         const int lpr = M / 8;
         if (lpr >= 64) {
             const int col_chunks = (M + kGatherColsI4 - 1) / kGatherColsI4;
+            if (N * col_chunks < kSplitMaxWaves && C >= kSplitMinCodebooks) {
+                const dim3 grid((unsigned)(N * col_chunks));
+#define LUTNN_LAUNCH_SPLIT_I4(DW, SPLIT)                                                                      \
+    hipLaunchKernelGGL((lookup_gather_i4_split_kernel<DW, SPLIT>), grid, dim3(64 * SPLIT), 0, s, T, scale, bias, \
+                       C, K, M, idx, Y, ldy, col_chunks, ((C + SPLIT - 1) / SPLIT + 3) & ~3)
+                if (C >= 512) {
+                    if (idx_dword) LUTNN_LAUNCH_SPLIT_I4(true, 16); else LUTNN_LAUNCH_SPLIT_I4(false, 16);
+                } else {
+                    if (idx_dword) LUTNN_LAUNCH_SPLIT_I4(true, 4); else LUTNN_LAUNCH_SPLIT_I4(false, 4);
+                }
+#undef LUTNN_LAUNCH_SPLIT_I4
+                return hipGetLastError();
+            }
             const int64_t gblocks = (N * col_chunks + kWaves - 1) / kWaves;
             if (gblocks > 0x7fffffffLL) return hipErrorInvalidValue;
             if (idx_dword)

@@ -285,7 +285,7 @@ def test_lookup_many_rows_gather_i8_i4_f32(lut, N, C, K, M):
 
 
 @pytest.mark.parametrize("N,C,K,M", [(1, 1024, 16, 4096), (1, 64, 16, 256), (3, 513, 16, 260), (7, 100, 40, 1028),
-                                     (2, 2048, 5, 512), (5, 70, 16, 4100)])
+                                     (2, 2048, 5, 512), (5, 70, 16, 4100), (6, 96, 16, 1032)])
 def test_lookup_few_rows_split_gather(lut, N, C, K, M):
     """A handful of rows: the workgroup's wavefronts split the codebooks and meet in LDS (int8 exact,
     fp32 in a fixed order within the usual tolerance); index matrix also at an odd address."""
@@ -308,6 +308,11 @@ def test_lookup_few_rows_split_gather(lut, N, C, K, M):
     assert_f32_close(got, oracle.lookup_f32(olf.Tf, idx, wf.bias))
     again = host(lut.lookup(device_layer_from_oracle(lut, olf), dev(idx), "lds"))
     np.testing.assert_array_equal(got, again)  # fixed summation order
+    # INT4 storage of the same codes clamped to 4 bits (the split form needs M % 8 == 0, M >= 512)
+    q4 = np.clip(ol.q, -7, 7).astype(np.int8)
+    l4 = lut.LutLayer(dev(w.P), dev(oracle.pack_nibbles(q4)), lut.TABLE_I4, M,
+                      scale=dev(np.array([ol.s], np.float32)), bias=dev(w.bias))
+    np.testing.assert_array_equal(host(lut.lookup(l4, dev(idx), "lds")), oracle.lookup_i8(q4, ol.s, idx, w.bias))
 
 
 def test_lookup_index_matrix_at_odd_address(lut):
