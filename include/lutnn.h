@@ -297,6 +297,22 @@ LUTNN_API lutnn_status lutnn_conv2d(const lutnn_layer* layer, const float* input
                                     int32_t variant, uint8_t* idx_workspace, void* stream);
 
 /*
+ * The hash encoder on a convolution's rows (lutnn_encode_tree on the im2col matrix of `input`,
+ * which is never written; row and column order as for lutnn_encode_conv2d), and the whole
+ * convolution with it: lutnn_encode_tree_conv2d into idx_workspace, then lutnn_lookup.
+ *   tree   C * V must equal Cin*kh*kw; V in {1,2,3,4,8,9,16} (E_UNSUPPORTED otherwise)
+ *   idx / idx_workspace  [B*Ho*Wo][C] uint8
+ * Errors: as lutnn_encode_tree, lutnn_encode_conv2d and lutnn_lookup; E_SHAPE when tree and layer
+ * disagree.
+ */
+LUTNN_API lutnn_status lutnn_encode_tree_conv2d(const lutnn_tree* tree, const float* input, int64_t B,
+                                                const lutnn_conv2d_geom* geom, uint8_t* idx, void* stream);
+LUTNN_API lutnn_status lutnn_conv2d_tree(const lutnn_layer* layer, const lutnn_tree* tree,
+                                         const float* input, int64_t B, const lutnn_conv2d_geom* geom,
+                                         float* Y, int64_t ldy, int32_t variant, uint8_t* idx_workspace,
+                                         void* stream);
+
+/*
  * Host: the variant that LUTNN_VARIANT_AUTO stands for in lutnn_lookup(layer, idx, N, ...) - and in
  * lutnn_linear when `idx` is its workspace - so that callers (and benchmarks) can report which
  * kernel ran.  Pure function of the descriptor, N and the address of idx; nothing is launched

@@ -29,7 +29,8 @@ VARIANTS = {"auto": VARIANT_AUTO, "lds": VARIANT_LDS, "mfma": VARIANT_MFMA, "fus
 
 EXPORTS = ["lutnn_table_bytes", "lutnn_packed_bytes", "lutnn_build_table", "lutnn_encode",
            "lutnn_lookup", "lutnn_linear", "lutnn_encode_tree", "lutnn_linear_tree",
-           "lutnn_softpq_backward", "lutnn_softpq_workspace_bytes", "lutnn_conv2d_rows", "lutnn_encode_conv2d", "lutnn_conv2d",
+           "lutnn_softpq_backward", "lutnn_softpq_workspace_bytes",
+           "lutnn_encode_tree_conv2d", "lutnn_conv2d_tree", "lutnn_conv2d_rows", "lutnn_encode_conv2d", "lutnn_conv2d",
            "lutnn_auto_variant", "lutnn_status_string", "lutnn_last_error", "lutnn_version"]
 
 
@@ -94,6 +95,11 @@ def _load():
     lib.lutnn_softpq_backward.restype = i32
     lib.lutnn_softpq_backward.argtypes = [ctypes.POINTER(_CLayer), ctypes.c_float, vp, i64, i64, vp, i64, vp,
                                           vp, i64, vp, vp, ctypes.c_size_t, vp]
+    lib.lutnn_encode_tree_conv2d.restype = i32
+    lib.lutnn_encode_tree_conv2d.argtypes = [ctypes.POINTER(_CTree), vp, i64, ctypes.POINTER(_CConvGeom), vp, vp]
+    lib.lutnn_conv2d_tree.restype = i32
+    lib.lutnn_conv2d_tree.argtypes = [ctypes.POINTER(_CLayer), ctypes.POINTER(_CTree), vp, i64,
+                                      ctypes.POINTER(_CConvGeom), vp, i64, i32, vp, vp]
     lib.lutnn_conv2d_rows.restype = i64
     lib.lutnn_conv2d_rows.argtypes = [ctypes.POINTER(_CConvGeom), i64]
     lib.lutnn_encode_conv2d.restype = i32
@@ -321,6 +327,39 @@ def conv2d(layer, inp, kernel, stride=1, pad=0, variant="auto", out=None, idx_wo
         idx_workspace = torch.empty((N, layer.C), dtype=torch.uint8, device=inp.device)
     _check(LIB.lutnn_conv2d(ctypes.byref(layer.c), _ptr(inp), inp.shape[0], ctypes.byref(geom), _ptr(out),
                             out.stride(0), _variant(variant), _ptr(idx_workspace), _stream()))
+    return out
+
+
+def encode_tree_conv2d(tree, inp, kernel, stride=1, pad=0, out=None):
+    """lutnn_encode_tree_conv2d: hash encoding of the im2col rows of `inp` [B, Cin, H, W], read in place."""
+    assert inp.is_cuda and inp.dtype == torch.float32 and inp.is_contiguous() and inp.dim() == 4
+    geom = conv_geom(inp, kernel, stride, pad)
+    N = conv2d_rows(geom, inp.shape[0])
+    if N < 0:
+        raise ValueError("invalid convolution geometry")
+    if out is None:
+        out = torch.empty((N, tree.C), dtype=torch.uint8, device=inp.device)
+    assert out.is_contiguous() and out.shape == (N, tree.C) and out.dtype == torch.uint8
+    _check(LIB.lutnn_encode_tree_conv2d(ctypes.byref(tree.c), _ptr(inp), inp.shape[0], ctypes.byref(geom),
+                                        _ptr(out), _stream()))
+    return out
+
+
+def conv2d_tree(layer, tree, inp, kernel, stride=1, pad=0, variant="auto", out=None, idx_workspace=None):
+    """lutnn_conv2d_tree: the convolution with the hash encoder, Y [B*Ho*Wo, M]."""
+    assert inp.is_cuda and inp.dtype == torch.float32 and inp.is_contiguous() and inp.dim() == 4
+    geom = conv_geom(inp, kernel, stride, pad)
+    N = conv2d_rows(geom, inp.shape[0])
+    if N < 0:
+        raise ValueError("invalid convolution geometry")
+    if out is None:
+        out = torch.empty((N, layer.M), dtype=torch.float32, device=inp.device)
+    assert out.dtype == torch.float32 and out.stride(1) == 1 and out.shape == (N, layer.M)
+    if idx_workspace is None:
+        idx_workspace = torch.empty((N, layer.C), dtype=torch.uint8, device=inp.device)
+    _check(LIB.lutnn_conv2d_tree(ctypes.byref(layer.c), ctypes.byref(tree.c), _ptr(inp), inp.shape[0],
+                                 ctypes.byref(geom), _ptr(out), out.stride(0), _variant(variant),
+                                 _ptr(idx_workspace), _stream()))
     return out
 
 

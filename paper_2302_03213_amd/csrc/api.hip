@@ -425,6 +425,64 @@ lutnn_status lutnn_encode_conv2d(const lutnn_layer* layer, const float* input, i
                       "convolution encode launch");
 }
 
+namespace {
+// The shape part of a tree, as the layer view check_conv wants (it reads C and V only).
+lutnn_layer shape_of(const lutnn_tree* T) {
+    lutnn_layer l{};
+    l.C = T->C;
+    l.V = T->V;
+    l.K = 1 << T->levels;
+    l.M = 1;
+    return l;
+}
+lutnn_status check_tree_shape(const lutnn_tree* T) {
+    if (!T) return fail(LUTNN_E_NULL, "tree is NULL");
+    if (T->reserved != 0) return fail(LUTNN_E_SHAPE, "tree->reserved must be 0");
+    if (T->levels < 1 || T->levels > 8)
+        return fail(LUTNN_E_SHAPE, "tree->levels=%d outside 1..8 (indices are uint8)", T->levels);
+    return check_dims(T->C, 1 << T->levels, T->V, 1);
+}
+}  // namespace
+
+lutnn_status lutnn_encode_tree_conv2d(const lutnn_tree* tree, const float* input, int64_t B,
+                                      const lutnn_conv2d_geom* geom, uint8_t* idx, void* stream) {
+    if (lutnn_status st = check_tree_shape(tree)) return st;
+    const lutnn_layer shape = shape_of(tree);
+    lutnn::ConvGeom g;
+    int64_t N = 0;
+    if (lutnn_status st = check_conv(&shape, geom, B, &g, &N)) return st;
+    if (N == 0) return LUTNN_OK;
+    if (!tree->split_dim || !tree->threshold) return fail(LUTNN_E_NULL, "tree->split_dim or tree->threshold is NULL");
+    if (!input) return fail(LUTNN_E_NULL, "input is NULL");
+    if (!idx) return fail(LUTNN_E_NULL, "idx is NULL");
+    if (!aligned(input, 4) || !aligned(tree->split_dim, 4) || !aligned(tree->threshold, 4))
+        return fail(LUTNN_E_ALIGN, "input, split_dim and threshold must be 4-byte aligned");
+    return hip_result(lutnn::launch_encode_tree_conv(tree->split_dim, tree->threshold, tree->C, tree->levels,
+                                                     tree->V, input, B, g, idx, static_cast<hipStream_t>(stream)),
+                      "convolution tree encode launch");
+}
+
+lutnn_status lutnn_conv2d_tree(const lutnn_layer* layer, const lutnn_tree* tree, const float* input, int64_t B,
+                               const lutnn_conv2d_geom* geom, float* Y, int64_t ldy, int32_t variant,
+                               uint8_t* idx_workspace, void* stream) {
+    if (lutnn_status st = check_layer(layer)) return st;
+    if (lutnn_status st = check_tree_shape(tree)) return st;
+    if (tree->C != layer->C || tree->V != layer->V || (1 << tree->levels) != layer->K)
+        return fail(LUTNN_E_SHAPE, "tree (C=%d V=%d levels=%d) does not match layer (C=%d V=%d K=%d)", tree->C,
+                    tree->V, tree->levels, layer->C, layer->V, layer->K);
+    lutnn::ConvGeom g;
+    int64_t N = 0;
+    if (lutnn_status st = check_conv(layer, geom, B, &g, &N)) return st;
+    if (N == 0) return LUTNN_OK;
+    if (variant == LUTNN_VARIANT_FUSED)
+        return fail(LUTNN_E_UNSUPPORTED, "there is no fused kernel for the hash encoder");
+    if (!idx_workspace) return fail(LUTNN_E_NULL, "idx_workspace is NULL");
+    const int v = resolve_lookup_variant(layer, variant, idx_workspace, N);
+    if (lutnn_status st = check_lookup(layer, v, idx_workspace, Y, N, ldy)) return st;
+    if (lutnn_status st = lutnn_encode_tree_conv2d(tree, input, B, geom, idx_workspace, stream)) return st;
+    return do_lookup(layer, v, idx_workspace, N, Y, ldy, static_cast<hipStream_t>(stream));
+}
+
 lutnn_status lutnn_conv2d(const lutnn_layer* layer, const float* input, int64_t B,
                           const lutnn_conv2d_geom* geom, float* Y, int64_t ldy, int32_t variant,
                           uint8_t* idx_workspace, void* stream) {

@@ -19,6 +19,7 @@
 // for the node and one 4-byte LDS read for the value it points at; within a wavefront the node
 // reads hit at most 2^level distinct addresses.
 #include <algorithm>
+#include <type_traits>
 
 #include "encode_tile.h"
 #include "lutnn_kernels.h"
@@ -132,6 +133,33 @@ __global__ __launch_bounds__(kEncThreads) void encode_tree_tile_kernel(
     write_index_rows<CT>(is, idx, N, C, row0, c0, idx_dword_ok, tid);
 }
 
+// The same for a convolution read from its NCHW batch (Sec. 4): the tile's rows are gathered through
+// the geometry instead of being copied from a matrix.
+template <int V, int CT, int L_T>
+__global__ __launch_bounds__(kEncThreads) void encode_tree_conv_kernel(
+    const float* __restrict__ input, ConvGeom geom, const int32_t* __restrict__ split_dim,
+    const float* __restrict__ threshold, uint8_t* __restrict__ idx, int64_t N, int C, int levels_rt,
+    int idx_dword_ok) {
+    using E = EncTile<V, CT>;
+    __shared__ float xs[E::kLdsFloats];
+    __shared__ uint32_t is[kEncRows * (CT / 4)];
+    extern __shared__ uint2 tp[];
+
+    const int levels = L_T ? L_T : levels_rt;
+    const int nodes = (1 << levels) - 1;
+    const int col_tiles = (C + CT - 1) / CT;
+    const int64_t row0 = (int64_t)(blockIdx.x / col_tiles) * kEncRows;
+    const int c0 = (int)(blockIdx.x % col_tiles) * CT;
+    const int tid = threadIdx.x;
+
+    stage_nodes<V, CT>(split_dim, threshold, C, c0, nodes, tp, tid);
+    stage_x_conv<V, CT>(input, geom, N, C * V, row0, c0, xs, tid);
+    __syncthreads();
+    walk_trees<V, CT, L_T>(xs, tp, levels, nodes, C, c0, __builtin_amdgcn_readfirstlane(tid >> 6), tid & 63, is);
+    __syncthreads();
+    write_index_rows<CT>(is, idx, N, C, row0, c0, idx_dword_ok, tid);
+}
+
 // Any V: one thread per sub-vector, everything from global memory.
 __global__ __launch_bounds__(kEncThreads) void encode_tree_generic_kernel(
     const float* __restrict__ X, int64_t ldx, const int32_t* __restrict__ split_dim,
@@ -189,7 +217,50 @@ hipError_t launch_tree(const int32_t* split_dim, const float* threshold, int C, 
     return launch_tree_ct<V, CT>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
 }
 
+template <int V>
+hipError_t launch_tree_conv(const int32_t* split_dim, const float* threshold, int C, int levels,
+                            const float* input, int64_t N, const ConvGeom& g, uint8_t* idx, hipStream_t s) {
+    // quarter-width tiles when the grid is small or the nodes of a full tile exceed 24 KiB, as above
+    constexpr int CTF = enc_tile_codebooks(V);
+    constexpr int CTS = CTF / 4 >= 4 ? CTF / 4 : 4;
+    const int64_t row_tiles = (N + kEncRows - 1) / kEncRows;
+    const size_t full_node_bytes = (size_t)CTF * ((1u << levels) - 1) * sizeof(uint2);
+    const bool small = CTS < CTF && (row_tiles * ((C + CTF - 1) / CTF) < 1024 || full_node_bytes > 24 * 1024);
+    const int idx_dword_ok = (C % 4 == 0) && ((reinterpret_cast<uintptr_t>(idx) & 3) == 0);
+    auto go = [&](auto ct_c) {
+        constexpr int CT = decltype(ct_c)::value;
+        const int64_t blocks = row_tiles * ((C + CT - 1) / CT);
+        if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+        const size_t node_bytes = (size_t)CT * ((1u << levels) - 1) * sizeof(uint2);
+        if (levels == 4)
+            hipLaunchKernelGGL((encode_tree_conv_kernel<V, CT, 4>), dim3((unsigned)blocks), dim3(kEncThreads),
+                               node_bytes, s, input, g, split_dim, threshold, idx, N, C, levels, idx_dword_ok);
+        else
+            hipLaunchKernelGGL((encode_tree_conv_kernel<V, CT, 0>), dim3((unsigned)blocks), dim3(kEncThreads),
+                               node_bytes, s, input, g, split_dim, threshold, idx, N, C, levels, idx_dword_ok);
+        return hipGetLastError();
+    };
+    return small ? go(std::integral_constant<int, CTS>{}) : go(std::integral_constant<int, CTF>{});
+}
+
 }  // namespace
+
+// Sub-vector lengths as for the distance encoder's convolution form.
+hipError_t launch_encode_tree_conv(const int32_t* split_dim, const float* threshold, int C, int levels,
+                                   int V, const float* input, int64_t B, const ConvGeom& g, uint8_t* idx,
+                                   hipStream_t s) {
+    const int64_t N = B * g.Ho * g.Wo;
+    switch (V) {
+        case 1: return launch_tree_conv<1>(split_dim, threshold, C, levels, input, N, g, idx, s);
+        case 2: return launch_tree_conv<2>(split_dim, threshold, C, levels, input, N, g, idx, s);
+        case 3: return launch_tree_conv<3>(split_dim, threshold, C, levels, input, N, g, idx, s);
+        case 4: return launch_tree_conv<4>(split_dim, threshold, C, levels, input, N, g, idx, s);
+        case 8: return launch_tree_conv<8>(split_dim, threshold, C, levels, input, N, g, idx, s);
+        case 9: return launch_tree_conv<9>(split_dim, threshold, C, levels, input, N, g, idx, s);
+        case 16: return launch_tree_conv<16>(split_dim, threshold, C, levels, input, N, g, idx, s);
+        default: return hipErrorInvalidValue;
+    }
+}
 
 hipError_t launch_encode_tree(const int32_t* split_dim, const float* threshold, int C, int levels,
                               int V, const float* X, int64_t N, int64_t ldx, uint8_t* idx,

@@ -42,6 +42,10 @@ hipError_t launch_softpq_backward(const float* P, int C, int K, int V, float t, 
                                   int64_t ldx, const float* Z, int64_t ldz, float* dP, float* dX,
                                   int64_t lddx, float* dt, float* workspace, hipStream_t s);
 
+hipError_t launch_encode_tree_conv(const int32_t* split_dim, const float* threshold, int C, int levels,
+                                   int V, const float* input, int64_t B, const ConvGeom& g, uint8_t* idx,
+                                   hipStream_t s);
+
 // Eq. 3 + Sec. 3.3.
 hipError_t launch_build_table_f32(const float* P, const float* W, int64_t ldw, int C, int K, int V,
                                   int M, float* T, hipStream_t s);
