@@ -388,9 +388,7 @@ __global__ __launch_bounds__(64 * SPLIT) void lookup_gather_split_kernel(
     const TT* __restrict__ tcol = T + (col_ok ? m : 0);
 
     Acc a[4] = {0, 0, 0, 0};
-    auto add = [&](int c, int k) {
-        k = k < K ? k : K - 1;
-        const Vec v = *reinterpret_cast<const Vec*>(tcol + ((size_t)c * K + k) * M);
+    auto accumulate = [&](const Vec& v) {
         if constexpr (I8) {
             a[0] += (int32_t)(int8_t)(v & 0xffu);
             a[1] += (int32_t)(int8_t)((v >> 8) & 0xffu);
@@ -403,10 +401,31 @@ __global__ __launch_bounds__(64 * SPLIT) void lookup_gather_split_kernel(
             a[3] += v.w;
         }
     };
+    auto add = [&](int c, int k) {
+        k = k < K ? k : K - 1;
+        accumulate(*reinterpret_cast<const Vec*>(tcol + ((size_t)c * K + k) * M));
+    };
     // codebooks [c, c_end) of this wavefront; per_wave is a multiple of 4, so dword index loads stay aligned
     int c = w * per_wave;
     const int c_end = min(C, c + per_wave);
     if (IDX_DWORD) {
+        // sixteen table rows in flight at a time: with so few wavefronts the loop is a latency chain,
+        // and a wait per group of four codebooks would be most of the kernel
+        for (; c + 16 <= c_end; c += 16) {
+            uint32_t word[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                word[q] = (uint32_t)__builtin_amdgcn_readfirstlane(*reinterpret_cast<const uint32_t*>(irow + c + 4 * q));
+            Vec v[16];
+#pragma unroll
+            for (int b = 0; b < 16; ++b) {
+                int k = (int)((word[b >> 2] >> (8 * (b & 3))) & 0xffu);
+                k = k < K ? k : K - 1;
+                v[b] = *reinterpret_cast<const Vec*>(tcol + ((size_t)(c + b) * K + k) * M);
+            }
+#pragma unroll
+            for (int b = 0; b < 16; ++b) accumulate(v[b]);
+        }
         for (; c + 4 <= c_end; c += 4) {
             const uint32_t word =
                 (uint32_t)__builtin_amdgcn_readfirstlane(*reinterpret_cast<const uint32_t*>(irow + c));
