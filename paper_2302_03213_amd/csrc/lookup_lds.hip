@@ -319,9 +319,7 @@ __global__ __launch_bounds__(kThreads) void lookup_gather_kernel(
 
     float fa[4] = {0.f, 0.f, 0.f, 0.f};
     int32_t ia[4] = {0, 0, 0, 0};
-    auto add = [&](int c, int k) {
-        k = k < K ? k : K - 1;
-        const Vec v = *reinterpret_cast<const Vec*>(tcol + ((size_t)c * K + k) * M);
+    auto accumulate = [&](const Vec& v) {
         if constexpr (I8) {
             ia[0] += (int32_t)(int8_t)(v & 0xffu);
             ia[1] += (int32_t)(int8_t)((v >> 8) & 0xffu);
@@ -334,8 +332,27 @@ __global__ __launch_bounds__(kThreads) void lookup_gather_kernel(
             fa[3] += v.w;
         }
     };
+    auto add = [&](int c, int k) {
+        k = k < K ? k : K - 1;
+        accumulate(*reinterpret_cast<const Vec*>(tcol + ((size_t)c * K + k) * M));
+    };
     int c = 0;
     if (IDX_DWORD) {
+        // sixteen table rows in flight at a time (added in codebook order all the same)
+        for (; c + 16 <= C; c += 16) {
+            uint32_t word[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) word[q] = uni(*reinterpret_cast<const uint32_t*>(irow + c + 4 * q));
+            Vec v[16];
+#pragma unroll
+            for (int b = 0; b < 16; ++b) {
+                int k = (int)((word[b >> 2] >> (8 * (b & 3))) & 0xffu);
+                k = k < K ? k : K - 1;
+                v[b] = *reinterpret_cast<const Vec*>(tcol + ((size_t)(c + b) * K + k) * M);
+            }
+#pragma unroll
+            for (int b = 0; b < 16; ++b) accumulate(v[b]);
+        }
         for (; c + 4 <= C; c += 4) {
             const uint32_t word = uni(*reinterpret_cast<const uint32_t*>(irow + c));
 #pragma unroll
