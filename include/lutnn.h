@@ -27,7 +27,10 @@
  *     (lutnn_softpq_backward still writes its zero sums).
  *   - Inputs are assumed finite.  Non-finite activations never cause an out-of-range
  *     index or an out-of-bounds access; the index chosen for them is unspecified.
- *   - Outputs must not alias inputs.
+ *   - Outputs must not alias inputs.  Some lookups use Y itself as integer scratch before the final
+ *     values are written, so Y must not be read by anyone else while a call on it is in flight.
+ *   - The library keeps no state between calls (the last-error text is per host thread): calls from
+ *     several host threads and on several streams may run concurrently.
  */
 #ifndef LUTNN_H
 #define LUTNN_H
