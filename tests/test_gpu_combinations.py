@@ -218,3 +218,38 @@ def test_four_million_rows_cross_the_32_bit_byte_offsets(lut):
     got = host(dX[rows_d])
     assert np.abs(got - dX_ref).max() <= 5e-5 * np.abs(dX_ref).max()
     assert np.abs(host(dP) - dP_ref).max() <= 5e-5 * np.abs(dP_ref).max()
+
+
+def test_two_host_threads_on_two_streams(lut):
+    """No state between calls: two host threads, each on its own stream with its own layer, get the
+    results of a serial run (the second uses the small-batch path whose Y doubles as scratch)."""
+    import threading
+    cases = []
+    for seed, (N, C, M) in enumerate([(700, 64, 320), (64, 1024, 512)]):
+        w = wl.make_layer("t", N, C, 16, 4, M, "i8", seed=50 + seed)
+        layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8, bias=dev(w.bias))
+        X = dev(w.X)
+        cases.append((layer, X, host(lut.linear(layer, X))))
+    torch.cuda.synchronize()
+    results, errors = [None, None], []
+
+    def work(i):
+        try:
+            layer, X, _ = cases[i]
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                for _ in range(40):
+                    Y = lut.linear(layer, X)
+                stream.synchronize()
+            results[i] = host(Y)
+        except Exception as e:  # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for i in range(2):
+        np.testing.assert_array_equal(results[i], cases[i][2])
