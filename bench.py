@@ -233,7 +233,7 @@ def main():
     # ---- per-kernel durations with HIP events on the launch stream (same kernels, same inputs):
     # encode and lookup of the FIRST (for bert_layer: every) layer, split as lutnn_linear splits them
     enc_ms, look_ms, fused_ms = [], [], []
-    variant_used = {}
+    variant_used, spread = {}, {}
     for (w, layer, Xs, Ys, ws) in dev_layers:
         fused = args.variant == "fused"
         if fused:
@@ -243,6 +243,7 @@ def main():
         else:
             variant_used[w.name] = args.variant
         e_acc = l_acc = f_acc = 0.0
+        e_all, l_all = [], []
         for i in range(args.steps):
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
             if fused:
@@ -258,8 +259,13 @@ def main():
                 lut.lookup(layer, ws, variant_used[w.name], out=Ys[i & 1])
                 ev[2].record()
                 ev[2].synchronize()
-                e_acc += ev[0].elapsed_time(ev[1])
-                l_acc += ev[1].elapsed_time(ev[2])
+                e_all.append(ev[0].elapsed_time(ev[1]))
+                l_all.append(ev[1].elapsed_time(ev[2]))
+                e_acc += e_all[-1]
+                l_acc += l_all[-1]
+        spread[w.name] = ({"encode_ms_min": round(min(e_all), 4), "encode_ms_median": round(float(np.median(e_all)), 4),
+                           "lookup_ms_min": round(min(l_all), 4), "lookup_ms_median": round(float(np.median(l_all)), 4)}
+                          if e_all else {})
         enc_ms.append(e_acc / args.steps)
         look_ms.append(l_acc / args.steps)
         fused_ms.append(f_acc / args.steps)
@@ -335,6 +341,7 @@ def main():
             kernels[w.name] = {"encode_ms": round(e, 4), "lookup_ms": round(l, 4),
                                "encode_hbm_GBps": round(eb / (e * 1e-3) / 1e9, 1),
                                "encode_hbm_frac": round(eb / (e * 1e-3) / cost.PEAK_HBM_BYTES_PER_S, 4)}
+            kernels[w.name].update(spread[w.name])
 
     # ---- CPU baseline: the oracle, as it stands, on a bounded row sample of the same workload
     cpu = None
