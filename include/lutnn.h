@@ -71,7 +71,9 @@ typedef enum {
                                 twice the matrix rate.  Needs C % 32 == 0, 16-byte aligned idx.
                                 The environment variable LUTNN_SMFMAC_TILE_ROWS (128, 256, 384 or
                                 512), read at every call, pins the rows per workgroup tile that the
-                                library otherwise prices itself: a tuning knob, results are the same */
+                                library otherwise prices itself; LUTNN_SMFMAC_SPLIT (0 or 1) likewise
+                                pins whether the codebooks of a tile are shared out over several
+                                workgroups: tuning knobs, results are the same                      */
 } lutnn_variant;
 
 /*

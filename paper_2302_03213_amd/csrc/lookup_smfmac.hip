@@ -502,11 +502,14 @@ hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias
     // Few tiles and many codebooks (a small batch on a wide layer): every workgroup would stream
     // 2 KiB x C of table alone while most of the chip idles.  Split the codebooks over `splits`
     // workgroups per tile instead; their int32 partial sums meet in Y through atomics, between a
-    // pass that zeroes Y and one that dequantises it.  Worth its two extra launches and its atomics
-    // from 512 codebooks on and up to 128 rows (measured at C = 1024, M = 4096: 0.025 against
-    // 0.035 ms per call at 33 rows, equal at 256, slower beyond); each share keeps at least 64
-    // codebooks.
-    if (tiles <= kComputeUnits / 2 && C >= 512 && N <= 128) {
+    // pass that zeroes Y and one that dequantises it.  What it saves is the serial walk over the
+    // codebooks, ~24 ns per codebook and workgroup, times (1 - 1/splits); what it costs is two more
+    // launches (~6 us) and the atomics and passes over Y, ~14 us per million outputs (fitted to
+    // sweeps over 129-4096 rows at (C, M) = (1536, 768), (1024, 4096), (512, 1024): e.g. 0.022
+    // against 0.042 ms at 512 rows of the first, break-even at 2048 rows; break-even at 256 rows of
+    // the second).  Each share keeps at least 64 codebooks.  LUTNN_SMFMAC_SPLIT = 0 | 1 pins the
+    // decision (sweeps, and tests that must reach both paths).
+    if (tiles <= kComputeUnits / 2 && C >= 512) {
         const int supers = C / 32;
         int splits = 1;
         for (int cand = (int)std::min<int64_t>(16, kComputeUnits / tiles); cand > 1; --cand)
@@ -514,6 +517,14 @@ hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias
                 splits = cand;
                 break;
             }
+        const double saved_us = 0.024 * C * (1.0 - 1.0 / splits);
+        const double cost_us = 6.0 + 14e-6 * (double)N * M;
+        bool split = saved_us > cost_us;
+        if (const char* e = std::getenv("LUTNN_SMFMAC_SPLIT")) {
+            if (e[0] == '0' && e[1] == 0) split = false;
+            if (e[0] == '1' && e[1] == 0) split = true;
+        }
+        if (!split) splits = 1;
         if (splits > 1) {
             const dim3 cells((unsigned)((M + 255) / 256), (unsigned)N);
             hipLaunchKernelGGL(zero_rows_kernel, cells, dim3(256), 0, s, Y, M, ldy);

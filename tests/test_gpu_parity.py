@@ -173,13 +173,22 @@ def test_lookup_smfmac_every_tile_height(lut, monkeypatch, rows, N, C, K, M):
     np.testing.assert_array_equal(host(lut.lookup(layer, dev(idx), "smfmac")), ol.lookup(idx))
 
 
-@pytest.mark.parametrize("N,C,K,M", [(33, 1024, 16, 4096), (100, 512, 16, 300), (128, 544, 16, 1000),
-                                     (64, 576, 7, 130), (1, 2048, 16, 256), (77, 1536, 16, 768)])
-def test_lookup_smfmac_codebooks_split_over_workgroups(lut, N, C, K, M):
+@pytest.mark.parametrize("N,C,K,M,rows", [(33, 1024, 16, 4096, 0), (100, 512, 16, 300, 0),
+                                          (128, 544, 16, 1000, 0), (64, 576, 7, 130, 0),
+                                          (1, 2048, 16, 256, 0), (77, 1536, 16, 768, 0),
+                                          (700, 1536, 16, 768, 0), (1029, 512, 16, 260, 0),
+                                          (700, 1536, 16, 768, 256), (1029, 1024, 16, 260, 384),
+                                          (1300, 1536, 16, 300, 512)])
+def test_lookup_smfmac_codebooks_split_over_workgroups(lut, monkeypatch, N, C, K, M, rows):
     """Few tiles, many codebooks: several workgroups share an output tile, each with a range of the
     codebooks, and add int32 partial sums into Y (zeroed before, dequantised after).  Bit-exact, with
     and without bias, into a strided Y whose guard band must stay untouched.  (544 codebooks = 17
-    groups of 32 cannot be split evenly: that shape takes the unsplit kernel.)"""
+    groups of 32 cannot be split evenly: that shape takes the unsplit kernel.)  The split is pinned
+    through the library's tuning variable so that the test does not depend on its price list; the
+    last cases also pin the tile height to reach the taller split instances."""
+    monkeypatch.setenv("LUTNN_SMFMAC_SPLIT", "1")
+    if rows:
+        monkeypatch.setenv("LUTNN_SMFMAC_TILE_ROWS", str(rows))
     w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=N + C + M)
     ol = OracleLayer(w)
     ol.q = wl.random_table_i8(C, K, M, seed=C + M)
