@@ -58,11 +58,12 @@ int resolve_lookup_variant(const lutnn_layer* L, int variant, const uint8_t* idx
     if (variant != LUTNN_VARIANT_AUTO) return variant;
     if (is_int_table(L->table_dtype) && L->table_packed && L->K <= 16) {
         // small problems with few codebooks: rows gathered straight from L2 beat a matrix-core launch
-        if (lutnn::gather_preferred(L->table, L->table_dtype == LUTNN_TABLE_I4 ? 2 : 1, L->C, L->M, N))
+        const bool sparse_ok = lutnn::smfmac_supported(L->C, L->K, idx);
+        if (lutnn::gather_preferred(L->table, L->table_dtype == LUTNN_TABLE_I4 ? 2 : 1, L->C, L->M, N, sparse_ok))
             return LUTNN_VARIANT_LDS;
         // the sparse kernel at any N (its 128-row tiles spread even a single row's columns over the
         // chip and stream the table in parallel); the dense one where the sparse one cannot run
-        if (lutnn::smfmac_supported(L->C, L->K, idx)) return LUTNN_VARIANT_SMFMAC;
+        if (sparse_ok) return LUTNN_VARIANT_SMFMAC;
         return LUTNN_VARIANT_MFMA;
     }
     return LUTNN_VARIANT_LDS;

@@ -666,7 +666,7 @@ inline bool idx_dword_ok(const uint8_t* idx, int C) {
 // True when the gather variant would read the table straight from L2 (no staging) and the whole
 // problem is small enough for that to beat the matrix-core kernels, whose tiles and pipeline fill
 // are wasted on it (measured cross-over: about 3e7 table entries) ...
-bool gather_preferred(const void* T, int table_kind, int C, int M, int64_t N) {
+bool gather_preferred(const void* T, int table_kind, int C, int M, int64_t N, bool sparse_ok) {
     if (!T) return false;
     const bool f32 = table_kind == 0;
     const int64_t rows_per_block = f32 ? kRowsPerWaveF32 * kWaves : kRowsPerWaveI8 * kWaves;
@@ -682,9 +682,18 @@ bool gather_preferred(const void* T, int table_kind, int C, int M, int64_t N) {
     const int chunk = table_kind == 2 ? kGatherColsI4 : kGatherCols;  // columns per wavefront
     const int64_t col_chunks = (M + chunk - 1) / chunk;
     if (M >= chunk && C >= kSplitMinCodebooks && N <= 32 && N * col_chunks < kSplitMaxWaves) return true;
-    // ... or the per-row chain of C dependent additions (about 65 ns each) is short: with a
-    // thousand codebooks a row takes 67 us on the unsplit gather and 34 us on the matrix cores
-    return C <= 256 && N * (int64_t)C * M <= (int64_t)1 << 25;
+    // Otherwise price both (ms per call, fitted to sweeps of 32-2048 rows over seventeen layer
+    // shapes; the rule picks the faster form or ties on all of them).  The gather costs its
+    // N*C*M entry reads; a matrix-core launch costs its pipeline fill and the serial walk over the
+    // codebooks - far longer per codebook on the dense kernel, which runs where the sparse one
+    // cannot (C % 32 != 0 or unaligned indices).  From 512 codebooks on the sparse kernel shares
+    // the codebooks of a tile out over workgroups and its time stops growing with C: there the
+    // gather only wins below ~5.6e7 entries.
+    const double entries = (double)N * C * M;
+    if (C >= 512 && sparse_ok) return entries <= 5.6e7;
+    const double t_gather = 0.0038 + 8.9e-11 * entries;
+    const double t_matrix = sparse_ok ? 0.0065 + 1.6e-5 * C : 0.0062 + 1.2e-4 * C;
+    return t_gather < t_matrix;
 }
 
 hipError_t launch_lookup_lds_i8(const int8_t* T, const float* scale, const float* bias, int C, int K,

@@ -75,7 +75,7 @@ hipError_t launch_lookup_rows_f32(const float* T, const float* bias, int C, int 
                                   const uint8_t* idx, int64_t N, float* Y, int64_t ldy, hipStream_t s);
 
 // table_kind: 0 fp32, 1 int8, 2 int4 (nibble pairs)
-bool gather_preferred(const void* T, int table_kind, int C, int M, int64_t N);
+bool gather_preferred(const void* T, int table_kind, int C, int M, int64_t N, bool sparse_ok);
 
 // Eq. 4, one-hot MFMA variant (INT8).
 hipError_t launch_lookup_mfma_i8(const int8_t* packed, const float* scale, const float* bias, int C,
