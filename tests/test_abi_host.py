@@ -302,6 +302,14 @@ def test_auto_variant_rule(lut):
     small = _layer(lut, C=64, M=64)  # few table entries: rows gathered straight from L2
     assert L.lutnn_auto_variant(ctypes.byref(small), vp(0x30000), 3136) == lut.VARIANT_LDS
     assert L.lutnn_auto_variant(ctypes.byref(small), vp(0x30000), 1 << 20) == lut.VARIANT_SMFMAC
+    # priced against the launch it would replace: a BERT attention-output shape takes the gather up
+    # to a few hundred rows, and where only the dense kernel can run (C % 32 != 0) for longer
+    attn = _layer(lut, C=384, M=768)
+    assert L.lutnn_auto_variant(ctypes.byref(attn), vp(0x30000), 128) == lut.VARIANT_LDS
+    assert L.lutnn_auto_variant(ctypes.byref(attn), vp(0x30000), 512) == lut.VARIANT_SMFMAC
+    v16 = _layer(lut, C=48, M=3072)
+    assert L.lutnn_auto_variant(ctypes.byref(v16), vp(0x30000), 512) == lut.VARIANT_LDS
+    assert L.lutnn_auto_variant(ctypes.byref(v16), vp(0x30000), 2048) == lut.VARIANT_MFMA
     f32 = _layer(lut, table_dtype=lut.TABLE_F32, C=128, M=512)
     assert L.lutnn_auto_variant(ctypes.byref(f32), vp(0x30000), 256) == lut.VARIANT_LDS
     wide_k = _layer(lut, K=32, C=64, M=4096)
