@@ -162,12 +162,19 @@ LUTNN_API lutnn_status lutnn_lookup(const lutnn_layer* layer, const uint8_t* idx
 /*
  * The whole operator: encode then lookup, Y ~= X . B (+ bias).
  *
- *   variant FUSED  one kernel; the indices stay in LDS.  `idx_workspace` is ignored.
+ *   variant FUSED  one kernel; the indices stay in LDS.  `idx_workspace` is ignored.  Two forms: a
+ *                  one-launch kernel for small problems (fp32 / INT8 table in its plain layout,
+ *                  M % 4 == 0), taken where it is the faster one or the only one that can run,
+ *                  and a tile kernel on the matrix cores (INT8: needs table_packed).  The
+ *                  environment variable LUTNN_FUSED_KERNEL (small or tile) pins the form.
  *   variant LDS / MFMA / SMFMAC  lutnn_encode into idx_workspace, then lutnn_lookup with that
  *                  variant.
- *   variant AUTO   with a workspace: lutnn_encode, then lutnn_lookup with AUTO (the fastest
- *                  lookup for the shape); without one: FUSED, if a fused kernel exists.
- *   idx_workspace  [N][C] uint8 device scratch; may be NULL only for FUSED / AUTO.
+ *   variant AUTO   the one-launch kernel where the problem is so small that a second launch would
+ *                  be most of the time; else, with a workspace: lutnn_encode, then lutnn_lookup
+ *                  with AUTO (the fastest lookup for the shape); without one: FUSED, if a fused
+ *                  kernel exists.  lutnn_linear_auto_variant reports the choice.
+ *   idx_workspace  [N][C] uint8 device scratch (contents unspecified afterwards); may be NULL
+ *                  only for FUSED / AUTO.
  * Errors: as lutnn_encode and lutnn_lookup.
  */
 LUTNN_API lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, int64_t N,
@@ -325,6 +332,14 @@ LUTNN_API lutnn_status lutnn_conv2d_tree(const lutnn_layer* layer, const lutnn_t
  * NULL workspace AUTO means LUTNN_VARIANT_FUSED instead.  Returns -1 for a NULL layer.
  */
 LUTNN_API int32_t lutnn_auto_variant(const lutnn_layer* layer, const uint8_t* idx, int64_t N);
+
+/*
+ * Host: the same for lutnn_linear(layer, X, N, ..., LUTNN_VARIANT_AUTO, idx_workspace, ...):
+ * LUTNN_VARIANT_FUSED where one launch does both steps, else what lutnn_auto_variant returns for
+ * the lookup that follows the encoding.  Returns -1 for a NULL layer.
+ */
+LUTNN_API int32_t lutnn_linear_auto_variant(const lutnn_layer* layer, const uint8_t* idx_workspace,
+                                            int64_t N);
 
 /* Host: static name of a status code. */
 LUTNN_API const char* lutnn_status_string(int32_t status);

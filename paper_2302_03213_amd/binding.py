@@ -31,7 +31,7 @@ EXPORTS = ["lutnn_table_bytes", "lutnn_packed_bytes", "lutnn_build_table", "lutn
            "lutnn_lookup", "lutnn_linear", "lutnn_encode_tree", "lutnn_linear_tree",
            "lutnn_softpq_backward", "lutnn_softpq_workspace_bytes",
            "lutnn_encode_tree_conv2d", "lutnn_conv2d_tree", "lutnn_conv2d_rows", "lutnn_encode_conv2d", "lutnn_conv2d",
-           "lutnn_auto_variant", "lutnn_status_string", "lutnn_last_error", "lutnn_version"]
+           "lutnn_auto_variant", "lutnn_linear_auto_variant", "lutnn_status_string", "lutnn_last_error", "lutnn_version"]
 
 
 class LutnnError(RuntimeError):
@@ -109,6 +109,8 @@ def _load():
                                  i32, vp, vp]
     lib.lutnn_auto_variant.restype = i32
     lib.lutnn_auto_variant.argtypes = [ctypes.POINTER(_CLayer), vp, i64]
+    lib.lutnn_linear_auto_variant.restype = i32
+    lib.lutnn_linear_auto_variant.argtypes = [ctypes.POINTER(_CLayer), vp, i64]
     lib.lutnn_status_string.restype = ctypes.c_char_p
     lib.lutnn_status_string.argtypes = [i32]
     lib.lutnn_last_error.restype = ctypes.c_char_p
@@ -366,6 +368,13 @@ def conv2d_tree(layer, tree, inp, kernel, stride=1, pad=0, variant="auto", out=N
 def auto_variant(layer, N, idx=None):
     """lutnn_auto_variant: name of the lookup variant that "auto" stands for at this shape."""
     code = LIB.lutnn_auto_variant(ctypes.byref(layer.c), _ptr(idx), N)
+    return {v: k for k, v in VARIANTS.items()}[code]
+
+
+def linear_auto_variant(layer, N, idx_workspace=None):
+    """lutnn_linear_auto_variant: name of what lutnn_linear runs for "auto" at this shape ("fused" =
+    one launch does both steps)."""
+    code = LIB.lutnn_linear_auto_variant(ctypes.byref(layer.c), _ptr(idx_workspace), N)
     return {v: k for k, v in VARIANTS.items()}[code]
 
 

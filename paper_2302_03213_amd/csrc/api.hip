@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 #include "lutnn.h"
@@ -339,6 +340,57 @@ lutnn_status lutnn_lookup(const lutnn_layer* layer, const uint8_t* idx, int64_t 
     return do_lookup(layer, v, idx, N, Y, ldy, static_cast<hipStream_t>(stream));
 }
 
+namespace {
+
+inline int small_table_kind(const lutnn_layer* L) {
+    return L->table_dtype == LUTNN_TABLE_F32 ? 0 : L->table_dtype == LUTNN_TABLE_I8 ? 1 : 2;
+}
+
+// The one-launch kernel is worth it where the lookup it replaces would be the gather anyway (the
+// indices it would see are 16-byte aligned in LDS, so the sparse kernel counts as available when
+// the shape allows it).
+bool small_preferred(const lutnn_layer* L, int64_t N) {
+    const int kind = small_table_kind(L);
+    if (kind == 2) return false;
+    const bool sparse_ok = is_int_table(L->table_dtype) && L->table_packed && L->K <= 16 && L->C % 32 == 0;
+    const bool matrix_ok = is_int_table(L->table_dtype) && L->table_packed && L->K <= 16;
+    const bool gather_wins = !matrix_ok || lutnn::gather_preferred(L->table, kind, L->C, L->M, N, sparse_ok);
+    return lutnn::linear_small_preferred(L->table, kind, L->C, L->K, L->V, L->M, N, gather_wins);
+}
+
+// Which of the two one-kernel forms FUSED runs: the one-launch kernel for small problems where it
+// is the faster one, or where the tile kernel cannot run at all; LUTNN_FUSED_KERNEL = small | tile
+// pins the choice (tests that must reach both).
+bool fused_takes_small_kernel(const lutnn_layer* L, int64_t N) {
+    const int kind = small_table_kind(L);
+    const bool can_small = lutnn::linear_small_supported(L->table, kind, L->C, L->K, L->V, L->M);
+    const bool can_tile = lutnn::fused_supported(L->C, L->K, L->V, L->M, L->table_dtype) &&
+                          (L->table_dtype == LUTNN_TABLE_F32 ? L->table != nullptr : L->table_packed != nullptr);
+    if (const char* e = std::getenv("LUTNN_FUSED_KERNEL")) {
+        if (std::strcmp(e, "small") == 0 && can_small) return true;
+        if (std::strcmp(e, "tile") == 0 && can_tile) return false;
+    }
+    if (!can_small) return false;
+    return !can_tile || small_preferred(L, N);
+}
+
+// What lutnn_linear runs for `variant`.  AUTO: one launch where the problem is small enough that
+// the second launch would be the larger part of the time; else encode once, then the fastest
+// lookup - over conv-like, BERT-like and FC shapes the two launches are never slower than the tile
+// form of the fused kernel (its 64-row workgroups encode all C codebooks serially and re-stream the
+// table per row block).  Without a workspace for the indices a fused kernel is the only choice.
+int resolve_linear_variant(const lutnn_layer* L, int variant, const uint8_t* idx_workspace, int64_t N) {
+    if (variant != LUTNN_VARIANT_AUTO) return variant;
+    if (small_preferred(L, N)) return LUTNN_VARIANT_FUSED;
+    const bool tile_ok = lutnn::fused_supported(L->C, L->K, L->V, L->M, L->table_dtype) &&
+                         (L->table_dtype == LUTNN_TABLE_F32 ? L->table != nullptr : L->table_packed != nullptr);
+    const bool small_ok = lutnn::linear_small_supported(L->table, small_table_kind(L), L->C, L->K, L->V, L->M);
+    if ((tile_ok || small_ok) && !idx_workspace) return LUTNN_VARIANT_FUSED;
+    return resolve_lookup_variant(L, LUTNN_VARIANT_AUTO, idx_workspace, N);
+}
+
+}  // namespace
+
 lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, int64_t N, int64_t ldx, float* Y,
                           int64_t ldy, int32_t variant, uint8_t* idx_workspace, void* stream) {
     if (lutnn_status st = check_layer(layer)) return st;
@@ -347,30 +399,30 @@ lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, int64_t N, i
     hipStream_t s = static_cast<hipStream_t>(stream);
     const lutnn_layer* L = layer;
 
-    int v = variant;
-    if (v == LUTNN_VARIANT_AUTO) {
-        // Encode once, then the fastest lookup: measured over conv-like, BERT-like and FC shapes the
-        // two launches are never slower than the fused kernel (its 64-row workgroups encode all C
-        // codebooks serially and re-stream the table per row block).  Without a workspace for the
-        // indices the fused kernel is the only choice.
-        const bool fused_ok = lutnn::fused_supported(L->C, L->K, L->V, L->M, L->table_dtype) &&
-                              (L->table_dtype == LUTNN_TABLE_F32 ? L->table != nullptr
-                                                                 : L->table_packed != nullptr);
-        if (fused_ok && !idx_workspace)
-            v = LUTNN_VARIANT_FUSED;
-        else
-            v = resolve_lookup_variant(L, LUTNN_VARIANT_AUTO, idx_workspace, N);
-    }
+    const int v = resolve_linear_variant(L, variant, idx_workspace, N);
 
     if (v == LUTNN_VARIANT_FUSED) {
         if (!Y) return fail(LUTNN_E_NULL, "Y is NULL");
         if (ldy < L->M) return fail(LUTNN_E_SHAPE, "ldy=%lld is smaller than M=%d", (long long)ldy, L->M);
         if (!aligned(Y, 4)) return fail(LUTNN_E_ALIGN, "Y must be 4-byte aligned");
+        if (L->bias && !aligned(L->bias, 4)) return fail(LUTNN_E_ALIGN, "bias must be 4-byte aligned");
+        if (is_int_table(L->table_dtype) && !L->scale)
+            return fail(LUTNN_E_NULL, "an integer table needs layer->scale");
+        if (fused_takes_small_kernel(L, N)) {
+            if (L->table_dtype == LUTNN_TABLE_I8)
+                return hip_result(lutnn::launch_linear_small_i8(L->centroids, static_cast<const int8_t*>(L->table),
+                                                                L->scale, L->bias, L->C, L->K, L->V, L->M, X, N,
+                                                                ldx, Y, ldy, s),
+                                  "one-launch linear");
+            return hip_result(lutnn::launch_linear_small_f32(L->centroids, static_cast<const float*>(L->table),
+                                                             L->bias, L->C, L->K, L->V, L->M, X, N, ldx, Y, ldy,
+                                                             s),
+                              "one-launch linear");
+        }
         if (!lutnn::fused_supported(L->C, L->K, L->V, L->M, L->table_dtype))
             return fail(LUTNN_E_UNSUPPORTED, "no fused kernel for C=%d K=%d V=%d M=%d dtype=%d", L->C, L->K,
                         L->V, L->M, L->table_dtype);
         if (is_int_table(L->table_dtype)) {
-            if (!L->scale) return fail(LUTNN_E_NULL, "an integer table needs layer->scale");
             if (!L->table_packed) return fail(LUTNN_E_NULL, "the fused INT8 kernel needs layer->table_packed");
             if (!aligned(L->table_packed, 16))
                 return fail(LUTNN_E_ALIGN, "table_packed must be 16-byte aligned");
@@ -509,6 +561,11 @@ lutnn_status lutnn_conv2d(const lutnn_layer* layer, const float* input, int64_t 
 int32_t lutnn_auto_variant(const lutnn_layer* layer, const uint8_t* idx, int64_t N) {
     if (!layer) return -1;
     return resolve_lookup_variant(layer, LUTNN_VARIANT_AUTO, idx, N);
+}
+
+int32_t lutnn_linear_auto_variant(const lutnn_layer* layer, const uint8_t* idx_workspace, int64_t N) {
+    if (!layer) return -1;
+    return resolve_linear_variant(layer, LUTNN_VARIANT_AUTO, idx_workspace, N);
 }
 
 const char* lutnn_last_error(void) { return g_err; }

@@ -97,4 +97,15 @@ hipError_t launch_linear_fused_f32(const float* P, const float* T, const float* 
                                    int V, int M, const float* X, int64_t N, int64_t ldx, float* Y,
                                    int64_t ldy, hipStream_t s);
 
+// Eq. 2 + Eq. 4 in one launch for small problems, reading the plain table (table_kind 0 fp32, 1 int8).
+bool linear_small_supported(const void* T, int table_kind, int C, int K, int V, int M);
+bool linear_small_preferred(const void* T, int table_kind, int C, int K, int V, int M, int64_t N,
+                            bool gather_wins);
+hipError_t launch_linear_small_f32(const float* P, const float* T, const float* bias, int C, int K, int V,
+                                   int M, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
+                                   hipStream_t s);
+hipError_t launch_linear_small_i8(const float* P, const int8_t* T, const float* scale, const float* bias, int C,
+                                  int K, int V, int M, const float* X, int64_t N, int64_t ldx, float* Y,
+                                  int64_t ldy, hipStream_t s);
+
 }  // namespace lutnn

@@ -317,6 +317,29 @@ def test_auto_variant_rule(lut):
     assert L.lutnn_auto_variant(None, vp(0x30000), 16) == -1
 
 
+def test_linear_auto_variant_rule(lut):
+    """What lutnn_linear runs for AUTO: one launch for small problems (the lookup would be the gather
+    and the centroids a workgroup re-reads are few), else the lookup's own rule; pure host function."""
+    L, vp = lut.LIB, ctypes.c_void_p
+    ws = vp(0x30000)
+    qkv = _layer(lut, C=384, V=2, M=2304)  # BERT QKV at V = 2
+    assert L.lutnn_linear_auto_variant(ctypes.byref(qkv), ws, 1) == lut.VARIANT_FUSED
+    assert L.lutnn_linear_auto_variant(ctypes.byref(qkv), ws, 16) == lut.VARIANT_FUSED
+    assert L.lutnn_linear_auto_variant(ctypes.byref(qkv), ws, 4096) == lut.VARIANT_SMFMAC
+    wide = _layer(lut, C=1024, V=4, M=4096)  # 256 KiB of centroids per workgroup: two launches
+    assert L.lutnn_linear_auto_variant(ctypes.byref(wide), ws, 1) == lut.VARIANT_LDS
+    assert L.lutnn_linear_auto_variant(ctypes.byref(wide), ws, 16384) == lut.VARIANT_SMFMAC
+    assert L.lutnn_linear_auto_variant(ctypes.byref(wide), None, 16384) == lut.VARIANT_FUSED  # no workspace
+    fc_small = _layer(lut, table_dtype=lut.TABLE_F32, C=128, V=4, M=512)
+    assert L.lutnn_linear_auto_variant(ctypes.byref(fc_small), ws, 256) == lut.VARIANT_FUSED
+    assert L.lutnn_linear_auto_variant(ctypes.byref(fc_small), ws, 1 << 16) == lut.VARIANT_LDS
+    odd_m = _layer(lut, C=64, V=4, M=37)  # M % 4 != 0: the one-launch form cannot run
+    assert L.lutnn_linear_auto_variant(ctypes.byref(odd_m), ws, 8) != lut.VARIANT_FUSED
+    int4 = _layer(lut, table_dtype=lut.TABLE_I4, C=64, V=4, M=512)
+    assert L.lutnn_linear_auto_variant(ctypes.byref(int4), ws, 8) != lut.VARIANT_FUSED
+    assert L.lutnn_linear_auto_variant(None, ws, 16) == -1
+
+
 def test_cost_model_formulas(lut):
     c = lut.cost
     # Table 1 with the paper's own example: FLOPs reduction M / (K + M/V) (Sec. 6.2)

@@ -2,6 +2,7 @@
 identical seeded inputs.  Bars (arXiv 2302.03213 leaves precision open; these are this project's):
 indices bit-exact except counted near-ties (fp64 distance gap < 1e-6 relative); INT8-table
 outputs bit-exact; fp32-table outputs within 1e-5 relative / 1e-4 absolute."""
+import os
 import sys
 
 import numpy as np
@@ -405,10 +406,20 @@ def check_linear(lut, w, variants, X=None):
     flips = near_tie_report(w, idx_gpu, idx_ref, X)
     clean = (idx_gpu == idx_ref).all(axis=1)
     assert flips <= max(1, idx_ref.size // 10000)
+    # "fused" has two forms (a one-launch kernel for small problems, a tile kernel); the library's
+    # tuning variable pins each in turn where it can run, so both are compared whatever AUTO prefers
+    runs = []
     for v in variants:
-        got = host(lut.linear(layer, Xd, v))
+        runs += [(v, form) for form in ("tile", "small")] if v == "fused" else [(v, None)]
+    for v, form in runs:
+        if form:
+            os.environ["LUTNN_FUSED_KERNEL"] = form
+        try:
+            got = host(lut.linear(layer, Xd, v))
+        finally:
+            os.environ.pop("LUTNN_FUSED_KERNEL", None)
         if w.table_dtype == "i8":
-            np.testing.assert_array_equal(got[clean], ref[clean], err_msg="variant %s" % v)
+            np.testing.assert_array_equal(got[clean], ref[clean], err_msg="variant %s %s" % (v, form))
             # rows holding a flipped near-tie: one table entry swapped per flip
             assert np.abs(got[~clean] - ref[~clean]).max(initial=0.0) <= 2 * 127 * float(ol.s) * 4
         else:
