@@ -402,6 +402,25 @@ def main():
                "kind": "oracle",
                "sample": "first %d rows of each layer of %s, encode+lookup, tables prebuilt; "
                          "%.2f s wall" % (n_cpu // len(dev_layers), args.workload, t_cpu)}
+        # the same oracle on one core, on a 1024-row slice of the first layer (distance encoder)
+        w = dev_layers[0][0]
+        if args.encoder == "distance":
+            all_threads = oracle.threads()
+            oracle.set_threads(1)
+            n1 = min(1024, w.N, len(w.X))
+            Tf = oracle.build_table_f32(w.P, w.W)
+            X1 = np.ascontiguousarray(w.X[:n1])
+            if w.table_dtype == "i8":
+                q, s = oracle.quantize(Tf, 4 if args.int4 else 8)
+                c0 = time.perf_counter()
+                oracle.linear_i8(w.P, q, s, X1, w.bias)
+            else:
+                c0 = time.perf_counter()
+                oracle.linear_f32(w.P, Tf, X1, w.bias)
+            t1 = time.perf_counter() - c0
+            oracle.set_threads(all_threads)
+            cpu["single_thread"] = {"value": round(n1 / t1, 1), "unit": "rows/s",
+                                    "sample": "first %d rows of %s; %.2f s" % (n1, w.name, t1)}
 
     w_desc = "; ".join("%s N=%d D=%d M=%d V=%d C=%d K=%d %s table" %
                        (w.name, w.N, w.D, w.M, w.V, w.C, w.K,
