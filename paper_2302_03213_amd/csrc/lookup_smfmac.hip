@@ -86,7 +86,7 @@ __device__ __forceinline__ void dma16_at(uint32_t lds_base, const void* sbase, u
 // contracts C / splits consecutive codebooks and adds its int32 partial sums into Y with atomics; Y
 // then holds integers (zeroed beforehand, turned into the final floats by a separate pass).  For
 // problems with fewer tiles than compute units: more workgroups stream the table in parallel.
-template <int TM, bool SPLIT = false>
+template <int TM, bool SPLIT = false, bool STREAM = false>
 __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const uint4* __restrict__ packed, const float* __restrict__ scale, const float* __restrict__ bias,
     int C, int M, int Mp, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y,
@@ -455,7 +455,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
         if constexpr (SPLIT)
             mfma_atomic_add_tile<TM>(acc, M, N, ct_m0 + w * WAVE_ROWS, ct_n0, reinterpret_cast<int32_t*>(Y), ldy);
         else
-            mfma_store_tile<TM>(acc, sc, bias, M, N, ct_m0 + w * WAVE_ROWS, ct_n0, Y, ldy);
+            mfma_store_tile<TM, STREAM>(acc, sc, bias, M, N, ct_m0 + w * WAVE_ROWS, ct_n0, Y, ldy);
         if (!has_next) break;
         // next tile: its first stages and index words are already in LDS / registers
 #pragma unroll
@@ -539,9 +539,16 @@ hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias
     // Stream several tiles per workgroup when the ring phase carries over from tile to tile:
     // one workgroup per compute unit (the kernel's LDS footprint allows only one anyway).
     if (C % 64 == 0 && blocks > kComputeUnits) blocks = kComputeUnits;
-    hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, false>), dim3((unsigned)blocks), dim3(kMfmaThreads), 0, s,
-                       reinterpret_cast<const uint4*>(packed), scale, bias, C, M, Mp, idx, N, Y, ldy,
-                       (int)row_tiles, tiles, 1);
+    // an output of 128 MiB or more cannot stay in any cache: stream it (512-row tiles only, the
+    // height such problems take)
+    if (TM == 4 && (double)N * M * 4 >= 134217728.0)
+        hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, false, TM == 4>), dim3((unsigned)blocks),
+                           dim3(kMfmaThreads), 0, s, reinterpret_cast<const uint4*>(packed), scale, bias, C, M, Mp,
+                           idx, N, Y, ldy, (int)row_tiles, tiles, 1);
+    else
+        hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, false>), dim3((unsigned)blocks), dim3(kMfmaThreads), 0, s,
+                           reinterpret_cast<const uint4*>(packed), scale, bias, C, M, Mp, idx, N, Y, ldy,
+                           (int)row_tiles, tiles, 1);
     return hipGetLastError();
 }
 
