@@ -158,7 +158,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_conv9_band_kernel(
             for (int t = 0; t < V; ++t) x[t] = ch[toff[t]];
             best = nearest_centroid<V, K_T>(x, P + (size_t)c * K * V, K);
         }
-        packed[j / 4] |= best << (8 * (j % 4));
+        packed[j / 4] |= index_byte(best, j % 4);
     }
     store_index_bytes<V, CT>(is + lane * (CT / 4), w * E::CPW, packed);
     __syncthreads();
