@@ -22,8 +22,8 @@ if ROOT not in sys.path:
 # WRITE_SIZE runs, scaled by the same counters on a copy kernel of known size); the summaries
 # are under profiles/.  Keyed by (workload, kernel).  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/lutnn_linear_fc_large.md: fetch 605,177,651 (295,497 KiB raw x 2.0) + write 268,610,458
-    ("fc_large", "lookup_smfmac_i8"): 873788109,
+    # profiles/lutnn_linear_fc_large.md: fetch 605,123,584 (295,471 KiB raw x 2.0) + write 268,566,118
+    ("fc_large", "lookup_smfmac_i8"): 873689702,
     # dense MFMA variant, measured before the sparse kernel became the default:
     # fetch 403,578,922 (197,084 KiB raw x 2.0) + write 268,435,456
     ("fc_large", "lookup_mfma_i8"): 672014378,
