@@ -242,11 +242,18 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
         }
     };
     // A values of row block i for step j of stage sp: stored byte 2(p>>2) = 1, i.e. the 64-bit
-    // value 1 << 16(p>>2); a 64-bit shift takes its amount modulo 64.
+    // value 1 << 16(p>>2).  The shift instruction itself takes its amount modulo 64, so the bytes
+    // above the one that holds the amount need no masking - which C cannot express (a shift by 64
+    // or more is undefined there), hence the instruction is written out: one AND less per value.
+    auto one_shl = [](uint32_t amount) {
+        u64 r;
+        asm("v_lshlrev_b64 %0, %1, 1" : "=v"(r) : "v"(amount));
+        return r;
+    };
     auto make_a_operand = [&](int set, int sp, int j, const IdxWords& wq, int i) {
         const uint32_t word = wq.sh[i][2 * sp + (j >> 1)];
-        a[set][i][0] = (u64)1 << ((word >> (16 * (j & 1))) & 63u);
-        a[set][i][1] = (u64)1 << ((word >> (16 * (j & 1) + 8)) & 63u);
+        a[set][i][0] = one_shl(word >> (16 * (j & 1)));
+        a[set][i][1] = one_shl(word >> (16 * (j & 1) + 8));
     };
 
     using I0 = std::integral_constant<int, 0>;
