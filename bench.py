@@ -120,8 +120,8 @@ def bench_softpq_backward(args, w, lut, cost, np, torch):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="fc_large",
                     choices=["fc_large", "fc_small", "conv_resnet18", "bert_ffn_up", "bert_layer",
                              "paper_kv", "conv_resnet18_b32"])
