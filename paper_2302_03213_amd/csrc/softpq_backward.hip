@@ -148,18 +148,22 @@ __global__ __launch_bounds__(kEncThreads) void softpq_backward_kernel(
             float* __restrict__ xr = xs + lane * E::LS + cl * V;
             const float* __restrict__ zr = zs + lane * E::LS + cl * V;
 
+            // centroid by centroid, so that only one centroid's V values (one scalar load) are
+            // live at a time: value by value, all K*V of them would have to stay in scalar registers
+            // through the loop, and what does not fit is spilled into vector lanes
+            float xv[V], zv[V];
+#pragma unroll
+            for (int v = 0; v < V; ++v) xv[v] = xr[v], zv[v] = zr[v];
             float d[K_T], a[K_T];
 #pragma unroll
-            for (int k = 0; k < K_T; ++k) d[k] = a[k] = 0.f;
+            for (int k = 0; k < K_T; ++k) {
+                d[k] = a[k] = 0.f;
 #pragma unroll
-            for (int v = 0; v < V; ++v) {
-                const float x = xr[v], z = zr[v];
-#pragma unroll
-                for (int k = 0; k < K_T; ++k) {
+                for (int v = 0; v < V; ++v) {
                     const float p = pc[k * V + v];
-                    const float t = x - p;
+                    const float t = xv[v] - p;
                     d[k] = __fmaf_rn(t, t, d[k]);
-                    a[k] = __fmaf_rn(z, p, a[k]);
+                    a[k] = __fmaf_rn(zv[v], p, a[k]);
                 }
             }
             float dmin = d[0];
@@ -188,24 +192,26 @@ __global__ __launch_bounds__(kEncThreads) void softpq_backward_kernel(
 #pragma unroll
             for (int g = 0; g < S::NG; ++g) {
                 float contrib[64];
+                float dxv[S::VG];
 #pragma unroll
-                for (int vv = 0; vv < S::VG; ++vv) {
-                    const int v = g * S::VG + vv;
-                    if (v < V) {
-                        const float x = xr[v], z = zr[v];
-                        float dx = 0.f;
+                for (int vv = 0; vv < S::VG; ++vv) dxv[vv] = 0.f;
 #pragma unroll
-                        for (int k = 0; k < K_T; ++k) {
-                            const float t = e2[k] * (x - pc[k * V + v]);  // 2 dd_k (x_v - P_kv)
-                            dx += t;
-                            contrib[k * S::VG + vv] = __fmaf_rn(s[k], z, -t);
+                for (int k = 0; k < K_T; ++k) {
+#pragma unroll
+                    for (int vv = 0; vv < S::VG; ++vv) {
+                        const int v = g * S::VG + vv;
+                        if (v < V) {
+                            const float t = e2[k] * (xv[v] - pc[k * V + v]);  // 2 dd_k (x_v - P_kv)
+                            dxv[vv] += t;
+                            contrib[k * S::VG + vv] = __fmaf_rn(s[k], zv[v], -t);
+                        } else {
+                            contrib[k * S::VG + vv] = 0.f;
                         }
-                        xr[v] = dx;  // this lane's own element: no other lane reads it
-                    } else {
-#pragma unroll
-                        for (int k = 0; k < K_T; ++k) contrib[k * S::VG + vv] = 0.f;
                     }
                 }
+#pragma unroll
+                for (int vv = 0; vv < S::VG; ++vv)
+                    if (g * S::VG + vv < V) xr[g * S::VG + vv] = dxv[vv];  // this lane's own element: no other lane reads it
                 const float r = reduce_scatter_64(contrib, lane);
 #pragma unroll
                 for (int jj = 0; jj < E::CPW; ++jj)  // j is wave-uniform; acc keeps static indices
