@@ -146,8 +146,6 @@ def main():
                     help="also run one 256 MiB device-to-device copy (untimed): the known-size kernel "
                          "against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
     args = ap.parse_args()
-    if args.encoder == "tree" and args.variant == "fused":
-        ap.error("--encoder tree has no fused kernel")
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the operator shards by rows with no "
               "communication; multi-GPU runs are not part of it). Use --gpus 1.", file=sys.stderr)
@@ -261,8 +259,8 @@ def main():
             variant_used[w.name] = "fused"
         elif args.variant == "auto":  # what the library's AUTO rule picks at this shape
             variant_used[w.name] = lut.auto_variant(layer, w.N, ws)
-            if not w.conv and args.encoder == "distance" and lut.linear_auto_variant(layer, w.N, ws) == "fused":
-                fused = True  # lutnn_linear does both steps in one launch here
+            if not w.conv and lut.linear_auto_variant(layer, w.N, ws) == "fused":
+                fused = True  # lutnn_linear / lutnn_linear_tree do both steps in one launch here
                 variant_used[w.name] = "fused"
         else:
             variant_used[w.name] = args.variant

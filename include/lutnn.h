@@ -216,8 +216,13 @@ LUTNN_API lutnn_status lutnn_encode_tree(const lutnn_tree* tree, const float* X,
  * layer->K must be 2^levels; layer->centroids is not used (the table rows are the buckets'
  * prototypes times the weights, built by lutnn_build_table from whatever prototypes training
  * assigned to the buckets).
- *   idx_workspace  [N][C] uint8 device scratch, required
- *   variant        a lookup variant: AUTO, LDS, MFMA or SMFMAC
+ *   idx_workspace  [N][C] uint8 device scratch; required unless the one-launch kernel runs
+ *   variant        AUTO, LDS, MFMA, SMFMAC, or FUSED = the one-launch kernel of lutnn_linear with the
+ *                  tree walk as its first step (fp32 or INT8 table in the plain layout, M % 4 == 0,
+ *                  V in {1,2,3,4,8,9,16,32}; E_UNSUPPORTED otherwise).  AUTO takes that kernel on
+ *                  the shapes where lutnn_linear's AUTO does (lutnn_linear_auto_variant), else
+ *                  the two launches; the indices, and with an INT8 table the outputs, are the
+ *                  same either way.
  * Errors: as lutnn_encode_tree and lutnn_lookup; E_SHAPE when tree and layer disagree.
  */
 LUTNN_API lutnn_status lutnn_linear_tree(const lutnn_layer* layer, const lutnn_tree* tree,

@@ -253,11 +253,11 @@ def linear_tree(layer, tree, X, variant="auto", out=None, idx_workspace=None):
     if out is None:
         out = torch.empty((N, layer.M), dtype=torch.float32, device=X.device)
     assert out.dtype == torch.float32 and out.stride(1) == 1 and out.shape == (N, layer.M)
-    if idx_workspace is None:
+    v = _variant(variant)
+    if idx_workspace is None and v != VARIANT_FUSED:
         idx_workspace = torch.empty((N, layer.C), dtype=torch.uint8, device=X.device)
     _check(LIB.lutnn_linear_tree(ctypes.byref(layer.c), ctypes.byref(tree.c), _ptr(X), N, X.stride(0),
-                                 _ptr(out), out.stride(0), _variant(variant), _ptr(idx_workspace),
-                                 _stream()))
+                                 _ptr(out), out.stride(0), v, _ptr(idx_workspace), _stream()))
     return out
 
 

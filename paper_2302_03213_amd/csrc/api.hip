@@ -266,29 +266,6 @@ lutnn_status lutnn_encode_tree(const lutnn_tree* tree, const float* X, int64_t N
                       "tree encode launch");
 }
 
-lutnn_status lutnn_linear_tree(const lutnn_layer* layer, const lutnn_tree* tree, const float* X,
-                               int64_t N, int64_t ldx, float* Y, int64_t ldy, int32_t variant,
-                               uint8_t* idx_workspace, void* stream) {
-    if (lutnn_status st = check_layer(layer)) return st;
-    if (lutnn_status st = check_tree(tree, X, N, ldx)) return st;
-    if (tree->C != layer->C || tree->V != layer->V || (1 << tree->levels) != layer->K)
-        return fail(LUTNN_E_SHAPE, "tree (C=%d V=%d levels=%d) does not match layer (C=%d V=%d K=%d)", tree->C,
-                    tree->V, tree->levels, layer->C, layer->V, layer->K);
-    if (N == 0) return LUTNN_OK;
-    if (!idx_workspace) return fail(LUTNN_E_NULL, "idx_workspace is NULL");
-    if (variant == LUTNN_VARIANT_FUSED)
-        return fail(LUTNN_E_UNSUPPORTED, "there is no fused kernel for the hash encoder");
-    const int v = resolve_lookup_variant(layer, variant, idx_workspace, N);
-    if (lutnn_status st = check_lookup(layer, v, idx_workspace, Y, N, ldy)) return st;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (lutnn_status st = hip_result(lutnn::launch_encode_tree(tree->split_dim, tree->threshold, tree->C,
-                                                               tree->levels, tree->V, X, N, ldx,
-                                                               idx_workspace, s),
-                                     "tree encode launch"))
-        return st;
-    return do_lookup(layer, v, idx_workspace, N, Y, ldy, s);
-}
-
 size_t lutnn_softpq_workspace_bytes(int32_t C, int32_t K, int32_t V, int64_t N) {
     if (C <= 0 || K <= 0 || V <= 0 || N <= 0) return 0;
     return lutnn::softpq_workspace_bytes(C, K, V, N);
@@ -447,6 +424,54 @@ lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, int64_t N, i
     return do_lookup(L, v, idx_workspace, N, Y, ldy, s);
 }
 
+lutnn_status lutnn_linear_tree(const lutnn_layer* layer, const lutnn_tree* tree, const float* X,
+                               int64_t N, int64_t ldx, float* Y, int64_t ldy, int32_t variant,
+                               uint8_t* idx_workspace, void* stream) {
+    if (lutnn_status st = check_layer(layer)) return st;
+    if (lutnn_status st = check_tree(tree, X, N, ldx)) return st;
+    if (tree->C != layer->C || tree->V != layer->V || (1 << tree->levels) != layer->K)
+        return fail(LUTNN_E_SHAPE, "tree (C=%d V=%d levels=%d) does not match layer (C=%d V=%d K=%d)", tree->C,
+                    tree->V, tree->levels, layer->C, layer->V, layer->K);
+    if (N == 0) return LUTNN_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // One launch (the tree walk, then the gather, in one kernel) where FUSED asks for it or where
+    // AUTO would take it with the distance encoder: the rule prices launches and table reads, and
+    // a walk costs less than the search it replaces.
+    const bool can_small =
+        lutnn::linear_small_supported(layer->table, small_table_kind(layer), layer->C, layer->K, layer->V, layer->M);
+    if (variant == LUTNN_VARIANT_FUSED && !can_small)
+        return fail(LUTNN_E_UNSUPPORTED, "no one-launch kernel with the hash encoder for C=%d K=%d V=%d M=%d dtype=%d",
+                    layer->C, layer->K, layer->V, layer->M, layer->table_dtype);
+    if (variant == LUTNN_VARIANT_FUSED || (variant == LUTNN_VARIANT_AUTO && small_preferred(layer, N))) {
+        if (!Y) return fail(LUTNN_E_NULL, "Y is NULL");
+        if (ldy < layer->M) return fail(LUTNN_E_SHAPE, "ldy=%lld is smaller than M=%d", (long long)ldy, layer->M);
+        if (!aligned(Y, 4)) return fail(LUTNN_E_ALIGN, "Y must be 4-byte aligned");
+        if (layer->bias && !aligned(layer->bias, 4)) return fail(LUTNN_E_ALIGN, "bias must be 4-byte aligned");
+        if (layer->table_dtype == LUTNN_TABLE_I8) {
+            if (!layer->scale) return fail(LUTNN_E_NULL, "an integer table needs layer->scale");
+            return hip_result(lutnn::launch_linear_small_tree_i8(
+                                  tree->split_dim, tree->threshold, tree->levels,
+                                  static_cast<const int8_t*>(layer->table), layer->scale, layer->bias, layer->C,
+                                  layer->V, layer->M, X, N, ldx, Y, ldy, s),
+                              "one-launch linear (hash encoder)");
+        }
+        return hip_result(lutnn::launch_linear_small_tree_f32(
+                              tree->split_dim, tree->threshold, tree->levels,
+                              static_cast<const float*>(layer->table), layer->bias, layer->C, layer->V, layer->M, X,
+                              N, ldx, Y, ldy, s),
+                          "one-launch linear (hash encoder)");
+    }
+    if (!idx_workspace) return fail(LUTNN_E_NULL, "idx_workspace is NULL");
+    const int v = resolve_lookup_variant(layer, variant, idx_workspace, N);
+    if (lutnn_status st = check_lookup(layer, v, idx_workspace, Y, N, ldy)) return st;
+    if (lutnn_status st = hip_result(lutnn::launch_encode_tree(tree->split_dim, tree->threshold, tree->C,
+                                                               tree->levels, tree->V, X, N, ldx,
+                                                               idx_workspace, s),
+                                     "tree encode launch"))
+        return st;
+    return do_lookup(layer, v, idx_workspace, N, Y, ldy, s);
+}
+
 const char* lutnn_status_string(int32_t status) {
     switch (status) {
         case LUTNN_OK: return "LUTNN_OK";
@@ -528,7 +553,7 @@ lutnn_status lutnn_conv2d_tree(const lutnn_layer* layer, const lutnn_tree* tree,
     if (lutnn_status st = check_conv(layer, geom, B, &g, &N)) return st;
     if (N == 0) return LUTNN_OK;
     if (variant == LUTNN_VARIANT_FUSED)
-        return fail(LUTNN_E_UNSUPPORTED, "there is no fused kernel for the hash encoder");
+        return fail(LUTNN_E_UNSUPPORTED, "there is no fused kernel for the hash encoder on a convolution");
     if (!idx_workspace) return fail(LUTNN_E_NULL, "idx_workspace is NULL");
     const int v = resolve_lookup_variant(layer, variant, idx_workspace, N);
     if (lutnn_status st = check_lookup(layer, v, idx_workspace, Y, N, ldy)) return st;

@@ -107,5 +107,13 @@ hipError_t launch_linear_small_f32(const float* P, const float* T, const float* 
 hipError_t launch_linear_small_i8(const float* P, const int8_t* T, const float* scale, const float* bias, int C,
                                   int K, int V, int M, const float* X, int64_t N, int64_t ldx, float* Y,
                                   int64_t ldy, hipStream_t s);
+// ... and with the hash encoder (Sec. 2) as step 1: the trees' K = 2^levels.
+hipError_t launch_linear_small_tree_f32(const int32_t* split_dim, const float* threshold, int levels,
+                                        const float* T, const float* bias, int C, int V, int M, const float* X,
+                                        int64_t N, int64_t ldx, float* Y, int64_t ldy, hipStream_t s);
+hipError_t launch_linear_small_tree_i8(const int32_t* split_dim, const float* threshold, int levels,
+                                       const int8_t* T, const float* scale, const float* bias, int C, int V,
+                                       int M, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
+                                       hipStream_t s);
 
 }  // namespace lutnn

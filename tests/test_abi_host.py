@@ -225,10 +225,14 @@ def test_tree_descriptor_validation(lut):
                              lut.VARIANT_AUTO, IDX, None), "LUTNN_E_SHAPE"),  # K != 2^levels
         (L.lutnn_linear_tree(ctypes.byref(layer), ctypes.byref(tree(V=2)), X, 8, 16, Y, 8,
                              lut.VARIANT_AUTO, IDX, None), "LUTNN_E_SHAPE"),
-        (L.lutnn_linear_tree(ctypes.byref(layer), ctypes.byref(ok), X, 8, 16, Y, 8, lut.VARIANT_AUTO,
-                             None, None), "LUTNN_E_NULL"),  # workspace required
-        (L.lutnn_linear_tree(ctypes.byref(layer), ctypes.byref(ok), X, 8, 16, Y, 8, lut.VARIANT_FUSED,
-                             IDX, None), "LUTNN_E_UNSUPPORTED"),
+        (L.lutnn_linear_tree(ctypes.byref(layer), ctypes.byref(ok), X, 8, 16, Y, 8, lut.VARIANT_LDS,
+                             None, None), "LUTNN_E_NULL"),  # two launches need the workspace
+        (L.lutnn_linear_tree(ctypes.byref(_layer(lut, M=6)), ctypes.byref(ok), X, 8, 16, Y, 8,
+                             lut.VARIANT_FUSED, IDX, None), "LUTNN_E_UNSUPPORTED"),  # M % 4 != 0
+        (L.lutnn_linear_tree(ctypes.byref(_layer(lut, table_dtype=lut.TABLE_I4)), ctypes.byref(ok), X, 8, 16,
+                             Y, 8, lut.VARIANT_FUSED, IDX, None), "LUTNN_E_UNSUPPORTED"),  # INT4 storage
+        (L.lutnn_linear_tree(ctypes.byref(layer), ctypes.byref(ok), X, 8, 16, Y, 7, lut.VARIANT_FUSED,
+                             None, None), "LUTNN_E_SHAPE"),  # one launch: ldy < M
         (L.lutnn_linear_tree(ctypes.byref(layer), ctypes.byref(ok), X, 8, 16, Y, 7, lut.VARIANT_LDS,
                              IDX, None), "LUTNN_E_SHAPE"),  # ldy < M
     ]

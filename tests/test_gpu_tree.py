@@ -122,7 +122,18 @@ LINEAR_TREE_SHAPES = [
     (130, 32, 4, 4, 96, "i8"), (600, 64, 4, 4, 320, "i8"), (77, 17, 9, 4, 64, "i8"),
     (100, 24, 32, 4, 50, "i8"), (90, 12, 4, 3, 40, "i8"), (64, 8, 4, 6, 33, "i8"),
     (130, 32, 4, 4, 96, "f32"), (50, 6, 2, 8, 20, "f32"),
+    # shapes of the one-launch kernel: one row of a BERT layer (codebooks shared out over sixteen
+    # and over four wavefronts), rows narrower than a wavefront, whole rows per wavefront, trees
+    # walked from memory (levels != 4), every sub-vector length it unrolls
+    (1, 384, 2, 4, 768, "i8"), (3, 384, 2, 4, 2304, "i8"), (5, 128, 4, 4, 512, "f32"),
+    (200, 32, 4, 4, 64, "i8"), (7, 70, 4, 3, 260, "i8"), (9, 16, 32, 5, 256, "f32"),
+    (4, 24, 16, 8, 128, "i8"), (33, 20, 8, 4, 1024, "i8"), (70, 10, 1, 4, 32, "f32"),
+    (6, 12, 3, 2, 16, "i8"), (130, 64, 9, 4, 128, "i8"), (2, 530, 2, 4, 300, "f32"),
 ]
+
+
+def one_launch_supported(V, M):
+    return V in (1, 2, 3, 4, 8, 9, 16, 32) and M % 4 == 0 and (M >= 256 or 64 % (M // 4) == 0)
 
 
 @pytest.mark.parametrize("N,C,V,levels,M,dtype", LINEAR_TREE_SHAPES)
@@ -139,6 +150,8 @@ def test_linear_tree_matches_oracle(lut, N, C, V, levels, M, dtype):
     variants = ["auto", "lds", "mfma"] if dtype == "i8" and K <= 16 else ["auto", "lds"]
     if dtype == "i8" and K <= 16 and C % 32 == 0:
         variants.append("smfmac")
+    if one_launch_supported(V, M):
+        variants.append("fused")
     for v in variants:
         got = host(lut.linear_tree(layer, tree, dev(w.X), v))
         if dtype == "i8":
@@ -177,55 +190,34 @@ def test_tree_error_statuses_and_empty_batch(lut):
     with pytest.raises(lut.LutnnError) as e:
         lut.linear_tree(layer, tree, X)
     assert e.value.status == 2
-    w16 = wl.make_layer("t", 8, C, 16, V, 16, "i8", seed=1)
+    w16 = wl.make_layer("t", 8, C, 16, V, 18, "i8", seed=1)  # M % 4 != 0: no one-launch kernel
     layer16 = lut.build_table(dev(w16.P), dev(w16.W), lut.TABLE_I8)
     with pytest.raises(lut.LutnnError) as e:
         lut.linear_tree(layer16, tree, X, "fused")
     assert e.value.status == 3
-
-
-def _unfold_rows(inp, kernel, stride, pad):
-    cols = torch.nn.functional.unfold(torch.from_numpy(inp), kernel, padding=pad, stride=stride)
-    return cols.permute(0, 2, 1).reshape(-1, cols.shape[1]).contiguous().numpy()
-
-
-TREE_CONV_SHAPES = [
-    # B, Cin, H, W, kernel, stride, pad, V, levels
-    (1, 16, 13, 17, (3, 3), (1, 1), (1, 1), 9, 4), (2, 8, 20, 20, (3, 3), (2, 2), (1, 1), 9, 3),
-    (3, 16, 9, 11, (1, 1), (1, 1), (0, 0), 4, 4), (2, 4, 15, 9, (3, 5), (2, 1), (1, 2), 2, 6),
-    (1, 64, 56, 56, (3, 3), (1, 1), (1, 1), 9, 4), (4, 32, 30, 30, (3, 3), (1, 1), (1, 1), 16, 8),
-]
-
-
-@pytest.mark.parametrize("B,Cin,H,W,kernel,stride,pad,V,levels", TREE_CONV_SHAPES)
-def test_encode_tree_conv2d_matches_oracle_on_unfolded_rows(lut, B, Cin, H, W, kernel, stride, pad, V, levels):
-    rng = np.random.default_rng(B + Cin + H)
-    inp = rng.standard_normal((B, Cin, H, W)).astype(np.float32)
-    X = _unfold_rows(inp, kernel, stride, pad)
-    C = X.shape[1] // V
-    assert C * V == X.shape[1]
-    dims, thr = wl.random_tree(C, V, levels, seed=H + W)
-    ref = oracle.encode_tree(dims, thr, X, V)
-    tree = device_tree(lut, dims, thr, V)
-    np.testing.assert_array_equal(host(lut.encode_tree_conv2d(tree, dev(inp), kernel, stride, pad)), ref)
-    # the same indices as the matrix form of the encoder on the unfolded rows
-    np.testing.assert_array_equal(host(lut.encode_tree(tree, dev(X))), ref)
-
-
-def test_conv2d_tree_matches_oracle(lut):
-    B, Cin, H, W, M, levels = 2, 16, 14, 12, 40, 4
-    rng = np.random.default_rng(3)
-    inp = rng.standard_normal((B, Cin, H, W)).astype(np.float32)
-    X = _unfold_rows(inp, (3, 3), (1, 1), (1, 1))
-    w = wl.make_layer("t", 1, Cin, 16, 9, M, "i8", seed=9)
-    dims, thr = wl.random_tree(Cin, 9, levels, seed=9)
-    ol = OracleLayer(w)
-    ref = ol.lookup(oracle.encode_tree(dims, thr, X, 9))
-    layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8, bias=dev(w.bias))
-    tree = device_tree(lut, dims, thr, 9)
-    for v in ("auto", "lds", "mfma"):
-        np.testing.assert_array_equal(host(lut.conv2d_tree(layer, tree, dev(inp), 3, 1, 1, v)), ref, err_msg=v)
-    with pytest.raises(lut.LutnnError) as e:  # V = 32 has no convolution form
-        lut.encode_tree_conv2d(device_tree(lut, *wl.random_tree(1, 32, 4, seed=1), 32),
-                               dev(rng.standard_normal((1, 32, 8, 8)).astype(np.float32)), 1, 1, 0)
+    w4 = wl.make_layer("t", 8, C, 16, V, 16, "i4", seed=1)  # nor for INT4 storage
+    layer4 = lut.build_table(dev(w4.P), dev(w4.W), lut.TABLE_I4)
+    with pytest.raises(lut.LutnnError) as e:
+        lut.linear_tree(layer4, tree, X, "fused")
     assert e.value.status == 3
+
+
+def test_linear_tree_one_launch_strides_no_bias_and_no_workspace(lut):
+    # row strides on X and Y, a layer without bias; the one-launch kernel takes no index workspace
+    # (the binding passes NULL for "fused")
+    N, C, V, levels, M = 6, 96, 4, 4, 512
+    w = wl.make_layer("t", N, C, 16, V, M, "i8", seed=77)
+    dims, thr = wl.random_tree(C, V, levels, seed=77)
+    ref = OracleLayer(w).lookup(oracle.encode_tree(dims, thr, w.X, V), bias=None)
+    tree = device_tree(lut, dims, thr, V)
+    layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8)
+    Xbig = torch.zeros((N, C * V + 12), dtype=torch.float32, device="cuda")
+    Xbig[:, 4:4 + C * V] = dev(w.X)
+    Ybig = torch.full((N, M + 8), -7.0, dtype=torch.float32, device="cuda")
+    lut.linear_tree(layer, tree, Xbig[:, 4:4 + C * V], "fused", out=Ybig[:, :M])
+    np.testing.assert_array_equal(host(Ybig[:, :M]), ref)
+    assert (host(Ybig[:, M:]) == -7.0).all()
+    # AUTO takes the same kernel on this shape, and equals the two launches
+    assert lut.linear_auto_variant(layer, N) == "fused"
+    np.testing.assert_array_equal(host(lut.linear_tree(layer, tree, dev(w.X), "auto")), ref)
+    np.testing.assert_array_equal(host(lut.linear_tree(layer, tree, dev(w.X), "lds")), ref)
