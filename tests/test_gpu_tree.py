@@ -221,3 +221,76 @@ def test_linear_tree_one_launch_strides_no_bias_and_no_workspace(lut):
     assert lut.linear_auto_variant(layer, N) == "fused"
     np.testing.assert_array_equal(host(lut.linear_tree(layer, tree, dev(w.X), "auto")), ref)
     np.testing.assert_array_equal(host(lut.linear_tree(layer, tree, dev(w.X), "lds")), ref)
+
+
+@pytest.mark.parametrize("levels", [4, 3])
+def test_linear_tree_one_launch_clamps_split_indices_and_walks_non_finite_values(lut, levels):
+    # the walk inside the one-launch kernel (from registers for four levels, from memory otherwise)
+    # treats split indices outside [0, V), NaN and the infinities as the stand-alone encoder does
+    N, C, V, M = 40, 24, 4, 256
+    K = 1 << levels
+    w = wl.make_layer("t", N, C, K, V, M, "i8", seed=5 + levels)
+    dims, thr = wl.random_tree(C, V, levels, seed=6 + levels)
+    bad = dims.copy()
+    bad[dims == 0] = -3
+    bad[dims == V - 1] = V + 50
+    X = w.X.copy()
+    X[3] = np.nan
+    X[4] = np.inf
+    X[5] = -np.inf
+    X[6, ::3] = np.nan
+    Xs = X.reshape(N, C, V)
+    Xs[10:20, :, 1] = thr[:, 0][None, :]  # values exactly on the root's threshold go left
+    idx_ref = oracle.encode_tree(dims, thr, X, V)
+    ref = OracleLayer(w).lookup(idx_ref)
+    layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8, bias=dev(w.bias))
+    got = host(lut.linear_tree(layer, device_tree(lut, bad, thr, V), dev(X), "fused"))
+    np.testing.assert_array_equal(got, ref)
+    assert (idx_ref[3] == 0).all() and (idx_ref[4] == K - 1).all() and (idx_ref[5] == 0).all()
+
+
+def _unfold_rows(inp, kernel, stride, pad):
+    cols = torch.nn.functional.unfold(torch.from_numpy(inp), kernel, padding=pad, stride=stride)
+    return cols.permute(0, 2, 1).reshape(-1, cols.shape[1]).contiguous().numpy()
+
+
+TREE_CONV_SHAPES = [
+    # B, Cin, H, W, kernel, stride, pad, V, levels
+    (1, 16, 13, 17, (3, 3), (1, 1), (1, 1), 9, 4), (2, 8, 20, 20, (3, 3), (2, 2), (1, 1), 9, 3),
+    (3, 16, 9, 11, (1, 1), (1, 1), (0, 0), 4, 4), (2, 4, 15, 9, (3, 5), (2, 1), (1, 2), 2, 6),
+    (1, 64, 56, 56, (3, 3), (1, 1), (1, 1), 9, 4), (4, 32, 30, 30, (3, 3), (1, 1), (1, 1), 16, 8),
+]
+
+
+@pytest.mark.parametrize("B,Cin,H,W,kernel,stride,pad,V,levels", TREE_CONV_SHAPES)
+def test_encode_tree_conv2d_matches_oracle_on_unfolded_rows(lut, B, Cin, H, W, kernel, stride, pad, V, levels):
+    rng = np.random.default_rng(B + Cin + H)
+    inp = rng.standard_normal((B, Cin, H, W)).astype(np.float32)
+    X = _unfold_rows(inp, kernel, stride, pad)
+    C = X.shape[1] // V
+    assert C * V == X.shape[1]
+    dims, thr = wl.random_tree(C, V, levels, seed=H + W)
+    ref = oracle.encode_tree(dims, thr, X, V)
+    tree = device_tree(lut, dims, thr, V)
+    np.testing.assert_array_equal(host(lut.encode_tree_conv2d(tree, dev(inp), kernel, stride, pad)), ref)
+    # the same indices as the matrix form of the encoder on the unfolded rows
+    np.testing.assert_array_equal(host(lut.encode_tree(tree, dev(X))), ref)
+
+
+def test_conv2d_tree_matches_oracle(lut):
+    B, Cin, H, W, M, levels = 2, 16, 14, 12, 40, 4
+    rng = np.random.default_rng(3)
+    inp = rng.standard_normal((B, Cin, H, W)).astype(np.float32)
+    X = _unfold_rows(inp, (3, 3), (1, 1), (1, 1))
+    w = wl.make_layer("t", 1, Cin, 16, 9, M, "i8", seed=9)
+    dims, thr = wl.random_tree(Cin, 9, levels, seed=9)
+    ol = OracleLayer(w)
+    ref = ol.lookup(oracle.encode_tree(dims, thr, X, 9))
+    layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_I8, bias=dev(w.bias))
+    tree = device_tree(lut, dims, thr, 9)
+    for v in ("auto", "lds", "mfma"):
+        np.testing.assert_array_equal(host(lut.conv2d_tree(layer, tree, dev(inp), 3, 1, 1, v)), ref, err_msg=v)
+    with pytest.raises(lut.LutnnError) as e:  # V = 32 has no convolution form
+        lut.encode_tree_conv2d(device_tree(lut, *wl.random_tree(1, 32, 4, seed=1), 32),
+                               dev(rng.standard_normal((1, 32, 8, 8)).astype(np.float32)), 1, 1, 0)
+    assert e.value.status == 3
