@@ -6,9 +6,17 @@ Bar (the paper fixes no precision for training): every gradient within 5e-5 of t
 magnitude of its tensor.  The softmax weights carry a relative error of about (d/t) * 2^-23 plus the
 2 ulp of the hardware exponential, i.e. up to 1e-5 for exponents of a few tens; a sum of N such
 terms in fp32 adds at most N * 2^-24 relative to the sum of magnitudes (1e-3 for N = 16384 in the
-worst case, ~sqrt(N) * 2^-24 = 8e-6 typically).  dt is one sum over all N * C * K terms with
-cancellation, so it is held to 2e-3 of the sum of the terms' magnitudes instead.  Observed: 2e-7 to 8e-7
-for dP and dX."""
+worst case, ~sqrt(N) * 2^-24 = 8e-6 typically).  Observed: 2e-7 to 8e-7 for dP and dX.
+
+dt (Sec. 3.2, the learned temperature) is one sum over all N * C * K terms dz_k d_k / t^2 with
+cancellation, so its error is measured against S = sum |dz_k d_k| / t^2, the magnitude it is summed
+from.  A term carries the relative error of its softmax weight (the exponent (d - d_min)/t is known
+to about (d/t) * 2^-23, i.e. 1e-6 for exponents of ten, plus 2 ulp of the exponential) and the fp32
+summation adds about sqrt(terms) * 2^-24 of S: both near 1e-6 * S.  The bar is 1e-5 * S, ten times
+that; wherever the gradient is not itself a cancellation residue (|dt| >= 1e-2 * S) it must also hold
+to 1e-3 relative.  |dt| / S is 3e-5 to 0.3 on the cases below (computed with the oracle), so a
+kernel returning 0 or the wrong sign misses the bar on every one of them.  Observed error: 1e-10 to
+8e-8 of S."""
 import sys
 
 import numpy as np
@@ -42,13 +50,24 @@ def close(got, ref, frac=5e-5):
     return err
 
 
-def dt_bar(w, t, G):
-    """2e-3 of the sum of |dz_k d_k| / t^2: the magnitude the temperature gradient is summed from."""
+def dt_magnitude(w, t, G):
+    """S = sum |dz_k d_k| / t^2: the magnitude the temperature gradient is summed from."""
     s, d, _ = osp.soft_encoding(w.P, w.X, t)
     P64, Wc = w.P.astype(np.float64), w.W.astype(np.float64).reshape(w.C, w.V, -1)
     ds = np.einsum("nm,ckm->nck", G, np.einsum("ckv,cvm->ckm", P64, Wc))
     dz = s * (ds - (s * ds).sum(-1, keepdims=True))
-    return 2e-3 * np.abs(dz * d).sum() / (t * t)
+    return np.abs(dz * d).sum() / (t * t)
+
+
+def check_dt(got, ref, S, frac=1e-5):
+    """|dt - dt_ref| <= frac * S, and <= 1e-3 * |dt_ref| where dt_ref is not a cancellation residue."""
+    err = abs(float(got) - float(ref))
+    print("dt %.6e ref %.6e  err/S %.2e  |ref|/S %.2e" % (got, ref, err / max(S, 1e-300),
+                                                        abs(ref) / max(S, 1e-300)))
+    assert err <= frac * S, "dt %.8e, oracle %.8e, error %.2e of S" % (got, ref, err / S)
+    if abs(ref) >= 1e-2 * S:
+        assert err <= 1e-3 * abs(ref), "dt %.8e, oracle %.8e" % (got, ref)
+    return err / max(S, 1e-300)
 
 
 def run_case(lut, N, C, K, V, M, t, seed, strided=False):
@@ -68,7 +87,7 @@ def run_case(lut, N, C, K, V, M, t, seed, strided=False):
     dP, dX, dt = lut.softpq_backward(layer, t, Xd, Zd)
     e1 = close(host(dP), dP_ref)
     e2 = close(host(dX), dX_ref)
-    assert abs(host(dt)[0] - dt_ref) <= dt_bar(w, t, G), (host(dt)[0], dt_ref)
+    check_dt(host(dt)[0], dt_ref, dt_magnitude(w, t, G))
     # without the input gradient the other two are unchanged, bit for bit (fixed summation order)
     dP2, none, dt2 = lut.softpq_backward(layer, t, Xd, Zd, need_dx=False)
     assert none is None
@@ -178,7 +197,8 @@ def test_autograd_wrapper_trains_centroids_and_temperature(lut):
     dP_ref, dX_ref, dt_ref = osp.backward(w.P, w.W, w.X, t, host(G).astype(np.float64))
     close(host(layer.centroids.grad), dP_ref, 5e-4)  # Z comes from torch's fp32 GEMM here
     close(host(X.grad), dX_ref, 5e-4)
-    assert abs(layer.temperature.grad.item() - dt_ref) <= dt_bar(w, t, host(G).astype(np.float64)) * 2
+    # Z comes from torch's fp32 GEMM here (relative error ~1e-6 per element): the same bar holds
+    check_dt(layer.temperature.grad.item(), dt_ref, dt_magnitude(w, t, host(G).astype(np.float64)))
     np.testing.assert_allclose(host(layer.bias.grad), host(G).sum(axis=0), rtol=1e-4, atol=1e-6)
 
     def soft_loss(P):
@@ -226,5 +246,5 @@ def test_autograd_conv2d_module_matches_oracle_on_unfolded_rows(lut):
     close(host(mod.centroids.grad), dP_ref, 5e-4)  # Z comes from torch's fp32 GEMM here
     close(host(x.grad), dinp_ref, 5e-4)
     w.X = X
-    assert abs(mod.temperature.grad.item() - dt_ref) <= 2 * dt_bar(w, t, G2)
+    check_dt(mod.temperature.grad.item(), dt_ref, dt_magnitude(w, t, G2))
     np.testing.assert_allclose(host(mod.bias.grad), G2.sum(axis=0), rtol=1e-4, atol=1e-5)
