@@ -352,7 +352,24 @@ LUTNN_API const char* lutnn_status_string(int32_t status);
 /* Host: description of the calling thread's most recent failure ("" if none). */
 LUTNN_API const char* lutnn_last_error(void);
 
-/* Host: library version, "major.minor.patch". */
+/*
+ * Host: pins a launcher's choice among its kernel instances, for tuning sweeps and for tests that
+ * must reach every instance; not needed in normal use.  Switches (each starts from the environment
+ * variable of the same name, which is read once, when the first call needs it):
+ *   "LUTNN_FUSED_KERNEL"      "small" | "tile"          which form LUTNN_VARIANT_FUSED runs
+ *   "LUTNN_SMFMAC_SPLIT"      "0" | "1"                 codebooks of a tile shared out over workgroups
+ *   "LUTNN_SMFMAC_TILE_ROWS"  "128" | "256" | "384" | "512"   tile height of the sparse matrix-core lookup
+ * value NULL or "" returns the switch to "not pinned".  A pinned choice the shape cannot take is
+ * ignored.  Process-wide and atomic: safe to call while other threads launch, which then see
+ * either the old or the new value.
+ * Errors: E_NULL (name), E_UNSUPPORTED (unknown name), E_SHAPE (value not understood).
+ */
+LUTNN_API lutnn_status lutnn_set_tunable(const char* name, const char* value);
+
+/*
+ * Host: library version, "major.minor.patch+<source hash>": the hash (12 hex digits) identifies the
+ * sources the library was compiled from, so that a loader can tell a stale binary.
+ */
 LUTNN_API const char* lutnn_version(void);
 
 #ifdef __cplusplus

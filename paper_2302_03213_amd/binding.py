@@ -27,7 +27,7 @@ VARIANT_SMFMAC = 4
 VARIANTS = {"auto": VARIANT_AUTO, "lds": VARIANT_LDS, "mfma": VARIANT_MFMA, "fused": VARIANT_FUSED,
             "smfmac": VARIANT_SMFMAC}
 
-EXPORTS = ["lutnn_table_bytes", "lutnn_packed_bytes", "lutnn_build_table", "lutnn_encode",
+EXPORTS = ["lutnn_set_tunable", "lutnn_table_bytes", "lutnn_packed_bytes", "lutnn_build_table", "lutnn_encode",
            "lutnn_lookup", "lutnn_linear", "lutnn_encode_tree", "lutnn_linear_tree",
            "lutnn_softpq_backward", "lutnn_softpq_workspace_bytes",
            "lutnn_encode_tree_conv2d", "lutnn_conv2d_tree", "lutnn_conv2d_rows", "lutnn_encode_conv2d", "lutnn_conv2d",
@@ -60,18 +60,21 @@ class _CTree(ctypes.Structure):
                 ("threshold", ctypes.c_void_p)]
 
 
+def _is_current(path):
+    """True if the library file was compiled from the sources as they are now: its version string
+    (lutnn_version()) ends in their hash.  Read from the file, so a stale library is never mapped."""
+    with open(path, "rb") as f:
+        return (b"+" + _build.source_hash().encode() + b"\0") in f.read()
+
+
 def _load():
     path = _build.LIB
-    if not os.path.exists(path):
+    if not os.path.exists(path) or not _is_current(path):
         _build.build()  # raises if hipcc is missing or the compile fails
     lib = ctypes.CDLL(path)
-    if not all(hasattr(lib, name) for name in EXPORTS):
-        # a library left over from older sources: unload it, rebuild, load again
-        import _ctypes
-        _ctypes.dlclose(lib._handle)
-        del lib
-        _build.build()
-        lib = ctypes.CDLL(path)
+    missing = [name for name in EXPORTS if not hasattr(lib, name)]
+    if missing:
+        raise ImportError("liblutnn.so lacks %s" % ", ".join(missing))
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     lib.lutnn_table_bytes.restype = ctypes.c_size_t
     lib.lutnn_table_bytes.argtypes = [i32, i32, i32, i32]
@@ -115,6 +118,8 @@ def _load():
     lib.lutnn_status_string.argtypes = [i32]
     lib.lutnn_last_error.restype = ctypes.c_char_p
     lib.lutnn_version.restype = ctypes.c_char_p
+    lib.lutnn_set_tunable.restype = i32
+    lib.lutnn_set_tunable.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
     return lib
 
 
@@ -137,6 +142,28 @@ def _ptr(t):
 
 def _variant(v):
     return VARIANTS[v] if isinstance(v, str) else int(v)
+
+
+def set_tunable(name, value=None):
+    """lutnn_set_tunable: pin ("small", "1", "256", ...) or release (None) a launcher's choice."""
+    _check(LIB.lutnn_set_tunable(name.encode(), None if value is None else str(value).encode()))
+
+
+class tunables:
+    """Context manager: pins the given switches for the block, releases them afterwards."""
+
+    def __init__(self, **pins):
+        self.pins = pins
+
+    def __enter__(self):
+        for name, value in self.pins.items():
+            set_tunable(name, value)
+        return self
+
+    def __exit__(self, *exc):
+        for name in self.pins:
+            set_tunable(name, None)
+        return False
 
 
 def version():

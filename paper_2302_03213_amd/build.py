@@ -6,6 +6,7 @@ Objects go to _build/ at the repository root (not committed); the shared library
 next to this file so that it travels with the source tree.
 """
 import concurrent.futures
+import hashlib
 import os
 import subprocess
 import sys
@@ -28,9 +29,23 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
          "-Wall", "-Wno-unused-function", "-I", INCLUDE, "-I", CSRC]
 
 
+def source_hash():
+    """12 hex digits over every file the library is compiled from (csrc/*, include/lutnn.h); the
+    library reports it through lutnn_version() so that the loader can tell a stale binary."""
+    h = hashlib.sha256()
+    files = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith((".hip", ".h"))]
+    for path in files + headers():
+        h.update(os.path.basename(path).encode() + b"\0")
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:12]
+
+
 def _compile(src):
     obj = os.path.join(OBJDIR, os.path.splitext(src)[0] + ".o")
     cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+    if src == "api.hip":
+        cmd.append('-DLUTNN_SOURCE_HASH="%s"' % source_hash())
     r = subprocess.run(cmd, capture_output=True, text=True)
     out = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                     if "packed-fp32-ops" not in l)  # host pass does not know the device feature
@@ -39,10 +54,8 @@ def _compile(src):
     return obj, out
 
 
-def build(verbose=False, save_temps=False):
+def build(verbose=False):
     os.makedirs(OBJDIR, exist_ok=True)
-    if save_temps:
-        FLAGS.extend(["-save-temps=obj"])
     with concurrent.futures.ThreadPoolExecutor(max_workers=6) as ex:
         results = list(ex.map(_compile, SOURCES))
     if verbose:
@@ -60,4 +73,4 @@ def headers():
 
 
 if __name__ == "__main__":
-    print(build(verbose=True, save_temps="--save-temps" in sys.argv))
+    print(build(verbose=True))

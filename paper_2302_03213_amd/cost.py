@@ -5,6 +5,14 @@ traffic figures the benchmark prices against the MI355X rooflines.  Pure host ar
 PEAK_HBM_BYTES_PER_S = 8.0e12
 PEAK_MFMA_INT8_OPS_PER_S = 5.0e15
 PEAK_VALU_F32_LANE_OPS_PER_S = 256 * 64 * 2.4e9  # 256 CUs x 64 lanes x 2.4 GHz, one op per lane-clock
+PEAK_LDS_BYTES_PER_S = 256 * 128 * 2.4e9         # 256 CUs x 128 bytes per clock x 2.4 GHz = 78.6 TB/s
+
+# One 32x32 int8 matrix instruction - dense v_mfma_i32_32x32x32_i8 or 2:4-sparse
+# v_smfmac_i32_32x32x64_i8 - holds its SIMD's matrix pipe for 32 cycles, the time in which the dense
+# form performs 2*32*32*32 = 65,536 ops.  1024 SIMDs x 65,536 / 32 cycles x 2.4 GHz = 5.03e15: the
+# published dense peak, so pricing every issued instruction at 65,536 ops against that peak gives the
+# share of the pipes' time the kernel's instructions occupy.
+MFMA_I8_32X32_OPS_PER_PIPE_SLOT = 2 * 32 * 32 * 32
 
 
 def lut_flops(N, D, M, K, V):
@@ -70,6 +78,20 @@ def lookup_entries(N, C, M):
 def lookup_mfma_ops(N, C, M, kpad=16):
     """Dense INT8 ops of the one-hot contraction: 2 * N * (C*kpad) * M (1/kpad of them useful)."""
     return 2 * N * C * kpad * M
+
+
+def lookup_matrix_instructions(N, C, M, sparse, kpad=16):
+    """32x32 int8 matrix instructions of the one-hot contraction OneHot[N x C*kpad] x T[C*kpad x M]: a
+    dense instruction covers 32 of the contraction's C*kpad positions (two codebooks at kpad = 16), a
+    2:4-sparse one 64 (four codebooks).  Unpadded (algorithmic) count; may be fractional."""
+    per = 64 if sparse else 32
+    return N * M * C * kpad / (32 * 32 * per)
+
+
+def lookup_lds_floor_s(N, C, M, table_elem_bytes):
+    """Time for Eq. 4's N*C*M table entries to cross the LDS once at its peak rate: the floor of a
+    gather kernel that reads every entry it adds from LDS."""
+    return N * C * M * table_elem_bytes / PEAK_LDS_BYTES_PER_S
 
 
 def lookup_hbm_bytes(N, C, K, M, table_elem_bytes):

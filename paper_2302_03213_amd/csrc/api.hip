@@ -2,11 +2,13 @@
 // include/lutnn.h.  Nothing here allocates device memory or synchronises.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "lutnn.h"
 #include "lutnn_kernels.h"
@@ -26,6 +28,32 @@ lutnn_status fail(lutnn_status st, const char* fmt, ...) {
 lutnn_status hip_result(hipError_t e, const char* what) {
     if (e == hipSuccess) return LUTNN_OK;
     return fail(LUTNN_E_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// ---- tuning switches (lutnn_kernels.h)
+const char* const kTunableNames[lutnn::kTuneCount] = {"LUTNN_FUSED_KERNEL", "LUTNN_SMFMAC_SPLIT",
+                                                      "LUTNN_SMFMAC_TILE_ROWS"};
+std::atomic<int> g_tunable[lutnn::kTuneCount];
+std::once_flag g_tunable_once;
+
+// Text of a switch -> its value; -1 for NULL, empty or anything not understood.
+int parse_tunable(int which, const char* text) {
+    if (!text || !*text) return -1;
+    if (which == lutnn::kTuneFusedKernel) {
+        if (std::strcmp(text, "small") == 0) return 1;
+        if (std::strcmp(text, "tile") == 0) return 0;
+        return -1;
+    }
+    char* end = nullptr;
+    const long v = std::strtol(text, &end, 10);
+    if (*end != 0) return -1;
+    if (which == lutnn::kTuneSmfmacSplit) return (v == 0 || v == 1) ? (int)v : -1;
+    return (v == 128 || v == 256 || v == 384 || v == 512) ? (int)v : -1;
+}
+
+void tunables_from_environment() {
+    for (int i = 0; i < lutnn::kTuneCount; ++i)
+        g_tunable[i].store(parse_tunable(i, std::getenv(kTunableNames[i])), std::memory_order_relaxed);
 }
 
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -200,7 +228,42 @@ lutnn_status check_conv_input(const lutnn_layer* L, const float* input) {
 
 }  // namespace
 
+namespace lutnn {
+
+int tunable(int which) {
+    std::call_once(g_tunable_once, tunables_from_environment);
+    return g_tunable[which].load(std::memory_order_relaxed);
+}
+
+int compute_units() {
+    constexpr int kDevices = 64;
+    static std::atomic<int> cached[kDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kDevices) return 256;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
+
+}  // namespace lutnn
+
 extern "C" {
+
+lutnn_status lutnn_set_tunable(const char* name, const char* value) {
+    if (!name) return fail(LUTNN_E_NULL, "name is NULL");
+    std::call_once(g_tunable_once, tunables_from_environment);
+    for (int i = 0; i < lutnn::kTuneCount; ++i)
+        if (std::strcmp(name, kTunableNames[i]) == 0) {
+            const int v = parse_tunable(i, value);
+            if (value && *value && v < 0) return fail(LUTNN_E_SHAPE, "%s does not take the value '%s'", name, value);
+            g_tunable[i].store(v, std::memory_order_relaxed);
+            return LUTNN_OK;
+        }
+    return fail(LUTNN_E_UNSUPPORTED, "no tuning switch named '%s'", name);
+}
 
 size_t lutnn_table_bytes(int32_t C, int32_t K, int32_t M, int32_t dtype) {
     if (C <= 0 || K <= 0 || M <= 0) return 0;
@@ -271,10 +334,16 @@ size_t lutnn_softpq_workspace_bytes(int32_t C, int32_t K, int32_t V, int64_t N) 
     return lutnn::softpq_workspace_bytes(C, K, V, N);
 }
 
-lutnn_status lutnn_softpq_backward(const lutnn_layer* layer, float temperature, const float* X, int64_t N,
-                                   int64_t ldx, const float* Z, int64_t ldz, float* dP, float* dX,
-                                   int64_t lddx, float* dt, void* workspace, size_t workspace_bytes,
-                                   void* stream) {
+}  // extern "C"
+
+namespace {
+
+// Validation shared by the two forms of the soft-PQ backward entry point; everything but the
+// scratch buffer, whose size in bytes the caller of this function has already established.
+lutnn_status softpq_backward_checked(const lutnn_layer* layer, float temperature, const float* X, int64_t N,
+                                     int64_t ldx, const float* Z, int64_t ldz, float* dP, float* dX,
+                                     int64_t lddx, float* dt, void* workspace, size_t workspace_bytes,
+                                     const char* what_scratch, void* stream) {
     if (lutnn_status st = check_layer(layer)) return st;
     if (!(temperature > 0.0f) || !std::isfinite(temperature))
         return fail(LUTNN_E_SHAPE, "temperature must be positive and finite (got %g)", (double)temperature);
@@ -293,7 +362,8 @@ lutnn_status lutnn_softpq_backward(const lutnn_layer* layer, float temperature, 
         if (!workspace) return fail(LUTNN_E_NULL, "workspace is NULL");
         const size_t need = lutnn::softpq_workspace_bytes(layer->C, layer->K, layer->V, N);
         if (workspace_bytes < need)
-            return fail(LUTNN_E_SHAPE, "workspace of %zu bytes is smaller than the %zu needed", workspace_bytes, need);
+            return fail(LUTNN_E_SHAPE, "%s of %zu bytes is smaller than the %zu this shape needs (C=%d K=%d V=%d N=%lld)",
+                        what_scratch, workspace_bytes, need, layer->C, layer->K, layer->V, (long long)N);
     }
     if (!aligned(Z, 4) || !aligned(dP, 4) || !aligned(dX, 4) || !aligned(dt, 4) || !aligned(workspace, 4))
         return fail(LUTNN_E_ALIGN, "Z, dP, dX, dt and workspace must be 4-byte aligned");
@@ -303,6 +373,18 @@ lutnn_status lutnn_softpq_backward(const lutnn_layer* layer, float temperature, 
                                                     X, N, ldx, Z, ldz, dP, dX, lddx, dt,
                                                     static_cast<float*>(workspace), s),
                       "soft-PQ backward launch");
+}
+
+}  // namespace
+
+extern "C" {
+
+lutnn_status lutnn_softpq_backward(const lutnn_layer* layer, float temperature, const float* X, int64_t N,
+                                   int64_t ldx, const float* Z, int64_t ldz, float* dP, float* dX,
+                                   int64_t lddx, float* dt, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+    return softpq_backward_checked(layer, temperature, X, N, ldx, Z, ldz, dP, dX, lddx, dt, workspace,
+                                   workspace_bytes, "workspace", stream);
 }
 
 lutnn_status lutnn_lookup(const lutnn_layer* layer, const uint8_t* idx, int64_t N, float* Y,
@@ -336,17 +418,16 @@ bool small_preferred(const lutnn_layer* L, int64_t N) {
 }
 
 // Which of the two one-kernel forms FUSED runs: the one-launch kernel for small problems where it
-// is the faster one, or where the tile kernel cannot run at all; LUTNN_FUSED_KERNEL = small | tile
-// pins the choice (tests that must reach both).
+// is the faster one, or where the tile kernel cannot run at all; the switch LUTNN_FUSED_KERNEL =
+// small | tile pins the choice (tests that must reach both).
 bool fused_takes_small_kernel(const lutnn_layer* L, int64_t N) {
     const int kind = small_table_kind(L);
     const bool can_small = lutnn::linear_small_supported(L->table, kind, L->C, L->K, L->V, L->M);
     const bool can_tile = lutnn::fused_supported(L->C, L->K, L->V, L->M, L->table_dtype) &&
                           (L->table_dtype == LUTNN_TABLE_F32 ? L->table != nullptr : L->table_packed != nullptr);
-    if (const char* e = std::getenv("LUTNN_FUSED_KERNEL")) {
-        if (std::strcmp(e, "small") == 0 && can_small) return true;
-        if (std::strcmp(e, "tile") == 0 && can_tile) return false;
-    }
+    const int pinned = lutnn::tunable(lutnn::kTuneFusedKernel);
+    if (pinned == 1 && can_small) return true;
+    if (pinned == 0 && can_tile) return false;
     if (!can_small) return false;
     return !can_tile || small_preferred(L, N);
 }
@@ -595,6 +676,9 @@ int32_t lutnn_linear_auto_variant(const lutnn_layer* layer, const uint8_t* idx_w
 
 const char* lutnn_last_error(void) { return g_err; }
 
-const char* lutnn_version(void) { return "0.1.0"; }
+#ifndef LUTNN_SOURCE_HASH
+#define LUTNN_SOURCE_HASH "unknown"
+#endif
+const char* lutnn_version(void) { return "0.2.0+" LUTNN_SOURCE_HASH; }
 
 }  // extern "C"

@@ -66,7 +66,6 @@ constexpr int SC = 16;                // codebooks per stage
 constexpr int KSTEPS = 4;             // MFMA steps per stage, 4 codebooks each
 constexpr int STAGE_VECS = SC * BN;   // uint4 per stage buffer (32 KiB)
 constexpr int B_LOADS = 8;            // table loads per wave per stage
-constexpr int kComputeUnits = 256;    // MI355X: 8 XCDs x 32 CUs
 
 // 64 lanes x 16 bytes global -> LDS at (lds_base + LDS_IMM) + 16 * lane; see dma16().
 template <int LDS_IMM>
@@ -516,6 +515,7 @@ hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias
     // against 0.042 ms at 512 rows of the first, break-even at 2048 rows; break-even at 256 rows of
     // the second).  Each share keeps at least 64 codebooks.  LUTNN_SMFMAC_SPLIT = 0 | 1 pins the
     // decision (sweeps, and tests that must reach both paths).
+    const int kComputeUnits = compute_units();
     if (tiles <= kComputeUnits / 2 && C >= 512) {
         const int supers = C / 32;
         int splits = 1;
@@ -527,10 +527,7 @@ hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias
         const double saved_us = 0.024 * C * (1.0 - 1.0 / splits);
         const double cost_us = 6.0 + 14e-6 * (double)N * M;
         bool split = saved_us > cost_us;
-        if (const char* e = std::getenv("LUTNN_SMFMAC_SPLIT")) {
-            if (e[0] == '0' && e[1] == 0) split = false;
-            if (e[0] == '1' && e[1] == 0) split = true;
-        }
+        if (const int pinned = tunable(kTuneSmfmacSplit); pinned >= 0) split = pinned == 1;
         if (!split) splits = 1;
         if (splits > 1) {
             const dim3 cells((unsigned)((M + 255) / 256), (unsigned)N);
@@ -574,20 +571,19 @@ hipError_t launch_lookup_smfmac_i8(const int8_t* packed, const float* scale, con
     // the 512-row tile: 0.8 for 384 rows, 0.56 for 256, 0.42 for 128 - the slab traffic does not
     // shrink).
     const int64_t col_tiles = (M + BN - 1) / BN;
+    const int kComputeUnits = compute_units();
     auto cost = [&](int64_t bm, double rel) {
         const int64_t tiles = ((N + bm - 1) / bm) * col_tiles;
         return (double)((tiles + kComputeUnits - 1) / kComputeUnits) * rel;
     };
     // LUTNN_SMFMAC_TILE_ROWS = 128 | 256 | 384 | 512 pins the height (tuning sweeps, and tests that
     // must reach every instance whatever the prices below say); anything else is ignored.
-    if (const char* e = std::getenv("LUTNN_SMFMAC_TILE_ROWS")) {
-        switch (std::atoi(e)) {
-            case 512: return launch_tm<4>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
-            case 384: return launch_tm<3>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
-            case 256: return launch_tm<2>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
-            case 128: return launch_tm<1>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
-            default: break;
-        }
+    switch (tunable(kTuneSmfmacTileRows)) {
+        case 512: return launch_tm<4>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
+        case 384: return launch_tm<3>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
+        case 256: return launch_tm<2>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
+        case 128: return launch_tm<1>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
+        default: break;
     }
     const double c4 = cost(512, 1.0), c3 = cost(384, 0.8), c2 = cost(256, 0.56), c1 = cost(128, 0.42);
     const double best = std::min(std::min(c4, c3), std::min(c2, c1));

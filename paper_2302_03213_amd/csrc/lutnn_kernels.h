@@ -13,6 +13,20 @@ constexpr int kPackedColPad = 256;
 inline int64_t packed_cols(int64_t M) { return (M + kPackedColPad - 1) / kPackedColPad * kPackedColPad; }
 inline int kblocks(int K) { return (K + 15) / 16; }
 
+// Tuning switches that pin a launcher's choice (sweeps, and tests that must reach every kernel
+// instance).  Each starts from the environment variable of the same name, read once when the first
+// switch is asked for, and can be changed through lutnn_set_tunable; -1 = not pinned.  Atomic.
+enum Tunable {
+    kTuneFusedKernel = 0,   // LUTNN_FUSED_KERNEL: 0 = "tile", 1 = "small"
+    kTuneSmfmacSplit,       // LUTNN_SMFMAC_SPLIT: 0 | 1
+    kTuneSmfmacTileRows,    // LUTNN_SMFMAC_TILE_ROWS: 128 | 256 | 384 | 512
+    kTuneCount
+};
+int tunable(int which);
+
+// Compute units of the current device (queried once per device; 256 on an MI355X).
+int compute_units();
+
 // A convolution seen as a matrix product (Sec. 4): row n = (image b, output pixel ho, wo),
 // column j = (input channel ci, filter row r, filter column s) with ci slowest, element
 // input[b][ci][ho*sh + r - ph][wo*sw + s - pw] or 0 outside the image.

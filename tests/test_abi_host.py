@@ -70,7 +70,7 @@ def test_status_strings_and_version(lut):
     names = [lut.LIB.lutnn_status_string(i).decode() for i in range(7)]
     assert names == ["LUTNN_OK", "LUTNN_E_NULL", "LUTNN_E_SHAPE", "LUTNN_E_UNSUPPORTED",
                      "LUTNN_E_ALIGN", "LUTNN_E_HIP", "LUTNN_E_UNKNOWN"]
-    assert re.fullmatch(r"\d+\.\d+\.\d+", lut.version())
+    assert re.fullmatch(r"\d+\.\d+\.\d+\+[0-9a-f]{12}", lut.version())
 
 
 def _layer(lut, **kw):
@@ -289,6 +289,30 @@ def test_softpq_backward_validation_and_workspace_query(lut):
     for i, (code, want) in enumerate(cases):
         name, detail = _status(lut, code)
         assert name == want, "case %d: got %s (%s), wanted %s" % (i, name, detail, want)
+
+
+def test_tuning_switches(lut):
+    for name, good, bad in (("LUTNN_FUSED_KERNEL", ("small", "tile"), "both"),
+                            ("LUTNN_SMFMAC_SPLIT", ("0", "1"), "2"),
+                            ("LUTNN_SMFMAC_TILE_ROWS", ("128", "256", "384", "512"), "200")):
+        for v in good:
+            lut.set_tunable(name, v)
+        with pytest.raises(lut.LutnnError) as e:
+            lut.set_tunable(name, bad)
+        assert e.value.name == "LUTNN_E_SHAPE"
+        lut.set_tunable(name, None)
+        lut.set_tunable(name, "")
+    with pytest.raises(lut.LutnnError) as e:
+        lut.set_tunable("LUTNN_NO_SUCH_SWITCH", "1")
+    assert e.value.name == "LUTNN_E_UNSUPPORTED"
+    assert lut.LIB.lutnn_set_tunable(None, b"1") == 1
+    with lut.tunables(LUTNN_SMFMAC_SPLIT=1):
+        pass
+
+
+def test_version_carries_the_hash_of_the_sources(lut):
+    from paper_2302_03213_amd import build
+    assert lut.version().endswith("+" + build.source_hash())
 
 
 def test_auto_variant_rule(lut):

@@ -21,8 +21,10 @@ def lut():
 
 
 @pytest.fixture(autouse=True)
-def pin_small(monkeypatch):
-    monkeypatch.setenv("LUTNN_FUSED_KERNEL", "small")
+def pin_small(lut):
+    lut.set_tunable("LUTNN_FUSED_KERNEL", "small")
+    yield
+    lut.set_tunable("LUTNN_FUSED_KERNEL", None)
 
 
 def run_case(lut, w, with_bias=True, x_pad=0, y_pad=0):
@@ -90,8 +92,8 @@ def test_one_launch_equals_encode_then_gather(lut):
             np.testing.assert_allclose(got, two, rtol=1e-5, atol=1e-5)
 
 
-def test_auto_takes_one_launch_for_small_problems(lut, monkeypatch):
-    monkeypatch.delenv("LUTNN_FUSED_KERNEL")
+def test_auto_takes_one_launch_for_small_problems(lut):
+    lut.set_tunable("LUTNN_FUSED_KERNEL", None)
     w = wl.fc_small(0)
     layer = lut.build_table(dev(w.P), dev(w.W), lut.TABLE_F32, bias=dev(w.bias))
     ws = torch.empty((w.N, w.C), dtype=torch.uint8, device="cuda")

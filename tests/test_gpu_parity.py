@@ -32,6 +32,19 @@ def announce(request):
     yield
 
 
+@pytest.fixture
+def pin(lut):
+    """pin(NAME, value): sets one of the library's tuning switches for the rest of the test."""
+    names = []
+
+    def set_one(name, value):
+        lut.set_tunable(name, value)
+        names.append(name)
+    yield set_one
+    for name in names:
+        lut.set_tunable(name, None)
+
+
 def assert_f32_close(got, ref):
     np.testing.assert_allclose(got, ref, rtol=F32_RTOL, atol=F32_ATOL)
 
@@ -163,10 +176,10 @@ SMFMAC_SHAPES = [
 
 @pytest.mark.parametrize("rows", [128, 256, 384, 512])
 @pytest.mark.parametrize("N,C,K,M", [(1500, 96, 16, 300), (2100, 64, 16, 3968), (4700, 64, 16, 4096)])
-def test_lookup_smfmac_every_tile_height(lut, monkeypatch, rows, N, C, K, M):
+def test_lookup_smfmac_every_tile_height(lut, pin, rows, N, C, K, M):
     """Each tile height on ragged rows / columns, one tile per workgroup (C % 64 != 0 or few tiles)
-    and several (the last shape), pinned through the library's tuning variable."""
-    monkeypatch.setenv("LUTNN_SMFMAC_TILE_ROWS", str(rows))
+    and several (the last shape), pinned through the library's tuning switch."""
+    pin("LUTNN_SMFMAC_TILE_ROWS", rows)
     w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=N + rows)
     ol = OracleLayer(w)
     idx = wl.random_indices(N, C, K, seed=N + rows)
@@ -180,16 +193,16 @@ def test_lookup_smfmac_every_tile_height(lut, monkeypatch, rows, N, C, K, M):
                                           (700, 1536, 16, 768, 0), (1029, 512, 16, 260, 0),
                                           (700, 1536, 16, 768, 256), (1029, 1024, 16, 260, 384),
                                           (1300, 1536, 16, 300, 512)])
-def test_lookup_smfmac_codebooks_split_over_workgroups(lut, monkeypatch, N, C, K, M, rows):
+def test_lookup_smfmac_codebooks_split_over_workgroups(lut, pin, N, C, K, M, rows):
     """Few tiles, many codebooks: several workgroups share an output tile, each with a range of the
     codebooks, and add int32 partial sums into Y (zeroed before, dequantised after).  Bit-exact, with
     and without bias, into a strided Y whose guard band must stay untouched.  (544 codebooks = 17
     groups of 32 cannot be split evenly: that shape takes the unsplit kernel.)  The split is pinned
-    through the library's tuning variable so that the test does not depend on its price list; the
+    through the library's tuning switch so that the test does not depend on its price list; the
     last cases also pin the tile height to reach the taller split instances."""
-    monkeypatch.setenv("LUTNN_SMFMAC_SPLIT", "1")
+    pin("LUTNN_SMFMAC_SPLIT", 1)
     if rows:
-        monkeypatch.setenv("LUTNN_SMFMAC_TILE_ROWS", str(rows))
+        pin("LUTNN_SMFMAC_TILE_ROWS", rows)
     w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=N + C + M)
     ol = OracleLayer(w)
     ol.q = wl.random_table_i8(C, K, M, seed=C + M)
@@ -424,17 +437,16 @@ def check_linear(lut, w, variants, X=None):
     clean = (idx_gpu == idx_ref).all(axis=1)
     assert flips <= max(1, idx_ref.size // 10000)
     # "fused" has two forms (a one-launch kernel for small problems, a tile kernel); the library's
-    # tuning variable pins each in turn where it can run, so both are compared whatever AUTO prefers
+    # tuning switch pins each in turn where it can run, so both are compared whatever AUTO prefers
     runs = []
     for v in variants:
         runs += [(v, form) for form in ("tile", "small")] if v == "fused" else [(v, None)]
     for v, form in runs:
-        if form:
-            os.environ["LUTNN_FUSED_KERNEL"] = form
+        lut.set_tunable("LUTNN_FUSED_KERNEL", form)
         try:
             got = host(lut.linear(layer, Xd, v))
         finally:
-            os.environ.pop("LUTNN_FUSED_KERNEL", None)
+            lut.set_tunable("LUTNN_FUSED_KERNEL", None)
         if w.table_dtype == "i8":
             np.testing.assert_array_equal(got[clean], ref[clean], err_msg="variant %s %s" % (v, form))
             # rows holding a flipped near-tie: one table entry swapped per flip
