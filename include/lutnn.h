@@ -30,7 +30,8 @@
  *   - Outputs must not alias inputs.  Some lookups use Y itself as integer scratch before the final
  *     values are written, so Y must not be read by anyone else while a call on it is in flight.
  *   - The library keeps no state between calls (the last-error text is per host thread): calls from
- *     several host threads and on several streams may run concurrently.
+ *     several host threads and on several streams may run concurrently.  The one exception is
+ *     lutnn_softpq_backward_static, whose calls share a static scratch array per GPU.
  */
 #ifndef LUTNN_H
 #define LUTNN_H
@@ -264,6 +265,31 @@ LUTNN_API lutnn_status lutnn_softpq_backward(const lutnn_layer* layer, float tem
 
 /* Host: bytes of workspace lutnn_softpq_backward needs; 0 for unsupported (K, V) or empty shapes. */
 LUTNN_API size_t lutnn_softpq_workspace_bytes(int32_t C, int32_t K, int32_t V, int64_t N);
+
+/*
+ * lutnn_softpq_backward for callers that cannot allocate device memory and have no workspace to
+ * pass: code under HIP graph capture, tight serving or training loops, harnesses that forbid
+ * hipMalloc.  Same arguments without the workspace, same kernels, same results bit for bit; the
+ * scratch is a static device array of LUTNN_SOFTPQ_STATIC_SCRATCH_BYTES inside the library (one copy
+ * on every GPU that loads the library, held until the process ends).  The call allocates nothing
+ * and frees nothing.
+ *   - A shape whose lutnn_softpq_workspace_bytes(C, K, V, N) exceeds the array is refused with
+ *     E_SHAPE before anything is enqueued.  The need grows with N up to a bound that the paper's
+ *     settings keep under 17 MB (N = 16384, C = 1024, K = 16, V = 4: 8.4 MB; K = 16, V = 32 with 128
+ *     or more codebooks: 16.8 MB); only layers of several million centroid values exceed 32 MiB.
+ *   - The device the stream belongs to must be the current device (E_HIP otherwise).  The first
+ *     call on a device looks the array's address up once (hipGetSymbolAddress); make that call
+ *     outside stream capture.
+ *   - All calls on one GPU share the one array: two calls whose kernels may overlap on that GPU
+ *     (different streams, or several host threads on different streams) race on it.  Calls on one
+ *     stream are ordered and safe.  Contents are unspecified between calls.
+ * Errors: as lutnn_softpq_backward.
+ */
+#define LUTNN_SOFTPQ_STATIC_SCRATCH_BYTES (32u << 20)
+LUTNN_API lutnn_status lutnn_softpq_backward_static(const lutnn_layer* layer, float temperature,
+                                                    const float* X, int64_t N, int64_t ldx,
+                                                    const float* Z, int64_t ldz, float* dP, float* dX,
+                                                    int64_t lddx, float* dt, void* stream);
 
 /*
  * A 2-D convolution as the operator above (Sec. 4: a convolution becomes a matrix product by

@@ -4,7 +4,7 @@ from .binding import (LIB, TABLE_F32, TABLE_I4, TABLE_I8, VARIANT_AUTO, VARIANT_
                       VARIANT_MFMA, VARIANT_SMFMAC, LutLayer, LutTree, LutnnError, auto_variant, build_table,
                       conv2d, conv2d_rows, conv2d_tree, conv_geom, encode, encode_conv2d, encode_tree,
                       encode_tree_conv2d, linear, linear_auto_variant,
-                      linear_tree, lookup, set_tunable, softpq_backward,
+                      linear_tree, lookup, set_tunable, softpq_backward, softpq_backward_static,
                       softpq_workspace_bytes, tunables,
                       packed_bytes, table_bytes, version)
 from . import cost  # noqa: F401

@@ -27,7 +27,7 @@ VARIANT_SMFMAC = 4
 VARIANTS = {"auto": VARIANT_AUTO, "lds": VARIANT_LDS, "mfma": VARIANT_MFMA, "fused": VARIANT_FUSED,
             "smfmac": VARIANT_SMFMAC}
 
-EXPORTS = ["lutnn_set_tunable", "lutnn_table_bytes", "lutnn_packed_bytes", "lutnn_build_table", "lutnn_encode",
+EXPORTS = ["lutnn_softpq_backward_static", "lutnn_set_tunable", "lutnn_table_bytes", "lutnn_packed_bytes", "lutnn_build_table", "lutnn_encode",
            "lutnn_lookup", "lutnn_linear", "lutnn_encode_tree", "lutnn_linear_tree",
            "lutnn_softpq_backward", "lutnn_softpq_workspace_bytes",
            "lutnn_encode_tree_conv2d", "lutnn_conv2d_tree", "lutnn_conv2d_rows", "lutnn_encode_conv2d", "lutnn_conv2d",
@@ -98,6 +98,9 @@ def _load():
     lib.lutnn_softpq_backward.restype = i32
     lib.lutnn_softpq_backward.argtypes = [ctypes.POINTER(_CLayer), ctypes.c_float, vp, i64, i64, vp, i64, vp,
                                           vp, i64, vp, vp, ctypes.c_size_t, vp]
+    lib.lutnn_softpq_backward_static.restype = i32
+    lib.lutnn_softpq_backward_static.argtypes = [ctypes.POINTER(_CLayer), ctypes.c_float, vp, i64, i64, vp, i64,
+                                                 vp, vp, i64, vp, vp]
     lib.lutnn_encode_tree_conv2d.restype = i32
     lib.lutnn_encode_tree_conv2d.argtypes = [ctypes.POINTER(_CTree), vp, i64, ctypes.POINTER(_CConvGeom), vp, vp]
     lib.lutnn_conv2d_tree.restype = i32
@@ -310,6 +313,26 @@ def softpq_backward(layer, temperature, X, Z, need_dx=True, workspace=None):
                                      dX.stride(0) if need_dx else 0, _ptr(dt), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), _stream()))
     return dP, dX, dt
+
+
+def softpq_backward_static(layer, temperature, X, Z, need_dx=True, dP=None, dX=None, dt=None):
+    """lutnn_softpq_backward_static: the same gradients with the library's static scratch array in
+    place of a workspace.  Pass dP, dX, dt to have the call itself allocate nothing."""
+    assert X.is_cuda and X.dtype == torch.float32 and X.stride(1) == 1
+    assert Z.is_cuda and Z.dtype == torch.float32 and Z.stride(1) == 1 and Z.shape == X.shape
+    N = X.shape[0]
+    if dP is None:
+        dP = torch.empty((layer.C, layer.K, layer.V), dtype=torch.float32, device=X.device)
+    if dX is None and need_dx:
+        dX = torch.empty((N, layer.C * layer.V), dtype=torch.float32, device=X.device)
+    if dt is None:
+        dt = torch.empty(1, dtype=torch.float32, device=X.device)
+    assert dP.is_contiguous() and dP.shape == (layer.C, layer.K, layer.V) and dt.numel() == 1
+    assert not need_dx or (dX.stride(1) == 1 and dX.shape == (N, layer.C * layer.V))
+    _check(LIB.lutnn_softpq_backward_static(ctypes.byref(layer.c), float(temperature), _ptr(X), N, X.stride(0),
+                                            _ptr(Z), Z.stride(0), _ptr(dP), _ptr(dX) if need_dx else None,
+                                            dX.stride(0) if need_dx else 0, _ptr(dt), _stream()))
+    return dP, (dX if need_dx else None), dt
 
 
 def _pair(v):

@@ -377,6 +377,45 @@ lutnn_status softpq_backward_checked(const lutnn_layer* layer, float temperature
 
 }  // namespace
 
+// Scratch of lutnn_softpq_backward_static: one copy per GPU that loads this library, held until the
+// process ends.  In host code this name is only a handle for hipGetSymbolAddress; the address a
+// kernel may use is the one that call returns, on the device it was made for.
+static __device__ __align__(256) unsigned char scratch[LUTNN_SOFTPQ_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device, looked up once per device.
+lutnn_status scratch_of_current_device(void* stream, void** out) {
+    int dev = -1;
+    if (hipError_t e = hipGetDevice(&dev)) return hip_result(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(LUTNN_E_HIP, "device ordinal %d outside 0..%d", dev, kMaxDevices - 1);
+    if (stream) {  // the array is per device: the stream's kernels must run where the address is valid
+        hipDevice_t sdev = -1;
+        if (hipError_t e = hipStreamGetDevice(static_cast<hipStream_t>(stream), &sdev))
+            return hip_result(e, "hipStreamGetDevice");
+        if ((int)sdev != dev)
+            return fail(LUTNN_E_HIP, "stream belongs to device %d but device %d is current", (int)sdev, dev);
+    }
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+        if (!p) {
+            if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) return hip_result(e, "hipGetSymbolAddress");
+            if (!p) return fail(LUTNN_E_HIP, "hipGetSymbolAddress returned no address");
+            g_scratch_ptr[dev].store(p, std::memory_order_release);
+        }
+    }
+    *out = p;
+    return LUTNN_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 lutnn_status lutnn_softpq_backward(const lutnn_layer* layer, float temperature, const float* X, int64_t N,
@@ -385,6 +424,27 @@ lutnn_status lutnn_softpq_backward(const lutnn_layer* layer, float temperature, 
                                    void* stream) {
     return softpq_backward_checked(layer, temperature, X, N, ldx, Z, ldz, dP, dX, lddx, dt, workspace,
                                    workspace_bytes, "workspace", stream);
+}
+
+lutnn_status lutnn_softpq_backward_static(const lutnn_layer* layer, float temperature, const float* X,
+                                          int64_t N, int64_t ldx, const float* Z, int64_t ldz, float* dP,
+                                          float* dX, int64_t lddx, float* dt, void* stream) {
+    // size first, on the host alone: a shape beyond the static array is refused before anything
+    // touches the device
+    if (lutnn_status st = check_layer(layer)) return st;
+    if (N > 0 && lutnn::softpq_supported(layer->K, layer->V) && N < kMaxRows) {
+        const size_t need = lutnn::softpq_workspace_bytes(layer->C, layer->K, layer->V, N);
+        if (need > (size_t)LUTNN_SOFTPQ_STATIC_SCRATCH_BYTES)
+            return fail(LUTNN_E_SHAPE, "this shape needs %zu bytes of scratch, the static buffer holds %zu "
+                        "(C=%d K=%d V=%d N=%lld): use lutnn_softpq_backward with a workspace",
+                        need, (size_t)LUTNN_SOFTPQ_STATIC_SCRATCH_BYTES, layer->C, layer->K, layer->V, (long long)N);
+    }
+    void* ptr = nullptr;
+    if (lutnn_status st = scratch_of_current_device(stream, &ptr)) return st;
+    // every partial sum the second kernel reads is written by the first in the same call, so
+    // nothing of the previous call's contents has to be cleared
+    return softpq_backward_checked(layer, temperature, X, N, ldx, Z, ldz, dP, dX, lddx, dt, ptr,
+                                   (size_t)LUTNN_SOFTPQ_STATIC_SCRATCH_BYTES, "the static scratch buffer", stream);
 }
 
 lutnn_status lutnn_lookup(const lutnn_layer* layer, const uint8_t* idx, int64_t N, float* Y,

@@ -291,6 +291,20 @@ def test_softpq_backward_validation_and_workspace_query(lut):
         assert name == want, "case %d: got %s (%s), wanted %s" % (i, name, detail, want)
 
 
+def test_static_scratch_form_refuses_oversize_shapes_on_the_host(lut):
+    """lutnn_softpq_backward_static checks the scratch need against its static array before it
+    touches a device: the refusal needs no GPU."""
+    L, vp, f = lut.LIB, ctypes.c_void_p, ctypes.c_float
+    X, Z, DP, DX, DT = (vp(0x10000 * i) for i in range(1, 6))
+    C, K, V, N = 131072, 16, 4, 8
+    assert lut.softpq_workspace_bytes(C, K, V, N) > 32 << 20
+    code = L.lutnn_softpq_backward_static(ctypes.byref(_layer(lut, C=C)), f(1.0), X, N, C * V, Z, C * V, DP, DX,
+                                          C * V, DT, None)
+    name, detail = _status(lut, code)
+    assert name == "LUTNN_E_SHAPE" and "static buffer" in detail, (name, detail)
+    assert L.lutnn_softpq_backward_static(None, f(1.0), X, 8, 16, Z, 16, DP, DX, 16, DT, None) == 1  # E_NULL
+
+
 def test_tuning_switches(lut):
     for name, good, bad in (("LUTNN_FUSED_KERNEL", ("small", "tile"), "both"),
                             ("LUTNN_SMFMAC_SPLIT", ("0", "1"), "2"),
