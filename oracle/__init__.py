@@ -27,9 +27,10 @@ _i32p = ctypes.POINTER(ctypes.c_int32)
 def _lib():
     global _LIB
     if _LIB is None:
-        path = _build.LIB
+        sanitize = os.environ.get("LUTNN_ORACLE_SANITIZE") == "1"  # see build.py
+        path = _build.LIB_SAN if sanitize else _build.LIB
         if not os.path.exists(path) or os.path.getmtime(path) < os.path.getmtime(_build.SRC):
-            _build.build(force=True)
+            _build.build(force=True, sanitize=sanitize)
         lib = ctypes.CDLL(path)
         lib.lutnn_oracle_threads.restype = ctypes.c_int
         lib.lutnn_oracle_set_threads.argtypes = [ctypes.c_int]

@@ -20,6 +20,7 @@ enum Tunable {
     kTuneFusedKernel = 0,   // LUTNN_FUSED_KERNEL: 0 = "tile", 1 = "small"
     kTuneSmfmacSplit,       // LUTNN_SMFMAC_SPLIT: 0 | 1
     kTuneSmfmacTileRows,    // LUTNN_SMFMAC_TILE_ROWS: 128 | 256 | 384 | 512
+    kTuneSmfmacTileCols,    // LUTNN_SMFMAC_TILE_COLS: 32 | 64 | 128
     kTuneCount
 };
 int tunable(int which);
