@@ -70,11 +70,9 @@ typedef enum {
     LUTNN_VARIANT_SMFMAC = 4 /* as MFMA, on the 2:4 structured-sparse matrix instructions: a one-hot
                                 slice is 2:4 sparse by construction, so the result is identical at
                                 twice the matrix rate.  Needs C % 32 == 0, 16-byte aligned idx.
-                                The environment variable LUTNN_SMFMAC_TILE_ROWS (128, 256, 384 or
-                                512), read at every call, pins the rows per workgroup tile that the
-                                library otherwise prices itself; LUTNN_SMFMAC_SPLIT (0 or 1) likewise
-                                pins whether the codebooks of a tile are shared out over several
-                                workgroups: tuning knobs, results are the same                      */
+                                The rows per workgroup tile and whether a tile's codebooks are
+                                shared out over several workgroups are priced by the library;
+                                lutnn_set_tunable pins either (results are the same)                */
 } lutnn_variant;
 
 /*
@@ -83,7 +81,7 @@ typedef enum {
  */
 typedef struct {
     int32_t C;               /* number of codebooks (sub-vectors per row), D = C * V           */
-    int32_t K;               /* centroids per codebook, 1..256                                  */
+    int32_t K;               /* centroids per codebook, 1..256 (..4096 for the 16-bit index calls) */
     int32_t V;               /* sub-vector length                                              */
     int32_t M;               /* output width                                                   */
     int32_t table_dtype;     /* lutnn_table_dtype                                              */
@@ -121,10 +119,11 @@ LUTNN_API size_t lutnn_packed_bytes(int32_t C, int32_t K, int32_t M, int32_t dty
  *   packed_out INT8 / INT4, nullable: the same q re-laid out for the MFMA variants, one int8 per
  *              entry for both dtypes:
  *              [C * ceil(K/16)][Mp][16] int8 with Mp = M rounded up to 256, k fastest,
- *              zero padded.  Must be 16-byte aligned.
+ *              zero padded.  Must be 16-byte aligned.  K <= 256 only.
  *   scale_out  INT8 / INT4: receives s (one fp32).  Also used as scratch during the call.
+ * K up to 4096 (the tables behind lutnn_lookup16) with packed_out = NULL.
  *
- * Errors: E_NULL, E_SHAPE, E_UNSUPPORTED (unknown dtype), E_ALIGN, E_HIP.
+ * Errors: E_NULL, E_SHAPE, E_UNSUPPORTED (unknown dtype; packed_out with K > 256), E_ALIGN, E_HIP.
  */
 LUTNN_API lutnn_status lutnn_build_table(const float* centroids, const float* W, int64_t ldw,
                                          int32_t C, int32_t K, int32_t V, int32_t M,
@@ -196,7 +195,7 @@ LUTNN_API lutnn_status lutnn_linear(const lutnn_layer* layer, const float* X, in
 typedef struct {
     int32_t C;       /* codebooks                                                             */
     int32_t V;       /* sub-vector length; D = C*V                                            */
-    int32_t levels;  /* 1..8; K = 2^levels buckets                                            */
+    int32_t levels;  /* 1..8 (..12 for the 16-bit index calls); K = 2^levels buckets           */
     int32_t reserved; /* must be 0                                                            */
     const int32_t* split_dim; /* device, [C][2^levels - 1] heap order; values outside [0, V)
                                  are clamped into it                                          */
@@ -230,6 +229,28 @@ LUTNN_API lutnn_status lutnn_linear_tree(const lutnn_layer* layer, const lutnn_t
                                          const float* X, int64_t N, int64_t ldx, float* Y,
                                          int64_t ldy, int32_t variant, uint8_t* idx_workspace,
                                          void* stream);
+
+/*
+ * The hash encoder with deep trees (Sec. 7 evaluates a 12-level tree: 4096 buckets per codebook)
+ * and the lookup behind it, with 16-bit indices.  Same definitions as lutnn_encode_tree,
+ * lutnn_lookup and lutnn_linear_tree; what changes is the index width and the limits:
+ *   tree->levels  1 .. 12                      layer->K  up to 4096 (= 2^levels for lutnn_linear_tree16)
+ *   idx / idx_workspace  [N][C] uint16, dense, 2-byte aligned; values >= K are treated as K - 1
+ *   tables        LUTNN_TABLE_I8 or LUTNN_TABLE_F32, layout [C][K][M] as always (INT4: E_UNSUPPORTED);
+ *                 lutnn_build_table builds them for K up to 4096 when packed_out is NULL
+ * The lookup reads the selected table rows straight from global memory (nothing of a table with
+ * thousands of rows per codebook can be staged), codebooks in ascending order: bit-exact int32 sums
+ * for INT8, a fixed fp32 summation order for fp32 tables.  There is no variant argument.
+ * Up to 8 levels the 8-bit entry points are the faster ones.
+ * Errors: as their 8-bit counterparts.
+ */
+LUTNN_API lutnn_status lutnn_encode_tree16(const lutnn_tree* tree, const float* X, int64_t N,
+                                           int64_t ldx, uint16_t* idx, void* stream);
+LUTNN_API lutnn_status lutnn_lookup16(const lutnn_layer* layer, const uint16_t* idx, int64_t N,
+                                      float* Y, int64_t ldy, void* stream);
+LUTNN_API lutnn_status lutnn_linear_tree16(const lutnn_layer* layer, const lutnn_tree* tree,
+                                           const float* X, int64_t N, int64_t ldx, float* Y,
+                                           int64_t ldy, uint16_t* idx_workspace, void* stream);
 
 /*
  * Soft-PQ backward pass (Sec. 3.1 "Backpropagation through soft-PQ", Eq. 5-6; Sec. 3.2 "Learned
@@ -385,7 +406,6 @@ LUTNN_API const char* lutnn_last_error(void);
  *   "LUTNN_FUSED_KERNEL"      "small" | "tile"          which form LUTNN_VARIANT_FUSED runs
  *   "LUTNN_SMFMAC_SPLIT"      "0" | "1"                 codebooks of a tile shared out over workgroups
  *   "LUTNN_SMFMAC_TILE_ROWS"  "128" | "256" | "384" | "512"   tile height of the sparse matrix-core lookup
- *   "LUTNN_SMFMAC_TILE_COLS"  "32" | "64" | "128"       its tile width (32 and 64 with heights 256 and 512)
  * value NULL or "" returns the switch to "not pinned".  A pinned choice the shape cannot take is
  * ignored.  Process-wide and atomic: safe to call while other threads launch, which then see
  * either the old or the new value.

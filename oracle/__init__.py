@@ -20,6 +20,7 @@ _LIB = None
 _f32p = ctypes.POINTER(ctypes.c_float)
 _f64p = ctypes.POINTER(ctypes.c_double)
 _u8p = ctypes.POINTER(ctypes.c_uint8)
+_u16p = ctypes.POINTER(ctypes.c_uint16)
 _i8p = ctypes.POINTER(ctypes.c_int8)
 _i32p = ctypes.POINTER(ctypes.c_int32)
 
@@ -41,15 +42,15 @@ def _lib():
         lib.lutnn_oracle_encode.argtypes = [_f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int, _f32p,
                                             ctypes.c_int64, ctypes.c_int64, _u8p]
         lib.lutnn_oracle_encode_tree.argtypes = [_i32p, _f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                                 _f32p, ctypes.c_int64, ctypes.c_int64, _u8p]
+                                                 _f32p, ctypes.c_int64, ctypes.c_int64, _u16p]
         lib.lutnn_oracle_distances_f64.argtypes = [_f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                    _f32p, ctypes.c_int64, ctypes.c_int64,
                                                    ctypes.c_int, _f64p]
         lib.lutnn_oracle_lookup_i8.argtypes = [_i8p, ctypes.c_float, _f32p, ctypes.c_int,
-                                               ctypes.c_int, ctypes.c_int, _u8p, ctypes.c_int64,
+                                               ctypes.c_int, ctypes.c_int, _u16p, ctypes.c_int64,
                                                _f32p, ctypes.c_int64, _i32p]
         lib.lutnn_oracle_lookup_f32.argtypes = [_f32p, _f32p, ctypes.c_int, ctypes.c_int,
-                                                ctypes.c_int, _u8p, ctypes.c_int64, _f32p,
+                                                ctypes.c_int, _u16p, ctypes.c_int64, _f32p,
                                                 ctypes.c_int64]
         _LIB = lib
     return _LIB
@@ -129,20 +130,21 @@ def encode(P, X):
 
 def encode_tree(split_dim, threshold, X, V):
     """Hash encoding (Sec. 2, Sec. 7): walk each codebook's balanced threshold tree (heap order,
-    right when x[split] > threshold); idx[n,c] = the leaf reached, counted from the left."""
+    right when x[split] > threshold); idx[n,c] = the leaf reached, counted from the left.  uint8 for
+    up to 8 levels, uint16 for the deeper trees of Sec. 7 (12 levels = 4096 buckets)."""
     split_dim = _c(split_dim, np.int32)
     threshold = _c(threshold, np.float32)
     X = _c(X, np.float32)
     C, nodes = split_dim.shape
     levels = (nodes + 1).bit_length() - 1
-    assert threshold.shape == (C, nodes) and nodes == (1 << levels) - 1 and 1 <= levels <= 8
+    assert threshold.shape == (C, nodes) and nodes == (1 << levels) - 1 and 1 <= levels <= 16
     N, D = X.shape
     assert D == C * V
     assert split_dim.min() >= 0 and split_dim.max() < V
-    idx = np.empty((N, C), dtype=np.uint8)
+    idx = np.empty((N, C), dtype=np.uint16)
     _lib().lutnn_oracle_encode_tree(_ptr(split_dim, _i32p), _ptr(threshold, _f32p), C, levels, V,
-                                    _ptr(X, _f32p), N, D, _ptr(idx, _u8p))
-    return idx
+                                    _ptr(X, _f32p), N, D, _ptr(idx, _u16p))
+    return idx.astype(np.uint8) if levels <= 8 else idx
 
 
 def distances_f64(P, X, n, c):
@@ -157,9 +159,10 @@ def distances_f64(P, X, n, c):
 
 
 def lookup_i8(q, scale, idx, bias=None, return_acc=False):
-    """Eq. 4 on an INT8 table: exact int32 sum, then Y = fma(acc, s, bias)."""
+    """Eq. 4 on an INT8 table: exact int32 sum, then Y = fma(acc, s, bias).  idx: uint8 or uint16."""
     q = _c(q, np.int8)
-    idx = _c(idx, np.uint8)
+    assert np.asarray(idx).dtype in (np.uint8, np.uint16)
+    idx = _c(idx, np.uint16)  # widened, values unchanged
     C, K, M = q.shape
     N = idx.shape[0]
     assert idx.shape[1] == C
@@ -169,15 +172,16 @@ def lookup_i8(q, scale, idx, bias=None, return_acc=False):
     b = None if bias is None else _c(bias, np.float32)
     _lib().lutnn_oracle_lookup_i8(_ptr(q, _i8p), ctypes.c_float(float(scale)),
                                   None if b is None else _ptr(b, _f32p), C, K, M,
-                                  _ptr(idx, _u8p), N, _ptr(Y, _f32p), M,
+                                  _ptr(idx, _u16p), N, _ptr(Y, _f32p), M,
                                   None if acc is None else _ptr(acc, _i32p))
     return (Y, acc) if return_acc else Y
 
 
 def lookup_f32(Tf, idx, bias=None):
-    """Eq. 4 on an fp32 table: double-precision sum rounded once to fp32."""
+    """Eq. 4 on an fp32 table: double-precision sum rounded once to fp32.  idx: uint8 or uint16."""
     Tf = _c(Tf, np.float32)
-    idx = _c(idx, np.uint8)
+    assert np.asarray(idx).dtype in (np.uint8, np.uint16)
+    idx = _c(idx, np.uint16)  # widened, values unchanged
     C, K, M = Tf.shape
     N = idx.shape[0]
     assert idx.shape[1] == C
@@ -185,7 +189,7 @@ def lookup_f32(Tf, idx, bias=None):
     Y = np.empty((N, M), dtype=np.float32)
     b = None if bias is None else _c(bias, np.float32)
     _lib().lutnn_oracle_lookup_f32(_ptr(Tf, _f32p), None if b is None else _ptr(b, _f32p), C, K, M,
-                                   _ptr(idx, _u8p), N, _ptr(Y, _f32p), M)
+                                   _ptr(idx, _u16p), N, _ptr(Y, _f32p), M)
     return Y
 
 

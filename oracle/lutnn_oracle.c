@@ -153,10 +153,11 @@ ORACLE_API void lutnn_oracle_encode(const float* P, int C, int K, int V, const f
  * value equal to the threshold, and a NaN, go left.
  *   split_dim  [C][2^levels - 1] int32, every value in [0, V)
  *   threshold  [C][2^levels - 1] fp32
+ *   idx        [N][C] uint16: Sec. 7 evaluates trees of up to 12 levels, i.e. 4096 buckets (levels <= 16)
  */
 ORACLE_API void lutnn_oracle_encode_tree(const int32_t* split_dim, const float* threshold, int C,
                                          int levels, int V, const float* X, int64_t N,
-                                         int64_t ldx, uint8_t* idx) {
+                                         int64_t ldx, uint16_t* idx) {
     const int nodes = (1 << levels) - 1;
 #pragma omp parallel for schedule(static)
     for (int64_t n = 0; n < N; ++n) {
@@ -169,7 +170,7 @@ ORACLE_API void lutnn_oracle_encode_tree(const int32_t* split_dim, const float* 
                 const int right = x[c * V + dim[node]] > thr[node];
                 node = 2 * node + 1 + right;
             }
-            idx[(size_t)n * C + c] = (uint8_t)(node - nodes);
+            idx[(size_t)n * C + c] = (uint16_t)(node - nodes);
         }
     }
 }
@@ -197,11 +198,12 @@ ORACLE_API void lutnn_oracle_distances_f64(const float* P, int C, int K, int V,
 /*
  * Eq. 4 with an INT8 table: acc[n][m] = sum_c q[c][idx[n][c]][m] (exact int32);
  * Y[n][m] = fma((float)acc, s, bias[m]), or (float)acc * s when bias is NULL.
- * q is [C][K][M], Y is [N][M] with row stride ldy.
+ * q is [C][K][M], Y is [N][M] with row stride ldy; idx is [N][C] uint16 (K up to 65536: the hash
+ * encoder's 12-level trees have 4096 buckets, Sec. 7; Eq. 2's indices are widened by the caller).
  * acc_out (nullable) receives the raw int32 sums, [N][M] dense.
  */
 ORACLE_API void lutnn_oracle_lookup_i8(const int8_t* q, float scale, const float* bias, int C,
-                                       int K, int M, const uint8_t* idx, int64_t N, float* Y,
+                                       int K, int M, const uint16_t* idx, int64_t N, float* Y,
                                        int64_t ldy, int32_t* acc_out) {
 #pragma omp parallel
     {
@@ -227,7 +229,7 @@ ORACLE_API void lutnn_oracle_lookup_i8(const int8_t* q, float scale, const float
  * Eq. 4 with an fp32 table: Y[n][m] = (float)( sum_c (double)Tf[c][idx[n][c]][m] + bias[m] ).
  */
 ORACLE_API void lutnn_oracle_lookup_f32(const float* Tf, const float* bias, int C, int K, int M,
-                                        const uint8_t* idx, int64_t N, float* Y, int64_t ldy) {
+                                        const uint16_t* idx, int64_t N, float* Y, int64_t ldy) {
 #pragma omp parallel
     {
         double* acc = (double*)malloc((size_t)M * sizeof(double));

@@ -27,7 +27,8 @@ VARIANT_SMFMAC = 4
 VARIANTS = {"auto": VARIANT_AUTO, "lds": VARIANT_LDS, "mfma": VARIANT_MFMA, "fused": VARIANT_FUSED,
             "smfmac": VARIANT_SMFMAC}
 
-EXPORTS = ["lutnn_softpq_backward_static", "lutnn_set_tunable", "lutnn_table_bytes", "lutnn_packed_bytes", "lutnn_build_table", "lutnn_encode",
+EXPORTS = ["lutnn_softpq_backward_static", "lutnn_set_tunable", "lutnn_encode_tree16", "lutnn_lookup16",
+           "lutnn_linear_tree16", "lutnn_table_bytes", "lutnn_packed_bytes", "lutnn_build_table", "lutnn_encode",
            "lutnn_lookup", "lutnn_linear", "lutnn_encode_tree", "lutnn_linear_tree",
            "lutnn_softpq_backward", "lutnn_softpq_workspace_bytes",
            "lutnn_encode_tree_conv2d", "lutnn_conv2d_tree", "lutnn_conv2d_rows", "lutnn_encode_conv2d", "lutnn_conv2d",
@@ -93,6 +94,13 @@ def _load():
     lib.lutnn_linear_tree.restype = i32
     lib.lutnn_linear_tree.argtypes = [ctypes.POINTER(_CLayer), ctypes.POINTER(_CTree), vp, i64, i64, vp,
                                       i64, i32, vp, vp]
+    lib.lutnn_encode_tree16.restype = i32
+    lib.lutnn_encode_tree16.argtypes = [ctypes.POINTER(_CTree), vp, i64, i64, vp, vp]
+    lib.lutnn_lookup16.restype = i32
+    lib.lutnn_lookup16.argtypes = [ctypes.POINTER(_CLayer), vp, i64, vp, i64, vp]
+    lib.lutnn_linear_tree16.restype = i32
+    lib.lutnn_linear_tree16.argtypes = [ctypes.POINTER(_CLayer), ctypes.POINTER(_CTree), vp, i64, i64, vp, i64,
+                                        vp, vp]
     lib.lutnn_softpq_workspace_bytes.restype = ctypes.c_size_t
     lib.lutnn_softpq_workspace_bytes.argtypes = [i32, i32, i32, i64]
     lib.lutnn_softpq_backward.restype = i32
@@ -217,7 +225,7 @@ def build_table(centroids, W, table_dtype, bias=None, packed=True):
             table = torch.empty((C, K, M), dtype=torch.int8, device=dev)
         scale = torch.empty(1, dtype=torch.float32, device=dev)
         pk = None
-        if packed:
+        if packed and K <= 256:  # the matrix-core operand copy exists for 8-bit indices only
             nbytes = packed_bytes(C, K, M, table_dtype)
             pk = torch.empty(nbytes, dtype=torch.int8, device=dev)
     _check(LIB.lutnn_build_table(_ptr(centroids), _ptr(W), W.stride(0), C, K, V, M, table_dtype,
@@ -288,6 +296,44 @@ def linear_tree(layer, tree, X, variant="auto", out=None, idx_workspace=None):
         idx_workspace = torch.empty((N, layer.C), dtype=torch.uint8, device=X.device)
     _check(LIB.lutnn_linear_tree(ctypes.byref(layer.c), ctypes.byref(tree.c), _ptr(X), N, X.stride(0),
                                  _ptr(out), out.stride(0), v, _ptr(idx_workspace), _stream()))
+    return out
+
+
+def encode_tree16(tree, X, out=None):
+    """lutnn_encode_tree16: the hash encoder with 16-bit leaves (trees of up to 12 levels)."""
+    assert X.is_cuda and X.dtype == torch.float32 and X.stride(1) == 1
+    N = X.shape[0]
+    if out is None:
+        out = torch.empty((N, tree.C), dtype=torch.int16, device=X.device)
+    assert out.dtype == torch.int16 and out.is_contiguous() and out.shape == (N, tree.C)
+    _check(LIB.lutnn_encode_tree16(ctypes.byref(tree.c), _ptr(X), N, X.stride(0), _ptr(out), _stream()))
+    return out
+
+
+def lookup16(layer, idx, out=None):
+    """lutnn_lookup16: Eq. 4 on 16-bit indices (torch has no uint16 arithmetic: an int16 tensor
+    carries the bits)."""
+    assert idx.is_cuda and idx.dtype == torch.int16 and idx.is_contiguous()
+    N = idx.shape[0]
+    assert idx.shape == (N, layer.C)
+    if out is None:
+        out = torch.empty((N, layer.M), dtype=torch.float32, device=idx.device)
+    assert out.dtype == torch.float32 and out.stride(1) == 1 and out.shape == (N, layer.M)
+    _check(LIB.lutnn_lookup16(ctypes.byref(layer.c), _ptr(idx), N, _ptr(out), out.stride(0), _stream()))
+    return out
+
+
+def linear_tree16(layer, tree, X, out=None, idx_workspace=None):
+    """lutnn_linear_tree16: deep-tree hash encoding, then the 16-bit index lookup."""
+    assert X.is_cuda and X.dtype == torch.float32 and X.stride(1) == 1
+    N = X.shape[0]
+    if out is None:
+        out = torch.empty((N, layer.M), dtype=torch.float32, device=X.device)
+    if idx_workspace is None:
+        idx_workspace = torch.empty((N, layer.C), dtype=torch.int16, device=X.device)
+    assert out.dtype == torch.float32 and out.stride(1) == 1 and out.shape == (N, layer.M)
+    _check(LIB.lutnn_linear_tree16(ctypes.byref(layer.c), ctypes.byref(tree.c), _ptr(X), N, X.stride(0),
+                                   _ptr(out), out.stride(0), _ptr(idx_workspace), _stream()))
     return out
 
 

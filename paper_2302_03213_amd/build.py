@@ -18,7 +18,7 @@ INCLUDE = os.path.join(ROOT, "include")
 OBJDIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "liblutnn.so")
 
-SOURCES = ["api.hip", "encode.hip", "encode_tree.hip", "build_table.hip", "lookup_lds.hip", "lookup_rows.hip", "lookup_mfma.hip", "lookup_smfmac.hip",
+SOURCES = ["api.hip", "encode.hip", "encode_tree.hip", "build_table.hip", "lookup_lds.hip", "lookup_rows.hip", "lookup_mfma.hip", "lookup_smfmac.hip", "lookup_wide.hip",
            "linear_fused.hip", "linear_small.hip", "softpq_backward.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -32,7 +32,7 @@ lutnn_status hip_result(hipError_t e, const char* what) {
 
 // ---- tuning switches (lutnn_kernels.h)
 const char* const kTunableNames[lutnn::kTuneCount] = {"LUTNN_FUSED_KERNEL", "LUTNN_SMFMAC_SPLIT",
-                                                      "LUTNN_SMFMAC_TILE_ROWS", "LUTNN_SMFMAC_TILE_COLS"};
+                                                      "LUTNN_SMFMAC_TILE_ROWS"};
 std::atomic<int> g_tunable[lutnn::kTuneCount];
 std::once_flag g_tunable_once;
 
@@ -48,7 +48,6 @@ int parse_tunable(int which, const char* text) {
     const long v = std::strtol(text, &end, 10);
     if (*end != 0) return -1;
     if (which == lutnn::kTuneSmfmacSplit) return (v == 0 || v == 1) ? (int)v : -1;
-    if (which == lutnn::kTuneSmfmacTileCols) return (v == 32 || v == 64 || v == 128) ? (int)v : -1;
     return (v == 128 || v == 256 || v == 384 || v == 512) ? (int)v : -1;
 }
 
@@ -61,10 +60,15 @@ bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p
 
 // Dimensions shared by every entry point.  CK*M and N*C style products are formed in int64 by the
 // kernels; the individual dimensions must fit comfortably in int32.
-lutnn_status check_dims(int32_t C, int32_t K, int32_t V, int32_t M) {
+constexpr int kMaxK8 = 256;    // uint8 indices
+constexpr int kMaxK16 = 4096;  // uint16 indices: the 12-level trees of Sec. 7
+
+lutnn_status check_dims(int32_t C, int32_t K, int32_t V, int32_t M, int32_t kmax = kMaxK8) {
     if (C <= 0 || K <= 0 || V <= 0 || M <= 0)
         return fail(LUTNN_E_SHAPE, "C, K, V, M must be positive (got C=%d K=%d V=%d M=%d)", C, K, V, M);
-    if (K > 256) return fail(LUTNN_E_SHAPE, "K=%d exceeds 256 (indices are uint8)", K);
+    if (K > kmax)
+        return fail(LUTNN_E_SHAPE, "K=%d exceeds %d (%s)", K, kmax,
+                    kmax == kMaxK8 ? "indices are uint8; the ...16 entry points take up to 4096" : "indices are uint16");
     // M: a grid dimension of the table kernels counts blocks of 256 padded columns and stops at 65535
     if ((int64_t)C * V > (1 << 24) || M > (1 << 24) - 512 || C > (1 << 22))
         return fail(LUTNN_E_SHAPE, "dimension too large (C=%d V=%d M=%d)", C, V, M);
@@ -73,12 +77,12 @@ lutnn_status check_dims(int32_t C, int32_t K, int32_t V, int32_t M) {
 
 inline bool is_int_table(int dtype) { return dtype == LUTNN_TABLE_I8 || dtype == LUTNN_TABLE_I4; }
 
-lutnn_status check_layer(const lutnn_layer* L) {
+lutnn_status check_layer(const lutnn_layer* L, int32_t kmax = kMaxK8) {
     if (!L) return fail(LUTNN_E_NULL, "layer is NULL");
     if (L->reserved != 0) return fail(LUTNN_E_SHAPE, "layer->reserved must be 0");
     if (L->table_dtype != LUTNN_TABLE_F32 && !is_int_table(L->table_dtype))
         return fail(LUTNN_E_UNSUPPORTED, "unknown table dtype %d", L->table_dtype);
-    return check_dims(L->C, L->K, L->V, L->M);
+    return check_dims(L->C, L->K, L->V, L->M, kmax);
 }
 
 constexpr int64_t kMaxRows = (int64_t)1 << 31;
@@ -169,12 +173,14 @@ lutnn_status check_encode(const lutnn_layer* L, const float* X, int64_t N, int64
     return LUTNN_OK;
 }
 
-lutnn_status check_tree(const lutnn_tree* T, const float* X, int64_t N, int64_t ldx) {
+lutnn_status check_tree(const lutnn_tree* T, const float* X, int64_t N, int64_t ldx, int max_levels = 8) {
     if (!T) return fail(LUTNN_E_NULL, "tree is NULL");
     if (T->reserved != 0) return fail(LUTNN_E_SHAPE, "tree->reserved must be 0");
-    if (T->levels < 1 || T->levels > 8)
-        return fail(LUTNN_E_SHAPE, "tree->levels=%d outside 1..8 (indices are uint8)", T->levels);
-    if (lutnn_status st = check_dims(T->C, 1 << T->levels, T->V, 1)) return st;
+    if (T->levels < 1 || T->levels > max_levels)
+        return fail(LUTNN_E_SHAPE, "tree->levels=%d outside 1..%d (%s)", T->levels, max_levels,
+                    max_levels == 8 ? "indices are uint8; the ...16 entry points take up to 12 levels"
+                                    : "indices are uint16");
+    if (lutnn_status st = check_dims(T->C, 1 << T->levels, T->V, 1, kMaxK16)) return st;
     if (N == 0) return LUTNN_OK;
     if (!T->split_dim || !T->threshold) return fail(LUTNN_E_NULL, "tree->split_dim or tree->threshold is NULL");
     if (!X) return fail(LUTNN_E_NULL, "X is NULL");
@@ -284,7 +290,9 @@ lutnn_status lutnn_build_table(const float* centroids, const float* W, int64_t l
                                int32_t K, int32_t V, int32_t M, int32_t dtype, void* table_out,
                                void* packed_out, float* scale_out, void* stream) {
     if (!centroids || !W || !table_out) return fail(LUTNN_E_NULL, "centroids, W or table_out is NULL");
-    if (lutnn_status st = check_dims(C, K, V, M)) return st;
+    if (lutnn_status st = check_dims(C, K, V, M, kMaxK16)) return st;
+    if (K > kMaxK8 && packed_out)
+        return fail(LUTNN_E_UNSUPPORTED, "no packed copy for K=%d > 256 (pass packed_out = NULL)", K);
     if (ldw < M) return fail(LUTNN_E_SHAPE, "ldw=%lld is smaller than M=%d", (long long)ldw, M);
     if (!aligned(centroids, 4) || !aligned(W, 4))
         return fail(LUTNN_E_ALIGN, "centroids and W must be 4-byte aligned");
@@ -612,6 +620,77 @@ lutnn_status lutnn_linear_tree(const lutnn_layer* layer, const lutnn_tree* tree,
                                      "tree encode launch"))
         return st;
     return do_lookup(layer, v, idx_workspace, N, Y, ldy, s);
+}
+
+lutnn_status lutnn_encode_tree16(const lutnn_tree* tree, const float* X, int64_t N, int64_t ldx,
+                                 uint16_t* idx, void* stream) {
+    if (lutnn_status st = check_tree(tree, X, N, ldx, 12)) return st;
+    if (N == 0) return LUTNN_OK;
+    if (!idx) return fail(LUTNN_E_NULL, "idx is NULL");
+    if (!aligned(idx, 2)) return fail(LUTNN_E_ALIGN, "idx must be 2-byte aligned");
+    return hip_result(lutnn::launch_encode_tree16(tree->split_dim, tree->threshold, tree->C, tree->levels,
+                                                  tree->V, X, N, ldx, idx, static_cast<hipStream_t>(stream)),
+                      "tree encode launch (16-bit leaves)");
+}
+
+namespace {
+lutnn_status lookup16_checked(const lutnn_layer* L, const uint16_t* idx, int64_t N, float* Y, int64_t ldy,
+                              hipStream_t s) {
+    if (L->table_dtype == LUTNN_TABLE_I4)
+        return fail(LUTNN_E_UNSUPPORTED, "the 16-bit index lookup reads INT8 and fp32 tables");
+    if (!idx) return fail(LUTNN_E_NULL, "idx is NULL");
+    if (!Y) return fail(LUTNN_E_NULL, "Y is NULL");
+    if (!L->table) return fail(LUTNN_E_NULL, "layer->table is NULL");
+    if (N < 0 || N >= kMaxRows) return fail(LUTNN_E_SHAPE, "N=%lld out of range", (long long)N);
+    if (ldy < L->M) return fail(LUTNN_E_SHAPE, "ldy=%lld is smaller than M=%d", (long long)ldy, L->M);
+    if (!aligned(idx, 2) || !aligned(Y, 4) || (L->bias && !aligned(L->bias, 4)))
+        return fail(LUTNN_E_ALIGN, "idx must be 2-byte, Y and bias 4-byte aligned");
+    if (L->table_dtype == LUTNN_TABLE_I8) {
+        if (!L->scale) return fail(LUTNN_E_NULL, "an integer table needs layer->scale");
+        return hip_result(lutnn::launch_lookup_wide_i8(static_cast<const int8_t*>(L->table), L->scale, L->bias,
+                                                       L->C, L->K, L->M, idx, N, Y, ldy, s),
+                          "lookup launch (16-bit indices)");
+    }
+    if (!aligned(L->table, 4)) return fail(LUTNN_E_ALIGN, "fp32 table must be 4-byte aligned");
+    return hip_result(lutnn::launch_lookup_wide_f32(static_cast<const float*>(L->table), L->bias, L->C, L->K,
+                                                    L->M, idx, N, Y, ldy, s),
+                      "lookup launch (16-bit indices)");
+}
+}  // namespace
+
+lutnn_status lutnn_lookup16(const lutnn_layer* layer, const uint16_t* idx, int64_t N, float* Y, int64_t ldy,
+                            void* stream) {
+    if (lutnn_status st = check_layer(layer, kMaxK16)) return st;
+    if (N == 0) return LUTNN_OK;
+    return lookup16_checked(layer, idx, N, Y, ldy, static_cast<hipStream_t>(stream));
+}
+
+lutnn_status lutnn_linear_tree16(const lutnn_layer* layer, const lutnn_tree* tree, const float* X, int64_t N,
+                                 int64_t ldx, float* Y, int64_t ldy, uint16_t* idx_workspace, void* stream) {
+    if (lutnn_status st = check_layer(layer, kMaxK16)) return st;
+    if (lutnn_status st = check_tree(tree, X, N, ldx, 12)) return st;
+    if (tree->C != layer->C || tree->V != layer->V || (1 << tree->levels) != layer->K)
+        return fail(LUTNN_E_SHAPE, "tree (C=%d V=%d levels=%d) does not match layer (C=%d V=%d K=%d)", tree->C,
+                    tree->V, tree->levels, layer->C, layer->V, layer->K);
+    if (N == 0) return LUTNN_OK;
+    if (!idx_workspace) return fail(LUTNN_E_NULL, "idx_workspace is NULL");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // validate the lookup before anything is enqueued
+    if (layer->table_dtype == LUTNN_TABLE_I4)
+        return fail(LUTNN_E_UNSUPPORTED, "the 16-bit index lookup reads INT8 and fp32 tables");
+    if (!Y || !layer->table) return fail(LUTNN_E_NULL, "Y or layer->table is NULL");
+    if (ldy < layer->M) return fail(LUTNN_E_SHAPE, "ldy=%lld is smaller than M=%d", (long long)ldy, layer->M);
+    if (layer->table_dtype == LUTNN_TABLE_I8 && !layer->scale)
+        return fail(LUTNN_E_NULL, "an integer table needs layer->scale");
+    if (!aligned(idx_workspace, 2) || !aligned(Y, 4) || (layer->bias && !aligned(layer->bias, 4)) ||
+        !aligned(layer->table, layer->table_dtype == LUTNN_TABLE_F32 ? 4 : 1))
+        return fail(LUTNN_E_ALIGN, "idx_workspace must be 2-byte, Y, bias and an fp32 table 4-byte aligned");
+    if (lutnn_status st = hip_result(lutnn::launch_encode_tree16(tree->split_dim, tree->threshold, tree->C,
+                                                                 tree->levels, tree->V, X, N, ldx,
+                                                                 idx_workspace, s),
+                                     "tree encode launch (16-bit leaves)"))
+        return st;
+    return lookup16_checked(layer, idx_workspace, N, Y, ldy, s);
 }
 
 const char* lutnn_status_string(int32_t status) {

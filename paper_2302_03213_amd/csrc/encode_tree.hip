@@ -160,10 +160,70 @@ __global__ __launch_bounds__(kEncThreads) void encode_tree_conv_kernel(
     write_index_rows<CT>(is, idx, N, C, row0, c0, idx_dword_ok, tid);
 }
 
+// Deep trees (9 to 12 levels; Sec. 7 evaluates 12): 2^levels - 1 nodes per codebook no longer fit
+// LDS for a tile's codebooks, so the walks read their nodes from global memory - the upper levels
+// are shared by all 64 lanes of a wavefront and by every row tile, so they stay in the caches; the
+// lowest levels are one 8-byte pair of loads per lane.  The X tile is staged as above; leaves are
+// 16-bit and leave through LDS so that each row's CT indices go out as one segment.
+template <int V, int CT>
+__global__ __launch_bounds__(kEncThreads) void encode_tree_deep_kernel(
+    const float* __restrict__ X, int64_t ldx, const int32_t* __restrict__ split_dim,
+    const float* __restrict__ threshold, uint16_t* __restrict__ idx, int64_t N, int C, int levels,
+    int vec4) {
+    using E = EncTile<V, CT>;
+    __shared__ float xs[E::kLdsFloats];
+    __shared__ uint16_t is[kEncRows * CT];
+
+    const int nodes = (1 << levels) - 1;
+    const int col_tiles = (C + CT - 1) / CT;
+    const int64_t row0 = (int64_t)(blockIdx.x / col_tiles) * kEncRows;
+    const int c0 = (int)(blockIdx.x % col_tiles) * CT;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    stage_x<V, CT>(X, ldx, N, C * V, row0, c0, xs, vec4, tid);
+    __syncthreads();
+    const float* __restrict__ xrow = xs + lane * E::LS + w * E::CPW * V;
+    int node[E::CPW];
+    const int32_t* dim[E::CPW];
+    const float* thr[E::CPW];
+#pragma unroll
+    for (int j = 0; j < E::CPW; ++j) {
+        // codebooks past C walk the last codebook's tree; their leaves are never written
+        const int c = min(c0 + w * E::CPW + j, C - 1);
+        node[j] = 0;
+        dim[j] = split_dim + (size_t)c * nodes;
+        thr[j] = threshold + (size_t)c * nodes;
+    }
+    for (int l = 0; l < levels; ++l) {  // the codebooks advance together: independent walks
+        int d[E::CPW];
+        float t[E::CPW];
+#pragma unroll
+        for (int j = 0; j < E::CPW; ++j) {
+            d[j] = dim[j][node[j]];
+            t[j] = thr[j][node[j]];
+        }
+#pragma unroll
+        for (int j = 0; j < E::CPW; ++j) {
+            const int dd = d[j] < 0 ? 0 : d[j] >= V ? V - 1 : d[j];
+            node[j] = 2 * node[j] + 1 + (xrow[j * V + dd] > t[j] ? 1 : 0);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < E::CPW; ++j) is[lane * CT + w * E::CPW + j] = (uint16_t)(node[j] - nodes);
+    __syncthreads();
+    for (int i = tid; i < kEncRows * CT; i += kEncThreads) {
+        const int r = i / CT, c = c0 + i % CT;
+        if (row0 + r < N && c < C) idx[(row0 + r) * (int64_t)C + c] = is[i];
+    }
+}
+
 // Any V: one thread per sub-vector, everything from global memory.
+template <typename IdxT>
 __global__ __launch_bounds__(kEncThreads) void encode_tree_generic_kernel(
     const float* __restrict__ X, int64_t ldx, const int32_t* __restrict__ split_dim,
-    const float* __restrict__ threshold, uint8_t* __restrict__ idx, int64_t N, int C, int levels,
+    const float* __restrict__ threshold, IdxT* __restrict__ idx, int64_t N, int C, int levels,
     int V) {
     const int64_t i = (int64_t)blockIdx.x * kEncThreads + threadIdx.x;
     if (i >= N * (int64_t)C) return;
@@ -178,7 +238,22 @@ __global__ __launch_bounds__(kEncThreads) void encode_tree_generic_kernel(
         const int d = dim[node];
         node = 2 * node + 1 + (x[d < 0 ? 0 : d >= V ? V - 1 : d] > thr[node] ? 1 : 0);
     }
-    idx[i] = (uint8_t)(node - nodes);
+    idx[i] = (IdxT)(node - nodes);
+}
+
+template <int V>
+hipError_t launch_tree_deep(const int32_t* split_dim, const float* threshold, int C, int levels,
+                            const float* X, int64_t N, int64_t ldx, uint16_t* idx, hipStream_t s) {
+    // quarter-width tiles: four times the wavefronts to hide the walks' global-memory latency
+    constexpr int CTF = enc_tile_codebooks(V);
+    constexpr int CT = CTF / 4 >= 4 ? CTF / 4 : 4;
+    const int64_t blocks = ((N + kEncRows - 1) / kEncRows) * ((C + CT - 1) / CT);
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int vec4 = ((CT * V) % 4 == 0) && (((int64_t)C * V) % 4 == 0) && (ldx % 4 == 0) &&
+                     ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
+    hipLaunchKernelGGL((encode_tree_deep_kernel<V, CT>), dim3((unsigned)blocks), dim3(kEncThreads), 0, s, X, ldx,
+                       split_dim, threshold, idx, N, C, levels, vec4);
+    return hipGetLastError();
 }
 
 template <int V, int CT>
@@ -279,8 +354,31 @@ hipError_t launch_encode_tree(const int32_t* split_dim, const float* threshold, 
     const int64_t total = N * (int64_t)C;
     const int64_t blocks = (total + kEncThreads - 1) / kEncThreads;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(encode_tree_generic_kernel, dim3((unsigned)blocks), dim3(kEncThreads), 0, s, X, ldx,
+    hipLaunchKernelGGL(encode_tree_generic_kernel<uint8_t>, dim3((unsigned)blocks), dim3(kEncThreads), 0, s, X, ldx,
                        split_dim, threshold, idx, N, C, levels, V);
+    return hipGetLastError();
+}
+
+// 16-bit leaves: trees of up to 12 levels (any depth from 1; the 8-bit form is the faster one up to 8).
+hipError_t launch_encode_tree16(const int32_t* split_dim, const float* threshold, int C, int levels,
+                                int V, const float* X, int64_t N, int64_t ldx, uint16_t* idx,
+                                hipStream_t s) {
+    switch (V) {
+        case 1: return launch_tree_deep<1>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        case 2: return launch_tree_deep<2>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        case 3: return launch_tree_deep<3>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        case 4: return launch_tree_deep<4>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        case 8: return launch_tree_deep<8>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        case 9: return launch_tree_deep<9>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        case 16: return launch_tree_deep<16>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        case 32: return launch_tree_deep<32>(split_dim, threshold, C, levels, X, N, ldx, idx, s);
+        default: break;
+    }
+    const int64_t total = N * (int64_t)C;
+    const int64_t blocks = (total + kEncThreads - 1) / kEncThreads;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(encode_tree_generic_kernel<uint16_t>, dim3((unsigned)blocks), dim3(kEncThreads), 0, s, X,
+                       ldx, split_dim, threshold, idx, N, C, levels, V);
     return hipGetLastError();
 }
 

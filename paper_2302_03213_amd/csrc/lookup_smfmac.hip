@@ -60,9 +60,12 @@ namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 
+constexpr int BN = 128;               // columns per workgroup
 constexpr int NBUF = 4;               // LDS ring depth, stages
 constexpr int SC = 16;                // codebooks per stage
 constexpr int KSTEPS = 4;             // MFMA steps per stage, 4 codebooks each
+constexpr int STAGE_VECS = SC * BN;   // uint4 per stage buffer (32 KiB)
+constexpr int B_LOADS = 8;            // table loads per wave per stage
 
 // 64 lanes x 16 bytes global -> LDS at (lds_base + LDS_IMM) + 16 * lane; see dma16().
 template <int LDS_IMM>
@@ -76,31 +79,21 @@ __device__ __forceinline__ void dma16_at(uint32_t lds_base, const void* sbase, u
         : "memory", "m0", "scc");
 }
 
-// TM = 32-row blocks per wavefront, TN = 32-column tiles: the workgroup tile is 128*TM rows x 32*TN
-// columns.  (4, 4) is the efficient shape for large problems (one workgroup per compute unit, 256
-// accumulator registers); TM = 3, 2, 1 at TN = 4 exist so that problems with few rows still spread
-// over the chip.  TN = 1 and 2 are the shapes for mid-size problems: a table byte staged in LDS
-// serves 128*TM rows whatever TN is, so a tall narrow tile moves no more table bytes per matrix
-// instruction than the large one while there are 4 or 2 times as many tiles; their 64-128
-// accumulator registers and 8-16 KiB stages let two or three workgroups share a compute unit, so one
-// workgroup's pipeline fill and store epilogue overlap another's contraction.
+// TM = 32-row blocks per wavefront: the workgroup tile is 128*TM rows x 128 columns.  TM = 4 is
+// the efficient shape; 3, 2 and 1 exist so that problems with few rows still spread over the chip.
 // SPLITS > 1 (run-time `splits`, template flag SPLIT): `splits` workgroups share an output tile, each
 // contracts C / splits consecutive codebooks and adds its int32 partial sums into Y with atomics; Y
 // then holds integers (zeroed beforehand, turned into the final floats by a separate pass).  For
 // problems with fewer tiles than compute units: more workgroups stream the table in parallel.
-template <int TM, int TN, bool SPLIT = false, bool STREAM = false>
-__global__ __launch_bounds__(kMfmaThreads, (TM * TN >= 8 ? 1 : 2)) void lookup_smfmac_i8_kernel(
+template <int TM, bool SPLIT = false, bool STREAM = false>
+__global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const uint4* __restrict__ packed, const float* __restrict__ scale, const float* __restrict__ bias,
     int C, int M, int Mp, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y,
     int64_t ldy, int row_tiles, int64_t tiles, int splits) {
     constexpr int WAVE_ROWS = TM * 32;
     constexpr int BM = 4 * WAVE_ROWS;  // rows per workgroup
-    constexpr int BN = 32 * TN;        // columns per workgroup
-    constexpr int STAGE_VECS = SC * BN;  // uint4 per stage buffer (8 KiB per column tile)
-    constexpr int B_LOADS = 2 * TN;    // table loads per wave per stage (1 KiB each)
     constexpr int I_LOADS = TM;        // index loads per wave per super-stage
-    constexpr int S = TN * TM;         // SMFMAC slots per step
-    constexpr int NB = 2 * TN;         // LDS reads of B operands per step
+    constexpr int S = 4 * TM;          // SMFMAC slots per step
     // index-word half-operations: 8*TM per super-stage, TM per step; the sequence of a super-stage
     // starts at this position of the one before it (after its index bytes were read from LDS in
     // step 0 of the second stage, early enough that the words of d = 0 are finished two steps later)
@@ -174,16 +167,9 @@ __global__ __launch_bounds__(kMfmaThreads, (TM * TN >= 8 ? 1 : 2)) void lookup_s
     const uint32_t lane16_hi = lane * 16 + 1024;  // second 64-column half of a row
     const uint32_t ring_w = lds_offset(ring) + 4 * w * BN * 16;
     const uint32_t ibuf_w = lds_offset(ibuf) + w * TM * 64 * 16;
-    // TN = 1: a row of 32 columns is half a load, so one load takes two rows (lanes 32-63 the second)
-    const uint32_t lane16_two_rows = (lane & 31) * 16 + (lane >> 5) * rs1;
     auto load_b = [&](auto fb_c, auto q_c) {  // load q of the stage that goes to ring buffer FB
         constexpr int FB = decltype(fb_c)::value, Q = decltype(q_c)::value;
-        if constexpr (TN == 4)
-            dma16_at<(FB * STAGE_VECS + (Q >> 1) * BN + 64 * (Q & 1)) * 16>(ring_w, bp, (Q & 1) ? lane16_hi : lane16);
-        else if constexpr (TN == 2)  // load q = row q of the wave's four; bp stays at the first
-            dma16_at<(FB * STAGE_VECS + Q * BN) * 16>(ring_w, bp + (size_t)Q * rs1, lane16);
-        else                         // load q = rows 2q and 2q + 1
-            dma16_at<(FB * STAGE_VECS + 2 * Q * BN) * 16>(ring_w, bp + (size_t)(2 * Q) * rs1, lane16_two_rows);
+        dma16_at<(FB * STAGE_VECS + (Q >> 1) * BN + 64 * (Q & 1)) * 16>(ring_w, bp, (Q & 1) ? lane16_hi : lane16);
     };
     auto load_idx = [&](auto i_c) {
         constexpr int I = decltype(i_c)::value;
@@ -192,17 +178,14 @@ __global__ __launch_bounds__(kMfmaThreads, (TM * TN >= 8 ? 1 : 2)) void lookup_s
     // after the four rows of a stage: on to the rows of the next stage (+8 codebooks within a
     // super-stage, +24 to the next super-stage)
     auto next_stage_rows = [&](int sp_of_loaded_stage) {
-        if constexpr (TN == 4)  // bp has moved on by three rows while the stage was loaded
-            bp += (sp_of_loaded_stage == 0) ? 5 * (size_t)rs1 : 21 * (size_t)rs1;
-        else
-            bp += (sp_of_loaded_stage == 0) ? 8 * (size_t)rs1 : 24 * (size_t)rs1;
+        bp += (sp_of_loaded_stage == 0) ? 5 * (size_t)rs1 : 21 * (size_t)rs1;
     };
 
-    v16i acc[TM][TN];
+    v16i acc[TM][4];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
@@ -211,7 +194,7 @@ __global__ __launch_bounds__(kMfmaThreads, (TM * TN >= 8 ? 1 : 2)) void lookup_s
     typedef unsigned long long u64;
     typedef u64 u64x2 __attribute__((ext_vector_type(2)));
     u64x2 a[2][TM];
-    v8i b[2][TN];
+    v8i b[2][4];
     auto load_b_operand = [&](int set, int sbuf, int j, int r) {
         const int tn = r >> 1, half = r & 1;
         const uint4 v = ring[sbuf * STAGE_VECS + (8 * half + 2 * j + h) * BN + tn * 32 + l32];
@@ -290,20 +273,15 @@ __global__ __launch_bounds__(kMfmaThreads, (TM * TN >= 8 ? 1 : 2)) void lookup_s
     auto load_stage = [&](auto fb_c) {
         load_b(fb_c, I0{});
         load_b(fb_c, I1{});
-        if constexpr (TN == 4) {
-            bp += rs1;
-            load_b(fb_c, std::integral_constant<int, 2>{});
-            load_b(fb_c, std::integral_constant<int, 3>{});
-            bp += rs1;
-            load_b(fb_c, std::integral_constant<int, 4>{});
-            load_b(fb_c, std::integral_constant<int, 5>{});
-            bp += rs1;
-            load_b(fb_c, std::integral_constant<int, 6>{});
-            load_b(fb_c, std::integral_constant<int, 7>{});
-        } else if constexpr (TN == 2) {
-            load_b(fb_c, std::integral_constant<int, 2>{});
-            load_b(fb_c, std::integral_constant<int, 3>{});
-        }
+        bp += rs1;
+        load_b(fb_c, std::integral_constant<int, 2>{});
+        load_b(fb_c, std::integral_constant<int, 3>{});
+        bp += rs1;
+        load_b(fb_c, std::integral_constant<int, 4>{});
+        load_b(fb_c, std::integral_constant<int, 5>{});
+        bp += rs1;
+        load_b(fb_c, std::integral_constant<int, 6>{});
+        load_b(fb_c, std::integral_constant<int, 7>{});
     };
     load_stage(I0{});
     next_stage_rows(0);
@@ -325,7 +303,7 @@ __global__ __launch_bounds__(kMfmaThreads, (TM * TN >= 8 ? 1 : 2)) void lookup_s
     __syncthreads();  // every lane has its words before the buffer is refilled
     if (supers > 1) load_idx_all();
 #pragma unroll
-    for (int r = 0; r < NB; ++r) load_b_operand(0, 0, 0, r);
+    for (int r = 0; r < 8; ++r) load_b_operand(0, 0, 0, r);
 #pragma unroll
     for (int i = 0; i < TM; ++i) make_a_operand(0, 0, 0, wq[0], i);
 
@@ -359,7 +337,6 @@ __global__ __launch_bounds__(kMfmaThreads, (TM * TN >= 8 ? 1 : 2)) void lookup_s
                     acc[i][tn] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(
                         a4, b[j & 1][tn], acc[i][tn], (int)wcur.pos[i][tstep], 0, 0);
                 }
-                if constexpr (TN == 4) {
                 // B operands of the next step, eight LDS reads spread over the slots; after the
                 // last step: the first step of the next stage, in the first slots so that the
                 // reads have returned when the barrier waits for the LDS counter
@@ -440,63 +417,6 @@ __global__ __launch_bounds__(kMfmaThreads, (TM * TN >= 8 ? 1 : 2)) void lookup_s
                     }
                     if (q == S - 1) ip += 32;
                 }
-                } else {
-                // ---- narrow tiles (TN = 1, 2): the same units of housekeeping, TM of each per
-                // step, in S = TM * TN slots.  B operands of the next step (after the last step:
-                // the first step of the next stage): NB = 2 TN reads, in the first slots
-#pragma unroll
-                for (int r = 0; r < NB; ++r)
-                    if (r * (S < NB ? S : NB) / NB == q) {
-                        if (j + 1 < KSTEPS)
-                            load_b_operand((j + 1) & 1, SB, j + 1, r);
-                        else
-                            load_b_operand(0, (SB + 1) % NBUF, 0, r);
-                    }
-                // slot q serves row block q / TN: it picks up the block's index bytes of the next
-                // super-stage (first step of the second stage), does the block's index-word
-                // half-operation of this step and builds its A values of the next step
-                if (q % TN == 0) {
-                    const int i = q / TN;
-                    if (SP == 1 && j == 0) read_ibuf(wnext, i);
-                    const int n = (4 * SP + j) * TM + i;
-                    idx_halfop(n >= HSTART ? wnext : wcur, (n - HSTART + HSEQ) % HSEQ);
-                }
-                if (q % TN == TN - 1) {
-                    const int i = q / TN;
-                    if (j + 1 < KSTEPS)
-                        make_a_operand((j + 1) & 1, SP, j + 1, wcur, i);
-                    else if (SP == 0)
-                        make_a_operand(0, 1, 0, wcur, i);
-                    else
-                        make_a_operand(0, 0, 0, wnext, i);
-                }
-                // table loads of stage s + 3: TN = 2: one row per step; TN = 1: two rows in steps 0 and 2
-                if (do_fetch && q == 0) {
-                    if constexpr (TN == 2) {
-                        if (j == 0) load_b(std::integral_constant<int, FB>{}, I0{});
-                        if (j == 1) load_b(std::integral_constant<int, FB>{}, I1{});
-                        if (j == 2) load_b(std::integral_constant<int, FB>{}, I2{});
-                        if (j == 3) load_b(std::integral_constant<int, FB>{}, I3{});
-                    } else {
-                        if (j == 0) load_b(std::integral_constant<int, FB>{}, I0{});
-                        if (j == 2) load_b(std::integral_constant<int, FB>{}, I1{});
-                    }
-                }
-                if (do_fetch && q == S - 1 && j + 1 == KSTEPS) next_stage_rows(SP ^ 1);
-                // the index buffer is free once its reads (step 0) have returned; refill it in
-                // step 3 with the super-stage after next, one load per row block
-                if (do_idx && j == 3) {
-                    if (q % TN == TN - 1) {
-                        if (q / TN == 0) load_idx(I0{});
-                        if (q / TN == 1) load_idx(I1{});
-                        if constexpr (TM > 2) {
-                            if (q / TN == 2) load_idx(I2{});
-                            if (q / TN == 3) load_idx(I3{});
-                        }
-                    }
-                    if (q == S - 1) ip += 32;
-                }
-                }
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -539,15 +459,15 @@ __global__ __launch_bounds__(kMfmaThreads, (TM * TN >= 8 ? 1 : 2)) void lookup_s
             }
         }
         if constexpr (SPLIT)
-            mfma_atomic_add_tile<TM, TN>(acc, M, N, ct_m0 + w * WAVE_ROWS, ct_n0, reinterpret_cast<int32_t*>(Y), ldy);
+            mfma_atomic_add_tile<TM>(acc, M, N, ct_m0 + w * WAVE_ROWS, ct_n0, reinterpret_cast<int32_t*>(Y), ldy);
         else
-            mfma_store_tile<TM, STREAM, TN>(acc, sc, bias, M, N, ct_m0 + w * WAVE_ROWS, ct_n0, Y, ldy);
+            mfma_store_tile<TM, STREAM>(acc, sc, bias, M, N, ct_m0 + w * WAVE_ROWS, ct_n0, Y, ldy);
         if (!has_next) break;
         // next tile: its first stages and index words are already in LDS / registers
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
         t += wg_per_xcd;
@@ -577,7 +497,7 @@ __global__ __launch_bounds__(256) void dequant_rows_kernel(float* __restrict__ Y
 template <int TM>
 hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias, int C, int M,
                      const uint8_t* idx, int64_t N, float* Y, int64_t ldy, hipStream_t s) {
-    constexpr int BM = 128 * TM, BN = 128;
+    constexpr int BM = 128 * TM;
     const int Mp = (int)packed_cols(M);
     const int64_t col_tiles = (M + BN - 1) / BN;  // the packed table is padded to 256 columns
     const int64_t row_tiles = (N + BM - 1) / BM;
@@ -613,7 +533,7 @@ hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias
             const dim3 cells((unsigned)((M + 255) / 256), (unsigned)N);
             hipLaunchKernelGGL(zero_rows_kernel, cells, dim3(256), 0, s, Y, M, ldy);
             const int64_t units = tiles * splits;
-            hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, 4, true>), dim3((unsigned)((units + 7) / 8 * 8)),
+            hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, true>), dim3((unsigned)((units + 7) / 8 * 8)),
                                dim3(kMfmaThreads), 0, s, reinterpret_cast<const uint4*>(packed), scale, bias, C, M,
                                Mp, idx, N, Y, ldy, (int)row_tiles, units, splits);
             hipLaunchKernelGGL(dequant_rows_kernel, cells, dim3(256), 0, s, Y, M, ldy, scale, bias);
@@ -626,36 +546,13 @@ hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias
     // an output of 128 MiB or more cannot stay in any cache: stream it (512-row tiles only, the
     // height such problems take)
     if (TM == 4 && (double)N * M * 4 >= 134217728.0)
-        hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, 4, false, TM == 4>), dim3((unsigned)blocks),
+        hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, false, TM == 4>), dim3((unsigned)blocks),
                            dim3(kMfmaThreads), 0, s, reinterpret_cast<const uint4*>(packed), scale, bias, C, M, Mp,
                            idx, N, Y, ldy, (int)row_tiles, tiles, 1);
     else
-        hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, 4, false>), dim3((unsigned)blocks), dim3(kMfmaThreads), 0, s,
+        hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, false>), dim3((unsigned)blocks), dim3(kMfmaThreads), 0, s,
                            reinterpret_cast<const uint4*>(packed), scale, bias, C, M, Mp, idx, N, Y, ldy,
                            (int)row_tiles, tiles, 1);
-    return hipGetLastError();
-}
-
-// Narrow tiles (TN = 1, 2): 128*TM rows x 32*TN columns, no codebook split, two workgroups per
-// compute unit where the registers allow it.
-template <int TM, int TN>
-hipError_t launch_narrow(const int8_t* packed, const float* scale, const float* bias, int C, int M,
-                         const uint8_t* idx, int64_t N, float* Y, int64_t ldy, hipStream_t s) {
-    constexpr int BM = 128 * TM, BN = 32 * TN;
-    constexpr int kPerCu = TM * TN >= 8 ? 1 : (TM * TN <= 2 ? 3 : 2);  // by registers and LDS
-    const int Mp = (int)packed_cols(M);
-    const int64_t col_tiles = (M + BN - 1) / BN;
-    const int64_t row_tiles = (N + BM - 1) / BM;
-    const int64_t tiles = row_tiles * col_tiles;
-    int64_t blocks = (tiles + 7) / 8 * 8;
-    if (blocks > 0x7fffffffLL || row_tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-    if ((int64_t)Mp * 16 * 25 > 0xffffffffLL) return hipErrorInvalidValue;  // row strides are 32-bit
-    // stream several tiles per workgroup when the ring phase carries over from tile to tile
-    const int64_t resident = (int64_t)compute_units() * kPerCu;
-    if (C % 64 == 0 && blocks > resident) blocks = resident;
-    hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, TN, false, false>), dim3((unsigned)blocks), dim3(kMfmaThreads),
-                       0, s, reinterpret_cast<const uint4*>(packed), scale, bias, C, M, Mp, idx, N, Y, ldy,
-                       (int)row_tiles, tiles, 1);
     return hipGetLastError();
 }
 
@@ -673,18 +570,8 @@ hipError_t launch_lookup_smfmac_i8(const int8_t* packed, const float* scale, con
     // price each height as (rounds of 256 workgroups) x (measured time of one tile relative to
     // the 512-row tile: 0.8 for 384 rows, 0.56 for 256, 0.42 for 128 - the slab traffic does not
     // shrink).
-    const int64_t col_tiles = (M + 127) / 128;
+    const int64_t col_tiles = (M + BN - 1) / BN;
     const int kComputeUnits = compute_units();
-    // LUTNN_SMFMAC_TILE_COLS = 32 | 64 pins a narrow tile (with LUTNN_SMFMAC_TILE_ROWS = 256 | 512,
-    // default 512)
-    if (const int cols = tunable(kTuneSmfmacTileCols); cols == 32 || cols == 64) {
-        const bool tall = tunable(kTuneSmfmacTileRows) != 256;
-        if (cols == 32)
-            return tall ? launch_narrow<4, 1>(packed, scale, bias, C, M, idx, N, Y, ldy, s)
-                        : launch_narrow<2, 1>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
-        return tall ? launch_narrow<4, 2>(packed, scale, bias, C, M, idx, N, Y, ldy, s)
-                    : launch_narrow<2, 2>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
-    }
     auto cost = [&](int64_t bm, double rel) {
         const int64_t tiles = ((N + bm - 1) / bm) * col_tiles;
         return (double)((tiles + kComputeUnits - 1) / kComputeUnits) * rel;

@@ -20,7 +20,6 @@ enum Tunable {
     kTuneFusedKernel = 0,   // LUTNN_FUSED_KERNEL: 0 = "tile", 1 = "small"
     kTuneSmfmacSplit,       // LUTNN_SMFMAC_SPLIT: 0 | 1
     kTuneSmfmacTileRows,    // LUTNN_SMFMAC_TILE_ROWS: 128 | 256 | 384 | 512
-    kTuneSmfmacTileCols,    // LUTNN_SMFMAC_TILE_COLS: 32 | 64 | 128
     kTuneCount
 };
 int tunable(int which);
@@ -48,6 +47,16 @@ hipError_t launch_encode(const float* P, int C, int K, int V, const float* X, in
 hipError_t launch_encode_tree(const int32_t* split_dim, const float* threshold, int C, int levels,
                               int V, const float* X, int64_t N, int64_t ldx, uint8_t* idx,
                               hipStream_t s);
+
+// The same with 16-bit leaves, for trees of up to 12 levels (Sec. 7), and Eq. 4 on 16-bit indices
+// (K up to 4096 table rows per codebook, read straight from global memory).
+hipError_t launch_encode_tree16(const int32_t* split_dim, const float* threshold, int C, int levels,
+                                int V, const float* X, int64_t N, int64_t ldx, uint16_t* idx,
+                                hipStream_t s);
+hipError_t launch_lookup_wide_i8(const int8_t* T, const float* scale, const float* bias, int C, int K, int M,
+                                 const uint16_t* idx, int64_t N, float* Y, int64_t ldy, hipStream_t s);
+hipError_t launch_lookup_wide_f32(const float* T, const float* bias, int C, int K, int M, const uint16_t* idx,
+                                  int64_t N, float* Y, int64_t ldy, hipStream_t s);
 
 // Soft-PQ backward (Sec. 3.1-3.2, Eq. 5-6): gradients with respect to the centroids, the layer
 // input and the temperature, from Z = dL/dY . W^T.  workspace: softpq_workspace_bytes() bytes.

@@ -244,6 +244,59 @@ def test_tree_descriptor_validation(lut):
                                lut.VARIANT_AUTO, None, None) == 0
 
 
+def test_sixteen_bit_index_entry_points_validate_on_the_host(lut):
+    """lutnn_encode_tree16 / lutnn_lookup16 / lutnn_linear_tree16: levels up to 12, K up to 4096."""
+    from paper_2302_03213_amd.binding import _CTree
+    L, vp = lut.LIB, ctypes.c_void_p
+    X, Y, IDX = vp(0x10000), vp(0x20000), vp(0x30000)
+
+    def tree(**kw):
+        f = dict(C=4, V=4, levels=12, reserved=0, split_dim=0x5000, threshold=0x6000)
+        f.update(kw)
+        return _CTree(**f)
+
+    deep = _layer(lut, K=4096)
+    cases = [
+        (L.lutnn_encode_tree16(None, X, 8, 16, IDX, None), "LUTNN_E_NULL"),
+        (L.lutnn_encode_tree16(ctypes.byref(tree(levels=13)), X, 8, 16, IDX, None), "LUTNN_E_SHAPE"),
+        (L.lutnn_encode_tree16(ctypes.byref(tree(levels=0)), X, 8, 16, IDX, None), "LUTNN_E_SHAPE"),
+        (L.lutnn_encode_tree16(ctypes.byref(tree()), X, 8, 15, IDX, None), "LUTNN_E_SHAPE"),
+        (L.lutnn_encode_tree16(ctypes.byref(tree()), X, 8, 16, None, None), "LUTNN_E_NULL"),
+        (L.lutnn_encode_tree16(ctypes.byref(tree()), X, 8, 16, vp(0x30001), None), "LUTNN_E_ALIGN"),
+        (L.lutnn_lookup16(None, IDX, 8, Y, 8, None), "LUTNN_E_NULL"),
+        (L.lutnn_lookup16(ctypes.byref(_layer(lut, K=4097)), IDX, 8, Y, 8, None), "LUTNN_E_SHAPE"),
+        (L.lutnn_lookup16(ctypes.byref(_layer(lut, K=4096, table_dtype=lut.TABLE_I4)), IDX, 8, Y, 8, None),
+         "LUTNN_E_UNSUPPORTED"),
+        (L.lutnn_lookup16(ctypes.byref(deep), None, 8, Y, 8, None), "LUTNN_E_NULL"),
+        (L.lutnn_lookup16(ctypes.byref(deep), IDX, 8, None, 8, None), "LUTNN_E_NULL"),
+        (L.lutnn_lookup16(ctypes.byref(deep), IDX, 8, Y, 7, None), "LUTNN_E_SHAPE"),
+        (L.lutnn_lookup16(ctypes.byref(_layer(lut, K=4096, scale=None)), IDX, 8, Y, 8, None), "LUTNN_E_NULL"),
+        (L.lutnn_lookup16(ctypes.byref(_layer(lut, K=4096, table=None)), IDX, 8, Y, 8, None), "LUTNN_E_NULL"),
+        (L.lutnn_lookup16(ctypes.byref(deep), vp(0x30001), 8, Y, 8, None), "LUTNN_E_ALIGN"),
+        (L.lutnn_linear_tree16(ctypes.byref(deep), ctypes.byref(tree(levels=11)), X, 8, 16, Y, 8, IDX, None),
+         "LUTNN_E_SHAPE"),  # K != 2^levels
+        (L.lutnn_linear_tree16(ctypes.byref(deep), ctypes.byref(tree()), X, 8, 16, Y, 8, None, None),
+         "LUTNN_E_NULL"),
+        (L.lutnn_linear_tree16(ctypes.byref(deep), ctypes.byref(tree()), X, 8, 16, Y, 7, IDX, None),
+         "LUTNN_E_SHAPE"),
+        # the 8-bit entry points still stop at 8 levels / 256 centroids, and say where to go
+        (L.lutnn_encode_tree(ctypes.byref(tree()), X, 8, 16, IDX, None), "LUTNN_E_SHAPE"),
+        (L.lutnn_lookup(ctypes.byref(deep), IDX, 8, Y, 8, lut.VARIANT_AUTO, None), "LUTNN_E_SHAPE"),
+    ]
+    for i, (code, want) in enumerate(cases):
+        name, detail = _status(lut, code)
+        assert name == want, "case %d: got %s (%s), wanted %s" % (i, name, detail, want)
+    assert "16" in _status(lut, L.lutnn_lookup(ctypes.byref(deep), IDX, 8, Y, 8, lut.VARIANT_AUTO, None))[1]
+    assert L.lutnn_encode_tree16(ctypes.byref(tree()), None, 0, 16, None, None) == 0  # empty batch
+    assert L.lutnn_lookup16(ctypes.byref(deep), None, 0, None, 8, None) == 0
+    # tables of up to 4096 rows per codebook are built without the packed copy
+    P, W, T, PK, S = (vp(0x10000 * i) for i in range(1, 6))
+    name, _ = _status(lut, L.lutnn_build_table(P, W, 8, 4, 4096, 4, 8, lut.TABLE_I8, T, PK, S, None))
+    assert name == "LUTNN_E_UNSUPPORTED"
+    name, _ = _status(lut, L.lutnn_build_table(P, W, 8, 4, 4097, 4, 8, lut.TABLE_I8, T, None, S, None))
+    assert name == "LUTNN_E_SHAPE"
+
+
 def test_softpq_backward_validation_and_workspace_query(lut):
     L, vp = lut.LIB, ctypes.c_void_p
     X, Z, DP, DX, DT, WS = (vp(0x10000 * i) for i in range(1, 7))

@@ -187,34 +187,6 @@ def test_lookup_smfmac_every_tile_height(lut, pin, rows, N, C, K, M):
     np.testing.assert_array_equal(host(lut.lookup(layer, dev(idx), "smfmac")), ol.lookup(idx))
 
 
-@pytest.mark.parametrize("rows,cols", [(512, 32), (256, 32), (512, 64), (256, 64)])
-@pytest.mark.parametrize("N,C,K,M", [(1500, 96, 16, 300), (700, 32, 7, 40), (2100, 64, 16, 3968),
-                                     (4700, 128, 16, 4096), (5000, 384, 16, 768), (16384, 64, 16, 1024)])
-def test_lookup_smfmac_narrow_tiles(lut, pin, rows, cols, N, C, K, M):
-    """Tall narrow tiles (32 or 64 columns): ragged rows / columns, a single super-stage (C = 32),
-    codebook counts that stream tiles through a workgroup (C % 64 == 0 with more tiles than resident
-    workgroups: the last three shapes) and one that does not (C = 96), with and without bias into a
-    strided Y whose guard band must stay untouched."""
-    pin("LUTNN_SMFMAC_TILE_COLS", cols)
-    pin("LUTNN_SMFMAC_TILE_ROWS", rows)
-    w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=N + rows + cols)
-    ol = OracleLayer(w)
-    ol.q = wl.random_table_i8(C, K, M, seed=C + M + cols)
-    ol.s = np.float32(0.0137)
-    idx = wl.random_indices(N, C, K, seed=N + rows)
-    ref = {True: ol.lookup(idx), False: ol.lookup(idx, bias=None)}
-    for with_bias in (True, False):
-        layer = device_layer_from_oracle(lut, ol, with_bias)
-        Ybig = torch.full((N + 2, M + 8), 3.5, dtype=torch.float32, device="cuda")
-        lut.lookup(layer, dev(idx), "smfmac", out=Ybig[1:N + 1, 3:M + 3])
-        got = host(Ybig)
-        assert np.array_equal(got[1:N + 1, 3:M + 3], ref[with_bias]), \
-            "%d elements differ" % (got[1:N + 1, 3:M + 3] != ref[with_bias]).sum()
-        guard = np.ones_like(got, bool)
-        guard[1:N + 1, 3:M + 3] = False
-        assert (got[guard] == 3.5).all(), "wrote outside its output"
-
-
 @pytest.mark.parametrize("N,C,K,M,rows", [(33, 1024, 16, 4096, 0), (100, 512, 16, 300, 0),
                                           (128, 544, 16, 1000, 0), (64, 576, 7, 130, 0),
                                           (1, 2048, 16, 256, 0), (77, 1536, 16, 768, 0),

@@ -24,7 +24,7 @@ def _inorder(levels):
     return out
 
 
-@pytest.mark.parametrize("levels", [1, 2, 4, 6, 8])
+@pytest.mark.parametrize("levels", [1, 2, 4, 6, 8, 9, 12])
 def test_one_split_index_is_sorted_threshold_bucketing(levels):
     # Every node tests the same value; thresholds sorted along the in-order walk make the tree a
     # binary search, so the bucket is the number of thresholds strictly below the value.
@@ -42,9 +42,12 @@ def test_one_split_index_is_sorted_threshold_bucketing(levels):
     # plant exact ties: a value equal to a threshold stays left of it
     X[:50, 0] = sorted_thr[0, rng.integers(0, nodes, 50)]
     got = oracle.encode_tree(dims, thr, X, V)
+    assert got.dtype == (np.uint8 if levels <= 8 else np.uint16)
     for c in range(C):
         want = np.searchsorted(sorted_thr[c], X[:, c * V + c % V], side="left")
         np.testing.assert_array_equal(got[:, c], want)
+    if levels > 8:  # 700 points over 512 or 4096 buckets: indices beyond one byte do occur
+        assert got.max() > 255
 
 
 def test_level_l_splits_on_value_l_at_zero_gives_the_sign_bits():
@@ -67,12 +70,31 @@ def test_level_l_splits_on_value_l_at_zero_gives_the_sign_bits():
     assert (got[:20] == 0).all()
 
 
-@pytest.mark.parametrize("levels,V", [(3, 4), (4, 9), (5, 2)])
+def test_twelve_levels_give_the_sign_bits_of_twelve_values():
+    # The paper's deepest setting (Sec. 7: 12 levels): level l looks at value l with threshold 0, so
+    # the 12-bit bucket is the sign pattern of the sub-vector's first twelve values.
+    C, V, levels, N = 2, 16, 12, 3000
+    rng = np.random.default_rng(12)
+    X = rng.standard_normal((N, C * V)).astype(np.float32)
+    nodes = (1 << levels) - 1
+    level_of = np.floor(np.log2(np.arange(nodes) + 1)).astype(np.int32)
+    dims = np.tile(level_of, (C, 1)).astype(np.int32)
+    got = oracle.encode_tree(dims, np.zeros((C, nodes), np.float32), X, V)
+    Xs = X.reshape(N, C, V)
+    want = np.zeros((N, C), np.int64)
+    for l in range(levels):
+        want |= (Xs[:, :, l] > 0).astype(np.int64) << (levels - 1 - l)
+    assert got.dtype == np.uint16
+    np.testing.assert_array_equal(got, want)
+    assert len(np.unique(got)) > 1500  # the buckets beyond 255 are really in use
+
+
+@pytest.mark.parametrize("levels,V", [(3, 4), (4, 9), (5, 2), (9, 3), (12, 32)])
 def test_each_point_lies_in_the_region_of_exactly_the_leaf_reported(levels, V):
     # Set definition instead of a walk: leaf b owns the points that satisfy every inequality on the
     # path from the root to b.  The regions partition the space, and the oracle's answer must be
     # the one region containing the point.
-    C, N = 4, 300
+    C, N = (4, 300) if levels <= 8 else (2, 120)
     dims, thr = wl.random_tree(C, V, levels, seed=11)
     rng = np.random.default_rng(3)
     X = rng.standard_normal((N, C * V)).astype(np.float32)
