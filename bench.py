@@ -36,7 +36,7 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 WORKLOADS = ["fc_large", "fc_small", "conv_resnet18", "bert_ffn_up", "bert_layer", "paper_kv",
-             "conv_resnet18_b32"]
+             "conv_resnet18_b32", "tree12"]
 
 
 def workload_by_name(name):
@@ -49,12 +49,14 @@ def workload_by_name(name):
         return wl.bert_layer(0)
     if name == "paper_kv":
         return wl.paper_kv_space(0)
+    if name == "tree12":  # runs with --encoder tree: 12-level trees, 16-bit indices
+        return [wl.bert_ffn_down_tree12(0)]
     return [table[name](0)]
 
 
 def kernel_roofline(cost, workload, w, kind, ms):
     """Roofline record of one kernel launch of layer `w` that took `ms`.
-    kind: smfmac | mfma | lds | fused | encode | encode_tree."""
+    kind: smfmac | mfma | lds | wide | fused | encode | encode_tree."""
     sec = ms * 1e-3
     table_bytes = 1 if w.table_dtype == "i8" else 4
     look_bytes = cost.lookup_hbm_bytes(w.N, w.C, w.K, w.M, table_bytes)
@@ -84,6 +86,20 @@ def kernel_roofline(cost, workload, w, kind, ms):
                      "lds_bound_ratio = (N*C*M table bytes through LDS at 78.6 TB/s) / kernel time, above 1 "
                      "because the matrix cores replace the gather"}
         return r
+    if kind == "wide":  # 16-bit indices: every selected table row is read from global memory
+        # distinct table rows N*C uniformly drawn (row, codebook) pairs select, in expectation
+        distinct = w.C * w.K * (1.0 - (1.0 - 1.0 / w.K) ** w.N)
+        byts = distinct * w.M * table_bytes + 2 * w.N * w.C + 4 * w.N * w.M
+        gathered = cost.lookup_entries(w.N, w.C, w.M) * table_bytes
+        achieved = byts / sec / 1e9
+        return {"kernel": "lookup_wide (16-bit indices)", "bound": "hbm", "achieved": round(achieved, 1),
+                "peak": cost.PEAK_HBM_BYTES_PER_S / 1e9, "unit": "GB/s",
+                "frac": round(achieved * 1e9 / cost.PEAK_HBM_BYTES_PER_S, 4), "traffic": None,
+                "kernel_ms": round(ms, 4), "algorithmic_bytes": int(byts),
+                "gathered_GBps": round(gathered / sec / 1e9, 1),
+                "note": "algorithmic bytes = the distinct table rows the batch selects (expected number under "
+                        "uniform indices) once + indices + Y; gathered_GBps counts every one of the N*C row "
+                        "reads of M entries, repeats served by the caches"}
     if kind == "lds":
         entries = cost.lookup_entries(w.N, w.C, w.M)
         achieved = entries / sec / 1e12
@@ -138,11 +154,14 @@ class Bench:
                 dt = lut.TABLE_I4
             P, W = torch.from_numpy(w.P).cuda(), torch.from_numpy(w.W).cuda()
             bias = torch.from_numpy(w.bias).cuda() if w.bias is not None else None
-            layer = lut.build_table(P, W, dt, bias=bias)
+            layer = lut.build_table(P, W, dt, bias=bias, packed=w.K <= 256)
             X0 = torch.from_numpy(w.conv["inp"] if w.conv else w.X).cuda()
             Xs = [X0, X0.flip(0).contiguous()]  # two rotating activation / output buffer sets
             Ys = [torch.empty((w.N, w.M), dtype=torch.float32, device="cuda") for _ in range(2)]
-            ws = torch.empty((w.N, w.C), dtype=torch.uint8, device="cuda")
+            # more than 256 buckets per codebook (trees deeper than 8 levels): the 16-bit index calls
+            wide = w.K > 256
+            assert not wide or encoder == "tree", "K > 256 comes from the hash encoder: use --encoder tree"
+            ws = torch.empty((w.N, w.C), dtype=torch.int16 if wide else torch.uint8, device="cuda")
             if encoder == "tree":
                 levels = w.K.bit_length() - 1
                 assert not w.conv and w.K == 1 << levels, "--encoder tree needs K = 2^levels and matrix input"
@@ -156,7 +175,9 @@ class Bench:
     # ---- the calls
     def run_layer(self, w, layer, X, variant, Y, ws):
         lut = self.lut
-        if self.encoder == "tree":
+        if w.K > 256:
+            lut.linear_tree16(layer, self.trees[w.name][0], X, out=Y, idx_workspace=ws)
+        elif self.encoder == "tree":
             lut.linear_tree(layer, self.trees[w.name][0], X, variant, out=Y, idx_workspace=ws)
         elif w.conv:  # the image batch, no im2col matrix
             lut.conv2d(layer, X, w.conv["kernel"], w.conv["stride"], w.conv["pad"], variant, out=Y,
@@ -166,7 +187,9 @@ class Bench:
 
     def run_encode(self, w, layer, X, ws):
         lut = self.lut
-        if self.encoder == "tree":
+        if w.K > 256:
+            lut.encode_tree16(self.trees[w.name][0], X, out=ws)
+        elif self.encoder == "tree":
             lut.encode_tree(self.trees[w.name][0], X, out=ws)
         elif w.conv:
             lut.encode_conv2d(layer, X, w.conv["kernel"], w.conv["stride"], w.conv["pad"], out=ws)
@@ -235,7 +258,9 @@ class Bench:
         """Per layer: (lookup variant, True if lutnn_linear does both steps in one launch)."""
         lut, out = self.lut, {}
         for (w, layer, Xs, Ys, ws) in self.layers:
-            if self.variant == "fused":
+            if w.K > 256:
+                out[w.name] = ("wide", False)
+            elif self.variant == "fused":
                 out[w.name] = ("fused", True)
             elif self.variant == "auto":  # what the library's AUTO rule picks at this shape
                 if not w.conv and lut.linear_auto_variant(layer, w.N, ws) == "fused":
@@ -266,7 +291,10 @@ class Bench:
                     ev[0].record()
                     self.run_encode(w, layer, Xs[i & 1], ws)
                     ev[1].record()
-                    lut.lookup(layer, ws, v, out=Ys[i & 1])
+                    if v == "wide":
+                        lut.lookup16(layer, ws, out=Ys[i & 1])
+                    else:
+                        lut.lookup(layer, ws, v, out=Ys[i & 1])
                     ev[2].record()
                     ev[2].synchronize()
                     e_all.append(ev[0].elapsed_time(ev[1]))
@@ -568,7 +596,9 @@ def main():
                    "launch": ("replays of a HIP graph of %d steps" % args.graph) if args.graph > 0 else
                              "one host call per layer and step"},
         "roofline": roofline, "kernels": kernels,
-        "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(b, args),
+        # (tables of 4096 rows per codebook take the plain-loop oracle minutes to build: no CPU leg there)
+        "cpu_baseline": None if (args.no_cpu_baseline or any(w.K > 256 for (w, *_r) in b.layers))
+        else cpu_baseline(b, args),
     }
 
     # ---- riding along with the headline (default workload only; outside its timed region, a few

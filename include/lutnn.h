@@ -162,11 +162,15 @@ LUTNN_API lutnn_status lutnn_lookup(const lutnn_layer* layer, const uint8_t* idx
 /*
  * The whole operator: encode then lookup, Y ~= X . B (+ bias).
  *
- *   variant FUSED  one kernel; the indices stay in LDS.  `idx_workspace` is ignored.  Two forms: a
- *                  one-launch kernel for small problems (fp32 / INT8 table in its plain layout,
- *                  M % 4 == 0), taken where it is the faster one or the only one that can run,
- *                  and a tile kernel on the matrix cores (INT8: needs table_packed).  The
- *                  environment variable LUTNN_FUSED_KERNEL (small or tile) pins the form.
+ *   variant FUSED  one kernel; the indices stay in LDS.  `idx_workspace` is ignored.  Two forms.
+ *                  The one-launch kernel for small problems (fp32 / INT8 table in its plain layout,
+ *                  M % 4 == 0) is the form that pays: at on-device batch sizes it beats the two
+ *                  launches, and AUTO takes it there.  The tile kernel on the matrix cores (INT8:
+ *                  needs table_packed) is strictly the fallback for callers that have no index
+ *                  workspace on shapes the one-launch kernel does not take: it re-encodes a row
+ *                  block per column split and re-streams the table per row block, and is several
+ *                  times slower than encode + lookup on every shape measured - give a workspace
+ *                  whenever you can.  lutnn_set_tunable("LUTNN_FUSED_KERNEL", ...) pins the form.
  *   variant LDS / MFMA / SMFMAC  lutnn_encode into idx_workspace, then lutnn_lookup with that
  *                  variant.
  *   variant AUTO   the one-launch kernel where the problem is so small that a second launch would

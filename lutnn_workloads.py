@@ -147,6 +147,13 @@ def paper_kv_space(seed=0):
     ]
 
 
+def bert_ffn_down_tree12(seed=0):
+    """BERT-base FFN-down rows (D = 3072) at V = 32 with the hash encoder's deepest setting of Sec. 7:
+    12-level trees, K = 4096 buckets per codebook (C = 96, M = 768; a 288 MiB INT8 table).  The
+    bucket prototypes are seeded random vectors, the trees come from random_tree."""
+    return make_layer("bert_ffn_down_v32_tree12_i8", 4096, 96, 4096, 32, 768, "i8", seed=seed + 200)
+
+
 def fc_large(seed=0):
     """Large LUT-FC stress: N=16384, D=4096, M=4096, V=4 (C=1024), K=16, INT8 table (64 MiB)."""
     return make_layer("fc_large_i8", 16384, 1024, 16, 4, 4096, "i8", seed=seed)
