@@ -39,9 +39,11 @@ def both_forms(lut, N, C, K, V, M, t, seed, oracle_too=False):
     dP = torch.full((C, K, V), float("nan"), dtype=torch.float32, device="cuda")
     dX = torch.full((N, C * V), float("nan"), dtype=torch.float32, device="cuda")
     dt = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
-    before = torch.cuda.memory_allocated()
+    # torch's count of allocations it has ever made (monotonic: frees by the garbage collector do
+    # not touch it) must not move across the call
+    before = torch.cuda.memory_stats().get("allocation.all.allocated", 0)
     got = lut.softpq_backward_static(layer, t, Xd, Zd, dP=dP, dX=dX, dt=dt)
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_stats().get("allocation.all.allocated", 0) == before
     for a, b, name in zip(got, ref, ("dP", "dX", "dt")):
         np.testing.assert_array_equal(host(a), host(b), err_msg=name)
     if oracle_too:
