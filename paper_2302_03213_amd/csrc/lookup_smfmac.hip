@@ -89,7 +89,7 @@ template <int TM, bool SPLIT = false, bool STREAM = false>
 __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const uint4* __restrict__ packed, const float* __restrict__ scale, const float* __restrict__ bias,
     int C, int M, int Mp, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y,
-    int64_t ldy, int row_tiles, int64_t tiles, int splits) {
+    int64_t ldy, int row_tiles, int64_t tiles, int splits, int row_group) {
     constexpr int WAVE_ROWS = TM * 32;
     constexpr int BM = 4 * WAVE_ROWS;  // rows per workgroup
     constexpr int I_LOADS = TM;        // index loads per wave per super-stage
@@ -109,9 +109,9 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const int l32 = lane & 31, h = lane >> 5;
 
     // XCD-aware tile schedule: consecutive workgroup ids land on different XCDs (8 of them, each
-    // with its own L2).  XCD x owns the contiguous tile range [x*per_xcd, (x+1)*per_xcd), tiles are
-    // ordered column-block major, and the workgroups of the XCD take its tiles round robin, so at
-    // any time they walk the same slab of the table.
+    // with its own L2).  XCD x owns the contiguous tile range [x*per_xcd, (x+1)*per_xcd) of the tile
+    // order (column-block major, or grouped by row tiles: see aim_loads_at), and the workgroups of
+    // the XCD take its tiles round robin, so at any time they share table slabs and index rows.
     const int64_t per_xcd = (tiles + 7) / 8;
     const int wg_per_xcd = gridDim.x >> 3;
     const int64_t xcd_end = min(((int64_t)(blockIdx.x & 7) + 1) * per_xcd, tiles);
@@ -141,8 +141,20 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const int row0 = 16 * (w >> 1) + 4 * (w & 1);
     auto aim_loads_at = [&](int64_t tt) {
         const int64_t tile = SPLIT ? tt / splits : tt;
-        ft_n0 = (int)(tile / row_tiles) * BN;
-        ft_m0 = (tile % row_tiles) * BM;
+        if (row_group > 0) {
+            // Row tiles in groups of `row_group`, column-block major within a group: the workgroups
+            // of an XCD that run at the same time then share `row_group` row tiles' index bytes AND
+            // a few column blocks' table slabs, instead of one slab and every row tile's indices.
+            const int64_t col_tiles = (SPLIT ? tiles / splits : tiles) / row_tiles;
+            const int64_t per_group = (int64_t)row_group * col_tiles;
+            const int64_t g = tile / per_group, rem = tile - g * per_group;
+            const int64_t rows_here = min((int64_t)row_group, (int64_t)row_tiles - g * row_group);
+            ft_n0 = (int)(rem / rows_here) * BN;
+            ft_m0 = (g * row_group + rem % rows_here) * BM;
+        } else {
+            ft_n0 = (int)(tile / row_tiles) * BN;
+            ft_m0 = (tile % row_tiles) * BM;
+        }
         bp = reinterpret_cast<const char*>(packed + ft_n0) + (size_t)(row0 + c_begin) * rs1;
         ip = idx + ft_m0 * C + c_begin;
 #pragma unroll
@@ -535,11 +547,20 @@ hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias
             const int64_t units = tiles * splits;
             hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, true>), dim3((unsigned)((units + 7) / 8 * 8)),
                                dim3(kMfmaThreads), 0, s, reinterpret_cast<const uint4*>(packed), scale, bias, C, M,
-                               Mp, idx, N, Y, ldy, (int)row_tiles, units, splits);
+                               Mp, idx, N, Y, ldy, (int)row_tiles, units, splits, 0);
             hipLaunchKernelGGL(dequant_rows_kernel, cells, dim3(256), 0, s, Y, M, ldy, scale, bias);
             return hipGetLastError();
         }
     }
+    // Tile order.  The 32 workgroups of an XCD that run at the same time read R row tiles' index
+    // bytes (128*TM*C each) and Q column blocks' table slabs (2048*C each), R*Q = 32: plain
+    // column-block-major order is R = 32, Q = 1 (config 5: 18 MiB per round and XCD, the whole index
+    // matrix once per column block); groups of 16 row tiles give R = 16, Q = 2 (12 MiB).  Measured on
+    // config 5 (rocprofv3 FETCH_SIZE): 605 -> 404 MB fetched per launch, time unchanged (the re-reads
+    // come from the Infinity Cache either way).  Only worth it when a launch has several rounds of
+    // tiles; LUTNN_SMFMAC_ROW_GROUP pins the group size (0 = plain).
+    int row_group = tiles >= 4 * (int64_t)kComputeUnits && row_tiles >= 16 ? 16 : 0;
+    if (const int pinned = tunable(kTuneSmfmacRowGroup); pinned >= 0) row_group = pinned;
     // Stream several tiles per workgroup when the ring phase carries over from tile to tile:
     // one workgroup per compute unit (the kernel's LDS footprint allows only one anyway).
     if (C % 64 == 0 && blocks > kComputeUnits) blocks = kComputeUnits;
@@ -548,11 +569,11 @@ hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias
     if (TM == 4 && (double)N * M * 4 >= 134217728.0)
         hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, false, TM == 4>), dim3((unsigned)blocks),
                            dim3(kMfmaThreads), 0, s, reinterpret_cast<const uint4*>(packed), scale, bias, C, M, Mp,
-                           idx, N, Y, ldy, (int)row_tiles, tiles, 1);
+                           idx, N, Y, ldy, (int)row_tiles, tiles, 1, row_group);
     else
         hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, false>), dim3((unsigned)blocks), dim3(kMfmaThreads), 0, s,
                            reinterpret_cast<const uint4*>(packed), scale, bias, C, M, Mp, idx, N, Y, ldy,
-                           (int)row_tiles, tiles, 1);
+                           (int)row_tiles, tiles, 1, row_group);
     return hipGetLastError();
 }
 

@@ -20,6 +20,7 @@ enum Tunable {
     kTuneFusedKernel = 0,   // LUTNN_FUSED_KERNEL: 0 = "tile", 1 = "small"
     kTuneSmfmacSplit,       // LUTNN_SMFMAC_SPLIT: 0 | 1
     kTuneSmfmacTileRows,    // LUTNN_SMFMAC_TILE_ROWS: 128 | 256 | 384 | 512
+    kTuneSmfmacRowGroup,    // LUTNN_SMFMAC_ROW_GROUP: row tiles per group of the tile order, 0..64 (0 = plain)
     kTuneCount
 };
 int tunable(int which);

@@ -187,6 +187,27 @@ def test_lookup_smfmac_every_tile_height(lut, pin, rows, N, C, K, M):
     np.testing.assert_array_equal(host(lut.lookup(layer, dev(idx), "smfmac")), ol.lookup(idx))
 
 
+@pytest.mark.parametrize("group", [0, 1, 3, 8, 64])
+@pytest.mark.parametrize("N,C,K,M,rows", [(4700, 64, 16, 4096, 512), (2100, 96, 16, 3968, 128),
+                                          (9000, 128, 16, 1100, 256), (1500, 32, 7, 300, 384)])
+def test_lookup_smfmac_tile_orders(lut, pin, group, N, C, K, M, rows):
+    """The grouped tile order (row tiles in groups, column-block major within a group) against the
+    plain one: every tile is visited exactly once whatever the group size, with ragged last groups,
+    with tiles streamed through a workgroup (C % 64 == 0 and more tiles than compute units) and
+    without."""
+    pin("LUTNN_SMFMAC_ROW_GROUP", group)
+    pin("LUTNN_SMFMAC_TILE_ROWS", rows)
+    w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=N + group)
+    ol = OracleLayer(w)
+    ol.q = wl.random_table_i8(C, K, M, seed=C + M)
+    ol.s = np.float32(0.031)
+    idx = wl.random_indices(N, C, K, seed=N + 3)
+    layer = device_layer_from_oracle(lut, ol)
+    got = host(lut.lookup(layer, dev(idx), "smfmac"))
+    ref = ol.lookup(idx)
+    assert np.array_equal(got, ref), "%d elements differ" % (got != ref).sum()
+
+
 @pytest.mark.parametrize("N,C,K,M,rows", [(33, 1024, 16, 4096, 0), (100, 512, 16, 300, 0),
                                           (128, 544, 16, 1000, 0), (64, 576, 7, 130, 0),
                                           (1, 2048, 16, 256, 0), (77, 1536, 16, 768, 0),
