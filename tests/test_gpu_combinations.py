@@ -174,6 +174,51 @@ def test_softpq_backward_and_tree_encode_replayed_from_a_hip_graph(lut):
         np.testing.assert_array_equal(host(idx), oracle.encode_tree(dims, thr, Xn, V))
 
 
+def test_static_scratch_backward_and_deep_tree_linear_replayed_from_a_hip_graph(lut):
+    """The callers lutnn_softpq_backward_static exists for: captured once (after a first eager call,
+    which looks the scratch array's address up), replayed with fresh inputs; and the 16-bit index
+    operator (12-level trees) in the same graph."""
+    N, C, K, V, M, levels = 1500, 32, 16, 4, 40, 12
+    w = wl.make_layer("t", N, C, K, V, 8, "f32", seed=29)
+    layer = lut.LutLayer(dev(w.P), None, lut.TABLE_F32, 8)
+    X = dev(w.X).clone()
+    Z = dev(np.random.default_rng(3).standard_normal((N, C * V)).astype(np.float32))
+    dP = torch.empty((C, K, V), dtype=torch.float32, device="cuda")
+    dX = torch.empty((N, C * V), dtype=torch.float32, device="cuda")
+    dt = torch.empty(1, dtype=torch.float32, device="cuda")
+    wt = wl.make_layer("t", 1, C, 1 << levels, V, M, "i8", seed=30)
+    dims, thr = wl.random_tree(C, V, levels, seed=30)
+    tree = lut.LutTree(dev(dims), dev(thr), V)
+    deep = lut.build_table(dev(wt.P), dev(wt.W), lut.TABLE_I8, bias=dev(wt.bias))
+    Y = torch.empty((N, M), dtype=torch.float32, device="cuda")
+    ws16 = torch.empty((N, C), dtype=torch.int16, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):  # warm-up outside capture
+        lut.softpq_backward_static(layer, 1.0, X, Z, dP=dP, dX=dX, dt=dt)
+        lut.linear_tree16(deep, tree, X, out=Y, idx_workspace=ws16)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lut.softpq_backward_static(layer, 1.0, X, Z, dP=dP, dX=dX, dt=dt)
+        lut.linear_tree16(deep, tree, X, out=Y, idx_workspace=ws16)
+    rng = np.random.default_rng(8)
+    q, s = oracle.quantize_i8(oracle.build_table_f32(wt.P, wt.W))
+    for rep in range(3):
+        Xn = rng.standard_normal((N, C * V)).astype(np.float32)
+        X.copy_(dev(Xn))
+        graph.replay()
+        torch.cuda.synchronize()
+        e = lut.softpq_backward(layer, 1.0, dev(Xn), Z)
+        for a, b in zip((dP, dX, dt), e):
+            np.testing.assert_array_equal(host(a), host(b), err_msg="replay %d" % rep)
+        idx_ref = oracle.encode_tree(dims, thr, Xn, V)
+        np.testing.assert_array_equal(host(ws16).view(np.uint16), idx_ref)
+        np.testing.assert_array_equal(host(Y), oracle.lookup_i8(q, s, idx_ref, wt.bias), err_msg="replay %d" % rep)
+        float((dev(Xn) * 2).sum())  # unrelated eager work and a synchronisation between replays
+
+
 def test_four_million_rows_cross_the_32_bit_byte_offsets(lut):
     """N = 2^22 + 77: X, Y and dX are larger than 2 GiB each, so every row offset the kernels form
     must be 64-bit.  The oracle checks the first and the last rows and a sample in between."""
