@@ -237,8 +237,12 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     // first half = position word of codebooks 4d, 4d+1; second half = that of 4d+2, 4d+3, and the
     // shift word.  Words are finished in the order d = 0, 1, 2, 3, the order the steps use them.
     uint32_t pair = 0;  // carried from the first half of a word to the second
-    auto plut_at = [&](uint32_t byte_off) {
-        return *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(plut) + byte_off);
+    // LDS address of the table in a vector register (kept opaque): (x & mask) | base is then one
+    // v_and_or_b32 instead of an AND and an OR with a constant that is no inline constant
+    uint32_t plut_base = lds_offset(plut);
+    asm volatile("" : "+v"(plut_base));
+    auto plut_at_addr = [&](uint32_t lds_addr) {
+        return *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>(lds_addr);
     };
     auto idx_halfop = [&](IdxWords& wq, int k) {
         const int d = (k >> 1) / TM, i = (k >> 1) % TM;
@@ -246,9 +250,9 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
             const uint32_t raw = wq.sh[i][d];
             // bits 2-9 = 4 (p0 | p1 << 4), bits 18-25 = 4 (p2 | p3 << 4): byte offsets into plut
             pair = (raw << 2) | (raw >> 2);
-            wq.pos[i][2 * d + 0] = plut_at(pair & 0x3fcu);
+            wq.pos[i][2 * d + 0] = plut_at_addr((pair & 0x3fcu) | plut_base);
         } else {
-            wq.pos[i][2 * d + 1] = plut_at((pair >> 16) & 0x3fcu);
+            wq.pos[i][2 * d + 1] = plut_at_addr(((pair >> 16) & 0x3fcu) | plut_base);
             wq.sh[i][d] = (wq.sh[i][d] << 2) & 0x30303030u;
         }
     };
