@@ -411,6 +411,7 @@ LUTNN_API const char* lutnn_last_error(void);
  *   "LUTNN_SMFMAC_SPLIT"      "0" | "1"                 codebooks of a tile shared out over workgroups
  *   "LUTNN_SMFMAC_TILE_ROWS"  "128" | "256" | "384" | "512"   tile height of the sparse matrix-core lookup
  *   "LUTNN_SMFMAC_ROW_GROUP"  "0" .. "64"               row tiles per group of its tile order (0 = plain)
+ *   "LUTNN_SMFMAC_TILE_COLS"  "96" | "128"              width of its 512-row tiles
  * value NULL or "" returns the switch to "not pinned".  A pinned choice the shape cannot take is
  * ignored.  Process-wide and atomic: safe to call while other threads launch, which then see
  * either the old or the new value.

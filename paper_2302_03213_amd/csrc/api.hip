@@ -32,7 +32,8 @@ lutnn_status hip_result(hipError_t e, const char* what) {
 
 // ---- tuning switches (lutnn_kernels.h)
 const char* const kTunableNames[lutnn::kTuneCount] = {"LUTNN_FUSED_KERNEL", "LUTNN_SMFMAC_SPLIT",
-                                                      "LUTNN_SMFMAC_TILE_ROWS", "LUTNN_SMFMAC_ROW_GROUP"};
+                                                      "LUTNN_SMFMAC_TILE_ROWS", "LUTNN_SMFMAC_ROW_GROUP",
+                                                      "LUTNN_SMFMAC_TILE_COLS"};
 std::atomic<int> g_tunable[lutnn::kTuneCount];
 std::once_flag g_tunable_once;
 
@@ -49,6 +50,7 @@ int parse_tunable(int which, const char* text) {
     if (*end != 0) return -1;
     if (which == lutnn::kTuneSmfmacSplit) return (v == 0 || v == 1) ? (int)v : -1;
     if (which == lutnn::kTuneSmfmacRowGroup) return (v >= 0 && v <= 64) ? (int)v : -1;
+    if (which == lutnn::kTuneSmfmacTileCols) return (v == 96 || v == 128) ? (int)v : -1;
     return (v == 128 || v == 256 || v == 384 || v == 512) ? (int)v : -1;
 }
 

@@ -60,40 +60,46 @@ namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 
-constexpr int BN = 128;               // columns per workgroup
 constexpr int NBUF = 4;               // LDS ring depth, stages
 constexpr int SC = 16;                // codebooks per stage
 constexpr int KSTEPS = 4;             // MFMA steps per stage, 4 codebooks each
-constexpr int STAGE_VECS = SC * BN;   // uint4 per stage buffer (32 KiB)
-constexpr int B_LOADS = 8;            // table loads per wave per stage
 
-// 64 lanes x 16 bytes global -> LDS at (lds_base + LDS_IMM) + 16 * lane; see dma16().
-template <int LDS_IMM>
+// 64 lanes x 16 bytes global -> LDS at (lds_base + LDS_IMM) + 16 * lane; see dma16().  GOFF: a constant
+// added to every lane's global address through the instruction's offset field, which the hardware
+// adds to the LDS address as well: M0 is set lower by as much.
+template <int LDS_IMM, int GOFF = 0>
 __device__ __forceinline__ void dma16_at(uint32_t lds_base, const void* sbase, uint32_t voff) {
     asm volatile(
         "s_add_u32 m0, %0, %3\n\t"
         "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %1, %2"
+        "global_load_lds_dwordx4 %1, %2 offset:%4"
         :
-        : "s"(lds_base), "v"(voff), "s"(sbase), "n"(LDS_IMM)
+        : "s"(lds_base), "v"(voff), "s"(sbase), "n"(LDS_IMM - GOFF), "n"(GOFF)
         : "memory", "m0", "scc");
 }
 
-// TM = 32-row blocks per wavefront: the workgroup tile is 128*TM rows x 128 columns.  TM = 4 is
-// the efficient shape; 3, 2 and 1 exist so that problems with few rows still spread over the chip.
+// TM = 32-row blocks per wavefront, TN = 32-column tiles per wavefront (4, or 3): the workgroup tile
+// is 128*TM rows x 32*TN columns.  (4, 4) is the efficient shape; TM = 3, 2 and 1 exist so that
+// problems with few rows still spread over the chip, and TN = 3 (96 columns) for widths where it
+// yields a whole number of rounds of tiles and 128 columns do not (M = 3072 at 4096 rows: 256 tiles
+// of 512 x 96 against 192 of 512 x 128 on 256 compute units).
 // SPLITS > 1 (run-time `splits`, template flag SPLIT): `splits` workgroups share an output tile, each
 // contracts C / splits consecutive codebooks and adds its int32 partial sums into Y with atomics; Y
 // then holds integers (zeroed beforehand, turned into the final floats by a separate pass).  For
 // problems with fewer tiles than compute units: more workgroups stream the table in parallel.
-template <int TM, bool SPLIT = false, bool STREAM = false>
+template <int TM, int TN, bool SPLIT = false, bool STREAM = false>
 __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const uint4* __restrict__ packed, const float* __restrict__ scale, const float* __restrict__ bias,
     int C, int M, int Mp, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y,
     int64_t ldy, int row_tiles, int64_t tiles, int splits, int row_group) {
     constexpr int WAVE_ROWS = TM * 32;
     constexpr int BM = 4 * WAVE_ROWS;  // rows per workgroup
-    constexpr int I_LOADS = TM;        // index loads per wave per super-stage
-    constexpr int S = 4 * TM;          // SMFMAC slots per step
+    static_assert(TN == 4 || (TN == 3 && TM == 4), "column tiles per wavefront");
+    constexpr int BN = 32 * TN;          // columns per workgroup
+    constexpr int STAGE_VECS = SC * BN;  // uint4 per stage buffer (32 KiB at TN = 4)
+    constexpr int B_LOADS = 2 * TN;      // table loads per wave per stage (1 KiB each)
+    constexpr int I_LOADS = TM;          // index loads per wave per super-stage
+    constexpr int S = TN * TM;           // SMFMAC slots per step
     // index-word half-operations: 8*TM per super-stage, TM per step; the sequence of a super-stage
     // starts at this position of the one before it (after its index bytes were read from LDS in
     // step 0 of the second stage, early enough that the words of d = 0 are finished two steps later)
@@ -179,9 +185,25 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     const uint32_t lane16_hi = lane * 16 + 1024;  // second 64-column half of a row
     const uint32_t ring_w = lds_offset(ring) + 4 * w * BN * 16;
     const uint32_t ibuf_w = lds_offset(ibuf) + w * TM * 64 * 16;
+    // TN = 3: a row of 96 columns is 1.5 loads.  The wave's four rows of a stage are 6 KiB = six
+    // loads, contiguous in LDS; load q covers rows 2(q/3) and 2(q/3)+1: the first KiB of the first
+    // row, then its last half KiB together with the first half KiB of the second (lanes 32-63), then
+    // the second row's last KiB.  bp stays at the wave's first row for the whole stage.
+    const uint32_t lane16_mid = lane < 32 ? 1024u + lane * 16u : rs1 + (lane - 32) * 16u;
     auto load_b = [&](auto fb_c, auto q_c) {  // load q of the stage that goes to ring buffer FB
         constexpr int FB = decltype(fb_c)::value, Q = decltype(q_c)::value;
-        dma16_at<(FB * STAGE_VECS + (Q >> 1) * BN + 64 * (Q & 1)) * 16>(ring_w, bp, (Q & 1) ? lane16_hi : lane16);
+        if constexpr (TN == 4) {
+            dma16_at<(FB * STAGE_VECS + (Q >> 1) * BN + 64 * (Q & 1)) * 16>(ring_w, bp, (Q & 1) ? lane16_hi : lane16);
+        } else {
+            constexpr int LDS = FB * STAGE_VECS * 16 + Q * 1024;
+            const char* rows = bp + (size_t)(2 * (Q / 3)) * rs1;
+            if constexpr (Q % 3 == 0)
+                dma16_at<LDS>(ring_w, rows, lane16);
+            else if constexpr (Q % 3 == 1)
+                dma16_at<LDS>(ring_w, rows, lane16_mid);
+            else
+                dma16_at<LDS, 512>(ring_w, rows + rs1, lane16);
+        }
     };
     auto load_idx = [&](auto i_c) {
         constexpr int I = decltype(i_c)::value;
@@ -190,14 +212,17 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     // after the four rows of a stage: on to the rows of the next stage (+8 codebooks within a
     // super-stage, +24 to the next super-stage)
     auto next_stage_rows = [&](int sp_of_loaded_stage) {
-        bp += (sp_of_loaded_stage == 0) ? 5 * (size_t)rs1 : 21 * (size_t)rs1;
+        if constexpr (TN == 4)  // bp has moved on by three rows while the stage was loaded
+            bp += (sp_of_loaded_stage == 0) ? 5 * (size_t)rs1 : 21 * (size_t)rs1;
+        else
+            bp += (sp_of_loaded_stage == 0) ? 8 * (size_t)rs1 : 24 * (size_t)rs1;
     };
 
-    v16i acc[TM][4];
+    v16i acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
@@ -206,7 +231,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     typedef unsigned long long u64;
     typedef u64 u64x2 __attribute__((ext_vector_type(2)));
     u64x2 a[2][TM];
-    v8i b[2][4];
+    v8i b[2][TN];
     auto load_b_operand = [&](int set, int sbuf, int j, int r) {
         const int tn = r >> 1, half = r & 1;
         const uint4 v = ring[sbuf * STAGE_VECS + (8 * half + 2 * j + h) * BN + tn * 32 + l32];
@@ -289,15 +314,17 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     auto load_stage = [&](auto fb_c) {
         load_b(fb_c, I0{});
         load_b(fb_c, I1{});
-        bp += rs1;
+        if constexpr (TN == 4) bp += rs1;
         load_b(fb_c, std::integral_constant<int, 2>{});
         load_b(fb_c, std::integral_constant<int, 3>{});
-        bp += rs1;
+        if constexpr (TN == 4) bp += rs1;
         load_b(fb_c, std::integral_constant<int, 4>{});
         load_b(fb_c, std::integral_constant<int, 5>{});
-        bp += rs1;
-        load_b(fb_c, std::integral_constant<int, 6>{});
-        load_b(fb_c, std::integral_constant<int, 7>{});
+        if constexpr (TN == 4) {
+            bp += rs1;
+            load_b(fb_c, std::integral_constant<int, 6>{});
+            load_b(fb_c, std::integral_constant<int, 7>{});
+        }
     };
     load_stage(I0{});
     next_stage_rows(0);
@@ -319,7 +346,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
     __syncthreads();  // every lane has its words before the buffer is refilled
     if (supers > 1) load_idx_all();
 #pragma unroll
-    for (int r = 0; r < 8; ++r) load_b_operand(0, 0, 0, r);
+    for (int r = 0; r < 2 * TN; ++r) load_b_operand(0, 0, 0, r);
 #pragma unroll
     for (int i = 0; i < TM; ++i) make_a_operand(0, 0, 0, wq[0], i);
 
@@ -357,7 +384,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
                 // last step: the first step of the next stage, in the first slots so that the
                 // reads have returned when the barrier waits for the LDS counter
                 if (j + 1 < KSTEPS) {
-                    if constexpr (S == 16) {
+                    if constexpr (S == 16 || TN == 3) {
                         if ((q & 1) == 0) load_b_operand((j + 1) & 1, SB, j + 1, q >> 1);
                     } else if constexpr (S == 12) {
                         if (q % 3 != 2) load_b_operand((j + 1) & 1, SB, j + 1, q - q / 3);
@@ -369,7 +396,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
                     }
                 } else {
                     if constexpr (S >= 8) {
-                        if (q < 8) load_b_operand(0, (SB + 1) % NBUF, 0, q);
+                        if (q < 2 * TN) load_b_operand(0, (SB + 1) % NBUF, 0, q);
                     } else {
                         load_b_operand(0, (SB + 1) % NBUF, 0, 2 * q);
                         load_b_operand(0, (SB + 1) % NBUF, 0, 2 * q + 1);
@@ -379,14 +406,14 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
                 // (their loads were issued a super-stage ago and awaited at the end of the
                 // previous stage; past the last super-stage this reads stale, unused data)
                 if (SP == 1 && j == 0 && (q & 1) == 0 && q / 2 < TM) read_ibuf(wnext, q / 2);
-                // index-word half-operations, one every fourth slot
-                if ((q & 3) == 1) {
-                    const int n = (4 * SP + j) * TM + (q >> 2);
+                // index-word half-operations, one every TN-th slot
+                if (q % TN == 1) {
+                    const int n = (4 * SP + j) * TM + q / TN;
                     idx_halfop(n >= HSTART ? wnext : wcur, (n - HSTART + HSEQ) % HSEQ);
                 }
                 // A values of the next step, one row block at a time
-                if ((q & 3) == 3) {
-                    const int i = q >> 2;
+                if (q % TN == TN - 1) {
+                    const int i = q / TN;
                     if (j + 1 < KSTEPS)
                         make_a_operand((j + 1) & 1, SP, j + 1, wcur, i);
                     else if (SP == 0)
@@ -394,8 +421,22 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
                     else
                         make_a_operand(0, 0, 0, wnext, i);
                 }
-                // table loads of stage s + 3: rows one per step, two halves
-                if (do_fetch) {
+                // table loads of stage s + 3: rows one per step, two halves (TN = 3: six loads,
+                // two in steps 0 and 2, one in steps 1 and 3)
+                if (do_fetch && TN == 3) {
+                    if (q == 2) {
+                        if (j == 0) load_b(std::integral_constant<int, FB>{}, I0{});
+                        if (j == 1) load_b(std::integral_constant<int, FB>{}, I2{});
+                        if (j == 2) load_b(std::integral_constant<int, FB>{}, I3{});
+                        if (j == 3) load_b(std::integral_constant<int, FB>{}, std::integral_constant<int, 5>{});
+                    }
+                    if (q == 8) {
+                        if (j == 0) load_b(std::integral_constant<int, FB>{}, I1{});
+                        if (j == 2) load_b(std::integral_constant<int, FB>{}, std::integral_constant<int, 4>{});
+                    }
+                    if (q == S - 1 && j + 1 == KSTEPS) next_stage_rows(SP ^ 1);
+                }
+                if (do_fetch && TN == 4) {
                     if (q == (S >= 8 ? 2 : 0)) {
                         if (j == 0) load_b(std::integral_constant<int, FB>{}, I0{});
                         if (j == 1) load_b(std::integral_constant<int, FB>{}, I2{});
@@ -428,8 +469,8 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
                         if (q == 8) load_idx(I2{});
                     }
                     if constexpr (TM == 4) {
-                        if (q == 12) load_idx(I2{});
-                        if (q == 14) load_idx(I3{});
+                        if (q == (TN == 4 ? 12 : 8)) load_idx(I2{});
+                        if (q == (TN == 4 ? 14 : 10)) load_idx(I3{});
                     }
                     if (q == S - 1) ip += 32;
                 }
@@ -475,15 +516,15 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
             }
         }
         if constexpr (SPLIT)
-            mfma_atomic_add_tile<TM>(acc, M, N, ct_m0 + w * WAVE_ROWS, ct_n0, reinterpret_cast<int32_t*>(Y), ldy);
+            mfma_atomic_add_tile<TM, TN>(acc, M, N, ct_m0 + w * WAVE_ROWS, ct_n0, reinterpret_cast<int32_t*>(Y), ldy);
         else
-            mfma_store_tile<TM, STREAM>(acc, sc, bias, M, N, ct_m0 + w * WAVE_ROWS, ct_n0, Y, ldy);
+            mfma_store_tile<TM, STREAM, TN>(acc, sc, bias, M, N, ct_m0 + w * WAVE_ROWS, ct_n0, Y, ldy);
         if (!has_next) break;
         // next tile: its first stages and index words are already in LDS / registers
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
         t += wg_per_xcd;
@@ -510,12 +551,13 @@ __global__ __launch_bounds__(256) void dequant_rows_kernel(float* __restrict__ Y
     *y = bias ? __fmaf_rn(a, *scale, bias[m]) : __fmul_rn(a, *scale);
 }
 
-template <int TM>
+template <int TM, int TN = 4>
 hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias, int C, int M,
                      const uint8_t* idx, int64_t N, float* Y, int64_t ldy, hipStream_t s) {
-    constexpr int BM = 128 * TM;
+    constexpr int BM = 128 * TM, BN = 32 * TN;
     const int Mp = (int)packed_cols(M);
     const int64_t col_tiles = (M + BN - 1) / BN;  // the packed table is padded to 256 columns
+    if (col_tiles * BN > Mp) return hipErrorInvalidValue;  // 96-column tiles past the padding
     const int64_t row_tiles = (N + BM - 1) / BM;
     const int64_t tiles = row_tiles * col_tiles;
     int64_t blocks = (tiles + 7) / 8 * 8;
@@ -532,7 +574,7 @@ hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias
     // the second).  Each share keeps at least 64 codebooks.  LUTNN_SMFMAC_SPLIT = 0 | 1 pins the
     // decision (sweeps, and tests that must reach both paths).
     const int kComputeUnits = compute_units();
-    if (tiles <= kComputeUnits / 2 && C >= 512) {
+    if (TN == 4 && tiles <= kComputeUnits / 2 && C >= 512) {
         const int supers = C / 32;
         int splits = 1;
         for (int cand = (int)std::min<int64_t>(16, kComputeUnits / tiles); cand > 1; --cand)
@@ -549,7 +591,7 @@ hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias
             const dim3 cells((unsigned)((M + 255) / 256), (unsigned)N);
             hipLaunchKernelGGL(zero_rows_kernel, cells, dim3(256), 0, s, Y, M, ldy);
             const int64_t units = tiles * splits;
-            hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, true>), dim3((unsigned)((units + 7) / 8 * 8)),
+            hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, 4, true>), dim3((unsigned)((units + 7) / 8 * 8)),
                                dim3(kMfmaThreads), 0, s, reinterpret_cast<const uint4*>(packed), scale, bias, C, M,
                                Mp, idx, N, Y, ldy, (int)row_tiles, units, splits, 0);
             hipLaunchKernelGGL(dequant_rows_kernel, cells, dim3(256), 0, s, Y, M, ldy, scale, bias);
@@ -570,12 +612,12 @@ hipError_t launch_tm(const int8_t* packed, const float* scale, const float* bias
     if (C % 64 == 0 && blocks > kComputeUnits) blocks = kComputeUnits;
     // an output of 128 MiB or more cannot stay in any cache: stream it (512-row tiles only, the
     // height such problems take)
-    if (TM == 4 && (double)N * M * 4 >= 134217728.0)
-        hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, false, TM == 4>), dim3((unsigned)blocks),
+    if (TM == 4 && TN == 4 && (double)N * M * 4 >= 134217728.0)
+        hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, 4, false, TM == 4>), dim3((unsigned)blocks),
                            dim3(kMfmaThreads), 0, s, reinterpret_cast<const uint4*>(packed), scale, bias, C, M, Mp,
                            idx, N, Y, ldy, (int)row_tiles, tiles, 1, row_group);
     else
-        hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, false>), dim3((unsigned)blocks), dim3(kMfmaThreads), 0, s,
+        hipLaunchKernelGGL((lookup_smfmac_i8_kernel<TM, TN, false>), dim3((unsigned)blocks), dim3(kMfmaThreads), 0, s,
                            reinterpret_cast<const uint4*>(packed), scale, bias, C, M, Mp, idx, N, Y, ldy,
                            (int)row_tiles, tiles, 1, row_group);
     return hipGetLastError();
@@ -595,16 +637,26 @@ hipError_t launch_lookup_smfmac_i8(const int8_t* packed, const float* scale, con
     // price each height as (rounds of 256 workgroups) x (measured time of one tile relative to
     // the 512-row tile: 0.8 for 384 rows, 0.56 for 256, 0.42 for 128 - the slab traffic does not
     // shrink).
-    const int64_t col_tiles = (M + BN - 1) / BN;
     const int kComputeUnits = compute_units();
-    auto cost = [&](int64_t bm, double rel) {
-        const int64_t tiles = ((N + bm - 1) / bm) * col_tiles;
+    auto cost = [&](int64_t bm, double rel, int bn = 128) {
+        const int64_t tiles = ((N + bm - 1) / bm) * ((M + bn - 1) / bn);
         return (double)((tiles + kComputeUnits - 1) / kComputeUnits) * rel;
     };
+    // 512 x 96 tiles where the padded table covers them and they fill the chip better in the same
+    // number of rounds: a quarter fewer matrix instructions per tile, but in a launch of one round
+    // the tile's time is mostly its loads and stores (measured at 4096 rows, 192 codebooks: 256
+    // tiles of 96 columns 0.0443 ms against 192 of 128 columns 0.0457 ms at M = 3072, 0.0378 against
+    // 0.0389 ms at M = 2304), hence the price of 0.9: never an extra round.
+    // LUTNN_SMFMAC_TILE_COLS = 96 | 128 pins the width of 512-row tiles.
+    constexpr double kNarrowRel = 0.9;
+    const bool narrow_fits = (int64_t)(M + 95) / 96 * 96 <= (int64_t)packed_cols(M);
+    const int pinned_cols = tunable(kTuneSmfmacTileCols);
     // LUTNN_SMFMAC_TILE_ROWS = 128 | 256 | 384 | 512 pins the height (tuning sweeps, and tests that
     // must reach every instance whatever the prices below say); anything else is ignored.
     switch (tunable(kTuneSmfmacTileRows)) {
-        case 512: return launch_tm<4>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
+        case 512:
+            if (pinned_cols == 96 && narrow_fits) return launch_tm<4, 3>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
+            return launch_tm<4>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
         case 384: return launch_tm<3>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
         case 256: return launch_tm<2>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
         case 128: return launch_tm<1>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
@@ -612,6 +664,8 @@ hipError_t launch_lookup_smfmac_i8(const int8_t* packed, const float* scale, con
     }
     const double c4 = cost(512, 1.0), c3 = cost(384, 0.8), c2 = cost(256, 0.56), c1 = cost(128, 0.42);
     const double best = std::min(std::min(c4, c3), std::min(c2, c1));
+    if (narrow_fits && pinned_cols != 128 && (cost(512, kNarrowRel, 96) < best || (pinned_cols == 96 && c4 == best)))
+        return launch_tm<4, 3>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
     if (c4 == best) return launch_tm<4>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
     if (c3 == best) return launch_tm<3>(packed, scale, bias, C, M, idx, N, Y, ldy, s);
     if (c2 == best) return launch_tm<2>(packed, scale, bias, C, M, idx, N, Y, ldy, s);

@@ -21,6 +21,7 @@ enum Tunable {
     kTuneSmfmacSplit,       // LUTNN_SMFMAC_SPLIT: 0 | 1
     kTuneSmfmacTileRows,    // LUTNN_SMFMAC_TILE_ROWS: 128 | 256 | 384 | 512
     kTuneSmfmacRowGroup,    // LUTNN_SMFMAC_ROW_GROUP: row tiles per group of the tile order, 0..64 (0 = plain)
+    kTuneSmfmacTileCols,    // LUTNN_SMFMAC_TILE_COLS: 96 | 128, width of the 512-row tiles
     kTuneCount
 };
 int tunable(int which);

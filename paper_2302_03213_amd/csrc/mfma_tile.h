@@ -177,29 +177,32 @@ __device__ __forceinline__ void mfma_lookup_tile(const uint4* __restrict__ packe
 // The bias values are fetched once, up front, and the stores of a tile that lies wholly inside
 // the matrix are issued without any test or wait in between (a wait on the load counter between
 // stores would wait for the stores before it as well: they share the counter).  For one (row
-// block, register) the four column tiles are written back to back: 4 x 128 contiguous bytes.
+// block, register) the TN column tiles are written back to back: TN x 128 contiguous bytes.
 // STREAM: Y is far larger than the caches (hundreds of megabytes): non-temporal stores keep it from
 // displacing the activations and indices the next launches read (config 5: the encoder of the next
 // step runs 4 % faster; the lookup itself is unchanged).
-template <int TM, bool BIAS, bool STREAM>
-__device__ __forceinline__ void mfma_store_tile_impl(const v16i (&acc)[TM][4], float s,
+template <int TM, bool BIAS, bool STREAM, int TN = 4>
+__device__ __forceinline__ void mfma_store_tile_impl(const v16i (&acc)[TM][TN], float s,
                                                      const float* __restrict__ bias, int M, int64_t N,
                                                      int64_t row_base, int col_base,
                                                      float* __restrict__ Y, int64_t ldy) {
     const int lane = threadIdx.x & 63;
     const int l32 = lane & 31, h = lane >> 5;
-    float bv[4] = {0.f, 0.f, 0.f, 0.f};
+    float bv[TN];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) bv[tn] = 0.f;
     if (BIAS) {
 #pragma unroll
-        for (int tn = 0; tn < 4; ++tn) {
+        for (int tn = 0; tn < TN; ++tn) {
             const int col = col_base + tn * 32 + l32;
             bv[tn] = col < M ? bias[col] : 0.f;
         }
-        // have the four values here, once, instead of a wait in front of every store
-        asm volatile("" : "+v"(bv[0]), "+v"(bv[1]), "+v"(bv[2]), "+v"(bv[3]));
+        // have the values here, once, instead of a wait in front of every store
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) asm volatile("" : "+v"(bv[tn]));
     }
     // wave-uniform: whole tile inside the matrix, and byte offsets within it fit 32 bits
-    const bool interior = row_base + TM * 32 <= N && col_base + 128 <= M && ldy < (1 << 22);
+    const bool interior = row_base + TM * 32 <= N && col_base + 32 * TN <= M && ldy < (1 << 22);
     if (interior) {
         // uniform base + 32-bit lane offset; rows advance the uniform part
         char* __restrict__ base = reinterpret_cast<char*>(Y + row_base * ldy + col_base);
@@ -210,7 +213,7 @@ __device__ __forceinline__ void mfma_store_tile_impl(const v16i (&acc)[TM][4], f
             for (int r = 0; r < 16; ++r) {
                 char* __restrict__ rowp = base + (int64_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * ldy * 4;
 #pragma unroll
-                for (int tn = 0; tn < 4; ++tn) {
+                for (int tn = 0; tn < TN; ++tn) {
                     const float a = (float)acc[i][tn][r];
                     const float y = BIAS ? __fmaf_rn(a, s, bv[tn]) : __fmul_rn(a, s);
                     if constexpr (STREAM)
@@ -230,7 +233,7 @@ __device__ __forceinline__ void mfma_store_tile_impl(const v16i (&acc)[TM][4], f
                 if (row_base + 4 * h + rr < N) {
                     float* __restrict__ q = p + (int64_t)rr * ldy;
 #pragma unroll
-                    for (int tn = 0; tn < 4; ++tn) {
+                    for (int tn = 0; tn < TN; ++tn) {
                         if (col_base + tn * 32 + l32 < M) {
                             const float a = (float)acc[i][tn][r];
                             q[tn * 32] = BIAS ? __fmaf_rn(a, s, bv[tn]) : __fmul_rn(a, s);
@@ -245,8 +248,8 @@ __device__ __forceinline__ void mfma_store_tile_impl(const v16i (&acc)[TM][4], f
 // The same tile added into an int32 image of Y (row stride ldy elements) with integer atomics:
 // the partial sums of workgroups that share an output tile but split the codebooks.  Integer
 // addition is associative, so the result does not depend on the order of arrival.
-template <int TM>
-__device__ __forceinline__ void mfma_atomic_add_tile(const v16i (&acc)[TM][4], int M, int64_t N,
+template <int TM, int TN = 4>
+__device__ __forceinline__ void mfma_atomic_add_tile(const v16i (&acc)[TM][TN], int M, int64_t N,
                                                      int64_t row_base, int col_base, int32_t* __restrict__ Yi,
                                                      int64_t ldy) {
     const int lane = threadIdx.x & 63;
@@ -260,22 +263,22 @@ __device__ __forceinline__ void mfma_atomic_add_tile(const v16i (&acc)[TM][4], i
             if (row_base + 4 * h + rr < N) {
                 int32_t* __restrict__ q = p + (int64_t)rr * ldy;
 #pragma unroll
-                for (int tn = 0; tn < 4; ++tn)
+                for (int tn = 0; tn < TN; ++tn)
                     if (col_base + tn * 32 + l32 < M) atomicAdd(q + tn * 32, acc[i][tn][r]);
             }
         }
     }
 }
 
-template <int TM, bool STREAM = false>
-__device__ __forceinline__ void mfma_store_tile(const v16i (&acc)[TM][4], float s,
+template <int TM, bool STREAM = false, int TN = 4>
+__device__ __forceinline__ void mfma_store_tile(const v16i (&acc)[TM][TN], float s,
                                                 const float* __restrict__ bias, int M, int64_t N,
                                                 int64_t row_base, int col_base, float* __restrict__ Y,
                                                 int64_t ldy) {
     if (bias)
-        mfma_store_tile_impl<TM, true, STREAM>(acc, s, bias, M, N, row_base, col_base, Y, ldy);
+        mfma_store_tile_impl<TM, true, STREAM, TN>(acc, s, bias, M, N, row_base, col_base, Y, ldy);
     else
-        mfma_store_tile_impl<TM, false, STREAM>(acc, s, bias, M, N, row_base, col_base, Y, ldy);
+        mfma_store_tile_impl<TM, false, STREAM, TN>(acc, s, bias, M, N, row_base, col_base, Y, ldy);
 }
 
 }  // namespace lutnn

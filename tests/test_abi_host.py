@@ -362,7 +362,8 @@ def test_tuning_switches(lut):
     for name, good, bad in (("LUTNN_FUSED_KERNEL", ("small", "tile"), "both"),
                             ("LUTNN_SMFMAC_SPLIT", ("0", "1"), "2"),
                             ("LUTNN_SMFMAC_TILE_ROWS", ("128", "256", "384", "512"), "200"),
-                            ("LUTNN_SMFMAC_ROW_GROUP", ("0", "8", "64"), "65")):
+                            ("LUTNN_SMFMAC_ROW_GROUP", ("0", "8", "64"), "65"),
+                            ("LUTNN_SMFMAC_TILE_COLS", ("96", "128"), "64")):
         for v in good:
             lut.set_tunable(name, v)
         with pytest.raises(lut.LutnnError) as e:

@@ -208,6 +208,35 @@ def test_lookup_smfmac_tile_orders(lut, pin, group, N, C, K, M, rows):
     assert np.array_equal(got, ref), "%d elements differ" % (got != ref).sum()
 
 
+@pytest.mark.parametrize("N,C,K,M,group", [(4700, 64, 16, 3072, -1), (2100, 96, 16, 3968, 0),
+                                           (9000, 128, 16, 1100, 3), (1500, 32, 7, 300, 0),
+                                           (4096, 192, 16, 3072, -1), (600, 32, 16, 4096, 0),
+                                           (513, 64, 16, 96, 0), (70, 32, 16, 97, 0)])
+def test_lookup_smfmac_tiles_of_96_columns(lut, pin, N, C, K, M, group):
+    """512 x 96 tiles (three column tiles per wavefront; table rows of 1.5 KiB copied as one and a
+    half loads): bit-exact against the oracle, with and without bias, into a strided Y whose guard
+    band must stay untouched - widths that are and are not multiples of 96, tiles streamed through a
+    workgroup and not, plain and grouped tile order.  M = 4096 has no room for a 43rd tile in the
+    table's padding and takes 128-column tiles whatever the switch says."""
+    pin("LUTNN_SMFMAC_TILE_ROWS", 512)
+    pin("LUTNN_SMFMAC_TILE_COLS", 96)
+    if group >= 0:
+        pin("LUTNN_SMFMAC_ROW_GROUP", group)
+    w = wl.make_layer("t", 1, C, K, 2, M, "i8", seed=N + C)
+    ol = OracleLayer(w)
+    ol.q = wl.random_table_i8(C, K, M, seed=C + M + 1)
+    ol.s = np.float32(0.017)
+    idx = wl.random_indices(N, C, K, seed=N + 11)
+    for with_bias in (True, False):
+        layer = device_layer_from_oracle(lut, ol, with_bias)
+        Ybig = torch.full((N, M + 8), 3.5, dtype=torch.float32, device="cuda")
+        lut.lookup(layer, dev(idx), "smfmac", out=Ybig[:, :M])
+        ref = ol.lookup(idx, bias="layer" if with_bias else None)
+        got = host(Ybig[:, :M])
+        assert np.array_equal(got, ref), "%d elements differ" % (got != ref).sum()
+        assert (host(Ybig[:, M:]) == 3.5).all()
+
+
 @pytest.mark.parametrize("N,C,K,M,rows", [(33, 1024, 16, 4096, 0), (100, 512, 16, 300, 0),
                                           (128, 544, 16, 1000, 0), (64, 576, 7, 130, 0),
                                           (1, 2048, 16, 256, 0), (77, 1536, 16, 768, 0),
