@@ -642,13 +642,13 @@ hipError_t launch_lookup_smfmac_i8(const int8_t* packed, const float* scale, con
         const int64_t tiles = ((N + bm - 1) / bm) * ((M + bn - 1) / bn);
         return (double)((tiles + kComputeUnits - 1) / kComputeUnits) * rel;
     };
-    // 512 x 96 tiles where the padded table covers them and they fill the chip better in the same
-    // number of rounds: a quarter fewer matrix instructions per tile, but in a launch of one round
-    // the tile's time is mostly its loads and stores (measured at 4096 rows, 192 codebooks: 256
-    // tiles of 96 columns 0.0443 ms against 192 of 128 columns 0.0457 ms at M = 3072, 0.0378 against
-    // 0.0389 ms at M = 2304), hence the price of 0.9: never an extra round.
+    // 512 x 96 tiles where the padded table covers them.  Same outputs and matrix instructions as
+    // a 384 x 128 tile, but a quarter less of the table to copy and to read per stage: priced 0.75
+    // (measured at 4096 rows, 384 codebooks: M = 2304 0.0342 ms against 0.0378 with 384-row and 0.0384
+    // with 512 x 128 tiles; M = 3072 0.0405 against 0.0423; at 8192 and 12288 rows of M = 3072 3-10 %
+    // ahead; at 16384 rows, where it needs a fourth round, 4 % behind - which the price reproduces).
     // LUTNN_SMFMAC_TILE_COLS = 96 | 128 pins the width of 512-row tiles.
-    constexpr double kNarrowRel = 0.9;
+    constexpr double kNarrowRel = 0.75;
     const bool narrow_fits = (int64_t)(M + 95) / 96 * 96 <= (int64_t)packed_cols(M);
     const int pinned_cols = tunable(kTuneSmfmacTileCols);
     // LUTNN_SMFMAC_TILE_ROWS = 128 | 256 | 384 | 512 pins the height (tuning sweeps, and tests that
