@@ -252,7 +252,21 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void lookup_smfmac_i8_kernel(
         uint32_t pos[TM][8];
     };
     auto read_ibuf = [&](IdxWords& wq, int i) {
-        const uint4 v = ibuf[w][i][lane];
+        // 384-row tiles: the address is formed here, from the lane's byte offset, every time.  Held
+        // in a register of its own across the stage loop it is one live value too many for that
+        // instance, and the allocator's way out was a reload from scratch memory inside the loop,
+        // whose wait (the vector-memory counter at zero) also waits for every table load in flight.
+        // (The other instances keep the plain form: their loops come out shorter with it.)
+        uint4 v;
+        if constexpr (TM == 3) {
+            uint32_t lane_bytes = lane16;
+            asm volatile("" : "+v"(lane_bytes));
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            const u32x4 t = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(ibuf_w + i * 1024 + lane_bytes);
+            v = uint4{t[0], t[1], t[2], t[3]};
+        } else {
+            v = ibuf[w][i][lane];
+        }
         wq.sh[i][0] = v.x;
         wq.sh[i][1] = v.y;
         wq.sh[i][2] = v.z;
