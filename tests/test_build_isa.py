@@ -72,6 +72,11 @@ def test_stage_loop_has_no_spills_and_fits_the_machine(isa, name):
     for b, ins in loops.items():
         spills = [x for x in ins if x.startswith(("scratch_", "buffer_store", "buffer_load_dword "))]
         assert not spills, "%s: %d scratch accesses in block %s" % (name, len(spills), b)
+        # the loop's own waits leave the loads of the current stage in flight (six or more); a
+        # wait for fewer would be the compiler's, for a load of its own, and would drain the ring
+        for x in ins:
+            m = re.match(r"s_waitcnt.*vmcnt\((\d+)\)", x)
+            assert not m or int(m.group(1)) >= 6, "%s: '%s' in block %s" % (name, x, b)
 
 
 def test_steady_state_loop_of_the_benchmark_instance_keeps_its_instruction_budget(isa):
