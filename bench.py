@@ -85,6 +85,13 @@ def kernel_roofline(cost, workload, w, kind, ms):
                      "(the one-hot operand is 15/16 zeros); hbm_frac = idx + Y + table once against 8 TB/s; "
                      "lds_bound_ratio = (N*C*M table bytes through LDS at 78.6 TB/s) / kernel time, above 1 "
                      "because the matrix cores replace the gather"}
+        if kind == "smfmac":
+            floor = insts / cost.SIMDS * cost.SMFMAC_I8_STREAM_SECONDS_RANDOM_OPERANDS
+            r["stream_floor_ms"] = round(floor * 1e3, 4)
+            r["frac_of_stream_floor"] = round(floor / sec, 4)
+            r["stream_floor_source"] = ("a loop of this matrix instruction alone on random INT8 operands, "
+                                        "19.0 ns per instruction and SIMD at the 1.66-1.72 GHz the chip then "
+                                        "holds (a microbenchmark of its own, not this run)")
         return r
     if kind == "wide":  # 16-bit indices: every selected table row is read from global memory
         # distinct table rows N*C uniformly drawn (row, codebook) pairs select, in expectation

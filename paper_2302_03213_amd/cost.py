@@ -80,6 +80,15 @@ def lookup_mfma_ops(N, C, M, kpad=16):
     return 2 * N * C * kpad * M
 
 
+# Measured, not published: a loop of nothing but v_smfmac_i32_32x32x64_i8 (16 independent accumulators,
+# one wave per SIMD, every SIMD of the chip busy) on full-range random INT8 B operands and random
+# one-hot A operands issues one instruction per SIMD every 19.0 ns (32.8 cycles at the 1.66-1.72 GHz
+# the chip holds under that load; 13.8-15 ns on constant operands).  The floor of the one-hot
+# contraction on such data, whatever feeds the pipes.
+SMFMAC_I8_STREAM_SECONDS_RANDOM_OPERANDS = 19.0e-9
+SIMDS = 1024
+
+
 def lookup_matrix_instructions(N, C, M, sparse, kpad=16):
     """32x32 int8 matrix instructions of the one-hot contraction OneHot[N x C*kpad] x T[C*kpad x M]: a
     dense instruction covers 32 of the contraction's C*kpad positions (two codebooks at kpad = 16), a
