@@ -502,6 +502,33 @@ def cpu_baseline(b, args):
     return cpu
 
 
+def stream_probe(torch, lut):
+    """ns per v_smfmac_i32_32x32x64_i8 and SIMD in a loop of nothing else (lutnn_probe_smfmac_stream), by
+    operand data; the random-INT8 figure is cost.SMFMAC_I8_STREAM_SECONDS_RANDOM_OPERANDS."""
+    from paper_2302_03213_amd import cost
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.empty(256 * cus, dtype=torch.int32, device="cuda")
+    iters, out = 40000, {}
+    for name, operands in (("constant", 0), ("random_int8", 1), ("random_3bit", 2)):
+        for _ in range(3):  # settle the clock on this kind of data
+            lut.probe_smfmac_stream(operands, iters, sink)
+        torch.cuda.synchronize()
+        times = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            lut.probe_smfmac_stream(operands, iters, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1) * 1e6 / (iters * 16.0))
+        times.sort()
+        out[name] = {"ns_per_instruction_median": round(times[2], 2), "ns_per_instruction_min": round(times[0], 2),
+                     "clock_GHz_if_32.8_cycles": round(32.8 / times[2], 2)}
+    print(json.dumps({"probe": "smfmac_stream", "compute_units": cus, "instructions_per_wave": iters * 16,
+                      "operands": out,
+                      "constant_in_cost_py_ns": cost.SMFMAC_I8_STREAM_SECONDS_RANDOM_OPERANDS * 1e9}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -533,6 +560,10 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 256 MiB device-to-device copy (untimed): the known-size kernel "
                          "against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
+    ap.add_argument("--stream-probe", action="store_true",
+                    help="instead of the benchmark: time a stream of the lookup's matrix instruction alone "
+                         "on constant, random INT8 and random 3-bit operands (the floor the roofline record "
+                         "quotes as stream_floor_ms) and print one JSON line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the operator shards by rows with no "
@@ -543,6 +574,9 @@ def main():
     import torch
 
     import paper_2302_03213_amd as lut  # noqa: F401  (fails loudly if the HIP library is missing)
+    if args.stream_probe:
+        stream_probe(torch, lut)
+        return
     from paper_2302_03213_amd import cost
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"

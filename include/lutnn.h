@@ -420,6 +420,21 @@ LUTNN_API const char* lutnn_last_error(void);
 LUTNN_API lutnn_status lutnn_set_tunable(const char* name, const char* value);
 
 /*
+ * Measurement aid, not part of the operator: enqueues a stream of nothing but the 2:4-sparse INT8
+ * matrix instruction that the one-hot form of Eq. 4 runs on - one workgroup of four waves per compute
+ * unit, 16 * iterations instructions per wave - so that a caller timing it with events learns how fast
+ * the matrix pipes go on a kind of operand data (the clock the chip holds depends on it): the floor of
+ * the lookup on such data, quoted by the benchmark beside the nominal peak.
+ *   operands   0 = the same constants in every instruction; 1 = full-range random INT8 table
+ *              values and random one-hot slices, as the lookup feeds them; 2 = as 1, 3-bit values
+ *   sink       device, at least 256 ints per compute unit (1 KiB each); written once, content
+ *              meaningless (it keeps the instructions alive)
+ * Errors: E_NULL, E_SHAPE (operands, iterations outside 0 .. 2^24, sink too small), E_ALIGN, E_HIP.
+ */
+LUTNN_API lutnn_status lutnn_probe_smfmac_stream(int32_t operands, int32_t iterations, int32_t* sink,
+                                                 size_t sink_bytes, void* stream);
+
+/*
  * Host: library version, "major.minor.patch+<source hash>": the hash (12 hex digits) identifies the
  * sources the library was compiled from, so that a loader can tell a stale binary.
  */

@@ -32,7 +32,8 @@ EXPORTS = ["lutnn_softpq_backward_static", "lutnn_set_tunable", "lutnn_encode_tr
            "lutnn_lookup", "lutnn_linear", "lutnn_encode_tree", "lutnn_linear_tree",
            "lutnn_softpq_backward", "lutnn_softpq_workspace_bytes",
            "lutnn_encode_tree_conv2d", "lutnn_conv2d_tree", "lutnn_conv2d_rows", "lutnn_encode_conv2d", "lutnn_conv2d",
-           "lutnn_auto_variant", "lutnn_linear_auto_variant", "lutnn_status_string", "lutnn_last_error", "lutnn_version"]
+           "lutnn_auto_variant", "lutnn_linear_auto_variant", "lutnn_status_string", "lutnn_last_error", "lutnn_version",
+           "lutnn_probe_smfmac_stream"]
 
 
 class LutnnError(RuntimeError):
@@ -131,6 +132,8 @@ def _load():
     lib.lutnn_version.restype = ctypes.c_char_p
     lib.lutnn_set_tunable.restype = i32
     lib.lutnn_set_tunable.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
+    lib.lutnn_probe_smfmac_stream.restype = i32
+    lib.lutnn_probe_smfmac_stream.argtypes = [i32, i32, vp, ctypes.c_size_t, vp]
     return lib
 
 
@@ -158,6 +161,13 @@ def _variant(v):
 def set_tunable(name, value=None):
     """lutnn_set_tunable: pin ("small", "1", "256", ...) or release (None) a launcher's choice."""
     _check(LIB.lutnn_set_tunable(name.encode(), None if value is None else str(value).encode()))
+
+
+def probe_smfmac_stream(operands, iterations, sink):
+    """lutnn_probe_smfmac_stream: 16 * iterations matrix instructions per wave on every SIMD; `sink` is an
+    int32 device tensor of at least 256 elements per compute unit."""
+    assert sink.is_cuda and sink.dtype == torch.int32 and sink.is_contiguous()
+    _check(LIB.lutnn_probe_smfmac_stream(operands, iterations, _ptr(sink), sink.numel() * 4, _stream()))
 
 
 class tunables:

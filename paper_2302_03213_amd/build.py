@@ -19,7 +19,7 @@ OBJDIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "liblutnn.so")
 
 SOURCES = ["api.hip", "encode.hip", "encode_tree.hip", "build_table.hip", "lookup_lds.hip", "lookup_rows.hip", "lookup_mfma.hip", "lookup_smfmac.hip", "lookup_wide.hip",
-           "linear_fused.hip", "linear_small.hip", "softpq_backward.hip"]
+           "linear_fused.hip", "linear_small.hip", "softpq_backward.hip", "probe_smfmac.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 

@@ -275,6 +275,20 @@ lutnn_status lutnn_set_tunable(const char* name, const char* value) {
     return fail(LUTNN_E_UNSUPPORTED, "no tuning switch named '%s'", name);
 }
 
+lutnn_status lutnn_probe_smfmac_stream(int32_t operands, int32_t iterations, int32_t* sink, size_t sink_bytes,
+                                       void* stream) {
+    if (!sink) return fail(LUTNN_E_NULL, "sink is NULL");
+    if (operands < 0 || operands > 2) return fail(LUTNN_E_SHAPE, "operands must be 0, 1 or 2 (got %d)", operands);
+    if (iterations < 0 || iterations > (1 << 24))
+        return fail(LUTNN_E_SHAPE, "iterations must be 0 .. 2^24 (got %d)", iterations);
+    if (sink_bytes < (size_t)lutnn::compute_units() * 256 * sizeof(int32_t))
+        return fail(LUTNN_E_SHAPE, "sink holds %zu bytes, the probe writes %zu", sink_bytes,
+                    (size_t)lutnn::compute_units() * 256 * sizeof(int32_t));
+    if (!aligned(sink, 4)) return fail(LUTNN_E_ALIGN, "sink must be 4-byte aligned");
+    return hip_result(lutnn::launch_probe_smfmac_stream(operands, iterations, sink, static_cast<hipStream_t>(stream)),
+                      "lutnn_probe_smfmac_stream");
+}
+
 size_t lutnn_table_bytes(int32_t C, int32_t K, int32_t M, int32_t dtype) {
     if (C <= 0 || K <= 0 || M <= 0) return 0;
     const size_t n = (size_t)C * (size_t)K * (size_t)M;

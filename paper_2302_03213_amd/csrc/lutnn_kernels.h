@@ -142,4 +142,7 @@ hipError_t launch_linear_small_tree_i8(const int32_t* split_dim, const float* th
                                        int M, const float* X, int64_t N, int64_t ldx, float* Y, int64_t ldy,
                                        hipStream_t s);
 
+// probe_smfmac.hip: sink holds 256 * compute_units() ints
+hipError_t launch_probe_smfmac_stream(int operands, int iterations, int32_t* sink, hipStream_t s);
+
 }  // namespace lutnn

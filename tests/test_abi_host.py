@@ -461,3 +461,14 @@ def test_bench_refuses_more_than_one_gpu():
     env = dict(os.environ, WORLD_SIZE="4")
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True, env=env)
     assert r.returncode == 2 and "ONE GPU" in r.stderr
+
+
+def test_stream_probe_validates_on_the_host(lut):
+    L = lut.LIB
+    assert L.lutnn_probe_smfmac_stream(1, 10, None, 1 << 20, None) == 1  # E_NULL
+    fake = ctypes.c_void_p(0x1000)
+    for operands, iterations, nbytes in ((3, 10, 1 << 20), (-1, 10, 1 << 20), (1, -1, 1 << 20),
+                                         (1, (1 << 24) + 1, 1 << 20), (1, 10, 16)):
+        code = L.lutnn_probe_smfmac_stream(operands, iterations, fake, nbytes, None)
+        name, detail = _status(lut, code)
+        assert name == "LUTNN_E_SHAPE", (operands, iterations, nbytes, name, detail)

@@ -298,3 +298,23 @@ def test_two_host_threads_on_two_streams(lut):
     assert not errors, errors
     for i in range(2):
         np.testing.assert_array_equal(results[i], cases[i][2])
+
+
+def test_stream_probe_runs_and_fills_its_sink(lut):
+    """lutnn_probe_smfmac_stream is a measurement aid; what can be checked is that it runs to the end
+    on every kind of operand and writes the whole sink (constant operands: every matrix instruction adds
+    the same products, so the sums it leaves grow with the iteration count)."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.full((256 * cus,), -1, dtype=torch.int32, device="cuda")
+    sums = []
+    for iterations in (1, 3):
+        lut.probe_smfmac_stream(0, iterations, sink)
+        torch.cuda.synchronize()
+        sums.append(sink.to(torch.int64).sum().item())
+    assert sums[0] != -256 * cus and sums[1] == 3 * sums[0]
+    for operands in (1, 2):
+        sink.fill_(-1)
+        lut.probe_smfmac_stream(operands, 50, sink)
+        torch.cuda.synchronize()
+    with pytest.raises(lut.LutnnError):
+        lut.probe_smfmac_stream(1, 10, sink[:100])
