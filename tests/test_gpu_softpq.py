@@ -248,3 +248,24 @@ def test_autograd_conv2d_module_matches_oracle_on_unfolded_rows(lut):
     w.X = X
     check_dt(mod.temperature.grad.item(), dt_ref, dt_magnitude(w, t, G2))
     np.testing.assert_allclose(host(mod.bias.grad), G2.sum(axis=0), rtol=1e-4, atol=1e-5)
+
+
+def draw_softpq_shape(seed):
+    rng = np.random.default_rng(3000 + seed)
+    K = int(rng.choice([16, 16, 8]))
+    V = int(rng.choice([1, 2, 3, 4, 4, 8, 9, 16, 32]))
+    C = int(rng.integers(1, 90))
+    N = int(np.exp(rng.uniform(0.0, np.log(5000.0))))
+    M = int(rng.integers(1, 40))
+    # temperatures from sharp to flat relative to the typical squared distance (about 2 V)
+    t = float(np.exp(rng.uniform(np.log(0.15 * V), np.log(8.0 * V))))
+    while N * C * K * max(V, M) > 6e7:
+        N = max(1, N // 2)
+    return N, C, K, V, M, t
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_softpq_backward_on_a_random_shape(lut, seed):
+    N, C, K, V, M, t = draw_softpq_shape(seed)
+    print("seed %d: N=%d C=%d K=%d V=%d M=%d t=%.3f" % (seed, N, C, K, V, M, t), file=sys.stderr, flush=True)
+    run_case(lut, N, C, K, V, M, t, seed=900 + seed, strided=bool(seed & 1))
