@@ -297,7 +297,6 @@ __global__ __launch_bounds__(kThreads) void lookup_gather_kernel(
     int K, int M, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y, int64_t ldy,
     int col_chunks, int lpr) {
     constexpr bool I8 = sizeof(TT) == 1;
-    typedef typename std::conditional<I8, uint32_t, float4>::type Vec;  // four columns
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t gw = (int64_t)blockIdx.x * kWaves + w;
