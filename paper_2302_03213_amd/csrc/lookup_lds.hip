@@ -296,7 +296,6 @@ __global__ __launch_bounds__(kThreads) void lookup_gather_kernel(
     const TT* __restrict__ T, const float* __restrict__ scale, const float* __restrict__ bias, int C,
     int K, int M, const uint8_t* __restrict__ idx, int64_t N, float* __restrict__ Y, int64_t ldy,
     int col_chunks, int lpr) {
-    constexpr bool I8 = sizeof(TT) == 1;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t gw = (int64_t)blockIdx.x * kWaves + w;
